@@ -1,0 +1,48 @@
+import os
+import sys
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Data-only gains of the synthetic weights (see thia_synth.weights): literal He-normal
+# weights without normalisation layers give degenerate (empty) proposals.
+RES_GAIN = 0.25
+PRED_STD = 0.01
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs an MI355X (runs through the C-ABI library)")
+
+
+_blob_cache = {}
+
+
+def get_blob(spec, seed):
+    """Weights blob for a ModelSpec; cached in memory and under /tmp (generation takes seconds)."""
+    from thia_synth import make_blob
+    import hashlib
+    key = hashlib.sha1(spec.header() + seed.to_bytes(8, "little") + repr((RES_GAIN, PRED_STD)).encode()).hexdigest()[:16]
+    if key in _blob_cache:
+        return _blob_cache[key]
+    path = f"/tmp/thia_blob_{key}.npy"
+    if os.path.exists(path):
+        blob = np.load(path)
+    else:
+        blob = make_blob(spec, seed, res_gain=RES_GAIN, pred_std=PRED_STD)
+        tmp = path + f".{os.getpid()}.npy"
+        np.save(tmp, blob)
+        os.replace(tmp, path)
+    _blob_cache[key] = blob
+    return blob
+
+
+@pytest.fixture(scope="session")
+def tiny():
+    """Config 1 (tiny single-exit fp32 detector): (config, blob, frames)."""
+    from thia_synth import CONFIGS, make_frames
+    cfg = CONFIGS[1]
+    return cfg, get_blob(cfg.model, cfg.weight_seed), make_frames(cfg.scene, cfg.frame_seed)
