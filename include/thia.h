@@ -1,0 +1,208 @@
+/*
+ * thia.h - C ABI of the MI355X (gfx950) execution engine for a multi-exit two-stage
+ * object detector run over chunks of video frames.
+ *
+ * The method (THIA, arXiv 2102.08481): ONE resident detector (backbone -> region
+ * proposal network -> region-of-interest head, Sec. 2.1) carries several exit
+ * points (EPs): extra RPN + ROI units attached to earlier backbone stages (Sec. 4.1,
+ * Sec. 4.2, Table 4, Fig. "EI in Faster-RCNN").  A query plan is a list of chunks
+ * (contiguous frame segments, Sec. 2.2), each assigned an EP or "skip" (Sec. 3,
+ * execution engine; Algorithm 1 emits {chunk : EP} pairs).  The engine runs every
+ * frame of a chunk through the backbone truncated at the chunk's EP and then through
+ * that EP's RPN, proposal decoding, NMS, ROIAlign and box head, and returns per frame
+ * the detected objects: category, box, confidence (Sec. 2.1).
+ *
+ * Conventions common to all calls
+ *  - "dev" pointers are device memory on the current HIP device, "host" pointers are
+ *    ordinary host memory.  The caller owns every buffer it passes in; the library owns
+ *    the weights and its workspace inside thia_model.
+ *  - Calls enqueue work on the model's stream (thia_set_stream; default: the null
+ *    stream) and return without waiting, unless stated otherwise.  The caller
+ *    synchronises before reading outputs.
+ *  - Return value: THIA_OK (0) or a negative THIA_E_* code; thia_last_error() gives a
+ *    message.  On an argument error nothing is enqueued and outputs are untouched.
+ *  - Exits are numbered 1..n_exits (exit k reads the output of backbone stage
+ *    conv(k+1)_x, stride 4 * 2^(k-1)); 0 means "skip the chunk".
+ *  - Detections: at most D = thia_info.max_det per frame, sorted by descending score.
+ *    out_boxes [n,D,4] = (x1,y1,x2,y2) in pixels, out_scores [n,D], out_labels [n,D]
+ *    = foreground class 1..n_classes-1.  Unused slots: box 0, score 0, label -1.
+ *  - A model must not be used from two threads at once; two calls on the same model
+ *    share its workspace and are ordered by the stream.
+ */
+#ifndef THIA_H
+#define THIA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct thia_model thia_model;
+
+enum {
+    THIA_OK = 0,
+    THIA_E_BADARG = -1, /* null pointer, negative size                               */
+    THIA_E_BADEP = -2,  /* exit outside 0..n_exits                                   */
+    THIA_E_SHAPE = -3,  /* frame size or channel count the kernels do not support    */
+    THIA_E_BLOB = -4,   /* malformed weights blob / n_exits mismatch                 */
+    THIA_E_NOMEM = -5,  /* device or host allocation failed                          */
+    THIA_E_HIP = -6     /* a HIP runtime call failed                                 */
+};
+
+typedef struct thia_info {
+    int32_t precision;  /* 0: fp32 tensors; 1: bf16 weights/activations, fp32 accumulate */
+    int32_t n_exits;
+    int32_t blocks[4];  /* bottleneck blocks of conv2_x..conv5_x                     */
+    int32_t head_ch;    /* channels of the map the RPN and ROIAlign read             */
+    int32_t n_anchors;  /* anchors per location                                      */
+    int32_t pre_nms, post_nms;
+    int32_t pool;       /* ROIAlign output side (7)                                  */
+    int32_t fc_dim;
+    int32_t n_classes;  /* including background (class 0)                            */
+    int32_t max_det;    /* D                                                         */
+    int32_t microbatch; /* frames processed together (0 = chosen per frame size)     */
+    int32_t has_lateral;
+} thia_info;
+
+/*
+ * Load the single multi-exit model (Sec. 4.1: one model, no model switching).
+ * weights: host, nbytes bytes: 256-byte little-endian header (hyper-parameters) then
+ * fp32 tensors, conv weights [Cout,Cin,kh,kw], FC weights [out,in] with FC1's input
+ * index = c*pool*pool + ph*pool + pw, each weight followed by its bias; order: stem,
+ * stages, then per exit lateral (optional), rpn.conv, rpn.obj, rpn.delta, fc1, fc2,
+ * cls, box.  n_exits must equal the header's.  The blob may be freed after the call.
+ * Blocking (allocates and uploads).  All channel counts except the 3 input channels
+ * and the predictor outputs must be multiples of 64.
+ */
+int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model** out);
+
+/* Waits for the model's stream, then frees weights and workspace. NULL is allowed. */
+void thia_free_model(thia_model* m);
+
+/* hip_stream: a hipStream_t (e.g. torch.cuda.current_stream().cuda_stream); NULL = null stream. */
+int thia_set_stream(thia_model* m, void* hip_stream);
+
+/* Frames processed together inside a call (workspace grows with it); 0 restores the
+ * default.  Results never depend on it: every frame is computed independently. */
+int thia_set_microbatch(thia_model* m, int frames);
+
+int thia_get_info(const thia_model* m, thia_info* out);
+
+/*
+ * Run one chunk at one exit (Sec. 3: the engine executes a chunk at the exit the plan
+ * chose; Sec. 4.1: inference is short-circuited there, later stages are not run).
+ * frames: dev, uint8 [n,3,H,W] (planar RGB), n >= 0.  ep: 1..n_exits, or 0 = skip
+ * (outputs are filled with the empty pattern).  Outputs: dev, see above.
+ * H, W >= 32.  May (re)allocate workspace when (H, W, microbatch) changes; that
+ * first call then blocks.
+ */
+int thia_detect_chunk(thia_model* m, const uint8_t* frames, int n, int H, int W, int ep,
+                      float* out_boxes, float* out_scores, int32_t* out_labels);
+
+/*
+ * Run a fine-grained plan (Sec. 3; Algorithm 1's output): frames dev uint8
+ * [n_chunks*chunk_len,3,H,W]; chunk c = frames [c*chunk_len, (c+1)*chunk_len) runs at
+ * exit chunk_ep[c] (host int32 [n_chunks], 0 = skip).  Chunks are grouped by exit and
+ * enqueued group by group on the one stream; outputs are written at the frames' own
+ * positions, so out_* are laid out exactly as for n_chunks*chunk_len frames of
+ * thia_detect_chunk, and each chunk's slice is bit-identical to a stand-alone call.
+ */
+int thia_run_plan(thia_model* m, const uint8_t* frames, int n_chunks, int chunk_len, int H, int W,
+                  const int32_t* chunk_ep, float* out_boxes, float* out_scores, int32_t* out_labels);
+
+const char* thia_last_error(const thia_model* m);
+
+/* ---------------------------------------------------------------- inspection
+ * Intermediates of the most recent thia_detect_chunk (needed to check the tolerances
+ * on RPN logits / box deltas, and to feed single steps).  Recording is off by
+ * default; thia_set_debug(m, 1) turns it on for later calls (costs copies + memory).
+ * thia_debug_tap waits for the stream and copies tap `which` to dst (host).
+ * Layouts (n = frames of the call, T = float or bf16 bits (uint16) per precision):
+ */
+enum {
+    THIA_TAP_FEAT = 0,        /* T   [n,Hk,Wk,Ck]       exit stage output, NHWC          */
+    THIA_TAP_HEAD_FEAT = 1,   /* T   [n,Hk,Wk,Ch]       lateral output, NHWC             */
+    THIA_TAP_RPN_LOGITS = 2,  /* f32 [n,Hk*Wk*A]        index (y*Wk+x)*A + a             */
+    THIA_TAP_RPN_DELTAS = 3,  /* f32 [n,Hk*Wk*A,4]                                       */
+    THIA_TAP_TOPK_IDX = 4,    /* i32 [n,pre]            anchor indices, best first, -1 pad */
+    THIA_TAP_PROP_BOXES = 5,  /* f32 [n,pre,4]          decoded, clipped, empties dropped */
+    THIA_TAP_PROP_N = 6,      /* i32 [n]                                                 */
+    THIA_TAP_ROIS = 7,        /* f32 [n,post,4]         zero padded                      */
+    THIA_TAP_ROI_N = 8,       /* i32 [n]                                                 */
+    THIA_TAP_ROI_FEAT = 9,    /* T   [n,post,P*P,Ch]    index (ph*P+pw)*Ch + c           */
+    THIA_TAP_CLS_LOGITS = 10, /* f32 [n,post,Kc]                                         */
+    THIA_TAP_BOX_DELTAS = 11, /* f32 [n,post,4*Kc]                                       */
+    THIA_TAP_CAND_SCORES = 12,/* f32 [n,post,Kc]                                         */
+    THIA_TAP_CAND_BOXES = 13, /* f32 [n,post,Kc,4]                                       */
+    THIA_TAP_DET_N = 14,      /* i32 [n]                                                 */
+    THIA_TAP_COUNT = 15
+};
+int thia_set_debug(thia_model* m, int enable);
+int thia_debug_tap(thia_model* m, int which, void* dst, size_t nbytes);
+/* Bytes tap `which` holds for the most recent call (0 if nothing recorded). */
+size_t thia_debug_tap_bytes(const thia_model* m, int which);
+
+/* ---------------------------------------------------------------- timing
+ * Per-kernel-class device time, measured with HIP events recorded on the model's
+ * stream around every launch while profiling is on.  thia_profile_read waits for the
+ * stream, sums the elapsed times since thia_profile_begin and fills ms[THIA_K_COUNT]
+ * and launches[THIA_K_COUNT] (host).  Profiling adds two event records per launch.
+ */
+enum {
+    THIA_K_STEM = 0, THIA_K_POOL = 1, THIA_K_CONV = 2 /* backbone+lateral+RPN implicit GEMMs */,
+    THIA_K_FC = 3, THIA_K_TOPK = 4, THIA_K_NMS = 5, THIA_K_ROIALIGN = 6, THIA_K_POST = 7, THIA_K_COUNT = 8
+};
+int thia_profile_begin(thia_model* m);
+int thia_profile_read(thia_model* m, float* ms, int32_t* launches);
+int thia_profile_end(thia_model* m);
+
+/* ---------------------------------------------------------------- single steps
+ * The kernels of the path, callable on caller-provided device tensors, so that each
+ * step can be checked against its definition with identical inputs (the orderings and
+ * NMS keeps are then exactly determined).  They use the model's hyper-parameters,
+ * stream and workspace; all pointers dev unless noted.
+ */
+
+/* Step "top-k + decode" of exit ep on an Hk x Wk map of an H x W frame: per frame the
+ * k = min(pre_nms, Hk*Wk*A) best logits by (logit desc, index asc), -0 == +0; their
+ * anchors are decoded with the deltas, clipped to the frame, and empty boxes
+ * (< 1e-3 px) dropped keeping order.  logits [n,Hk*Wk*A], deltas [n,Hk*Wk*A,4];
+ * out_idx [n,pre] (-1 padded), out_boxes [n,pre,4] (zero padded), out_n [n]. */
+int thia_op_rpn_proposals(thia_model* m, const float* logits, const float* deltas, int n, int H, int W, int ep,
+                          int32_t* out_idx, float* out_boxes, int32_t* out_n);
+
+/* Greedy NMS of boxes already in priority order: box i is kept iff no kept j < i has
+ * IoU(i,j) > thr (inter > thr * union, fp32, no fused multiply-add); at most max_keep
+ * kept.  boxes [n,cap,4], counts [n] (<= cap <= 4096); out_keep [n,max_keep] positions
+ * (-1 padded), out_n [n]. */
+int thia_op_nms(thia_model* m, const float* boxes, const int32_t* counts, int n, int cap, float thr, int max_keep,
+                int32_t* out_keep, int32_t* out_n);
+
+/* ROIAlign (P x P bins, 2 x 2 samples, texel centres at j + 0.5) of rois [n,post,4]
+ * (pixels) on feat T [n,Hk,Wk,Ch] with the given stride; out T [n,post,P*P,Ch]. */
+int thia_op_roialign(thia_model* m, const void* feat, const float* rois, int n, int Hk, int Wk, int stride, void* out);
+
+/* Detection selection: scores [n,post,Kc], boxes [n,post,Kc,4], roi_n [n]: candidates
+ * (roi < roi_n, class >= 1, score > score_thr, box non-empty) ordered by (score desc,
+ * roi*Kc + class asc), greedy same-class NMS at det_nms_thr, first D.  Outputs as for
+ * thia_detect_chunk, plus out_n [n] (may be NULL). */
+int thia_op_select_detections(thia_model* m, const float* scores, const float* boxes, const int32_t* roi_n, int n,
+                              float* out_boxes, float* out_scores, int32_t* out_labels, int32_t* out_n);
+
+/* One convolution layer of the path on caller tensors: in T [n,H,W,Cin] NHWC, weights
+ * host fp32 [Cout,Cin,k,k] (converted and uploaded by the call, which therefore
+ * blocks), bias host fp32 [Cout], optional residual T [n,Ho,Wo,Cout], out T or (if
+ * out_f32) float [n,Ho,Wo,Cout].  Cin must be a multiple of 64. */
+int thia_op_conv(thia_model* m, const void* in, int n, int H, int W, int Cin, const float* weights, const float* bias,
+                 int Cout, int k, int stride, int pad, const void* residual, int relu, int out_f32, void* out);
+
+/* Stem of the backbone on frames dev uint8 [n,3,H,W]: normalise, 7x7/2 conv + ReLU,
+ * 3x3/2 max-pool; out T [n,Hp,Wp,stem_ch] NHWC. */
+int thia_op_stem(thia_model* m, const uint8_t* frames, int n, int H, int W, void* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* THIA_H */

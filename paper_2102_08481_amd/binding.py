@@ -1,0 +1,252 @@
+"""Thin Python binding of libthia.so (include/thia.h): argument marshalling only.
+
+Device buffers are torch tensors on the current HIP device; every step of the
+detector runs inside the library's kernels.  If the shared library is missing or a
+symbol cannot be resolved this module raises: there is no fallback path.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libthia.so")
+
+THIA_OK = 0
+ERRORS = {-1: "THIA_E_BADARG", -2: "THIA_E_BADEP", -3: "THIA_E_SHAPE", -4: "THIA_E_BLOB", -5: "THIA_E_NOMEM", -6: "THIA_E_HIP"}
+
+TAPS = {"feat": 0, "head_feat": 1, "rpn_logits": 2, "rpn_deltas": 3, "topk_idx": 4, "prop_boxes": 5, "prop_n": 6,
+        "rois": 7, "roi_n": 8, "roi_feat": 9, "cls_logits": 10, "box_deltas": 11, "cand_scores": 12, "cand_boxes": 13,
+        "det_n": 14}
+_TAP_ELEM = {"feat": "T", "head_feat": "T", "roi_feat": "T", "topk_idx": "i", "prop_n": "i", "roi_n": "i", "det_n": "i"}
+KERNEL_CLASSES = ["stem", "pool", "conv", "fc", "topk", "nms", "roialign", "post"]
+
+EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_microbatch", "thia_get_info",
+           "thia_detect_chunk", "thia_run_plan", "thia_last_error", "thia_set_debug", "thia_debug_tap",
+           "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
+           "thia_op_rpn_proposals", "thia_op_nms", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
+           "thia_op_stem"]
+
+
+class ThiaInfo(C.Structure):
+    _fields_ = [("precision", C.c_int32), ("n_exits", C.c_int32), ("blocks", C.c_int32 * 4), ("head_ch", C.c_int32),
+                ("n_anchors", C.c_int32), ("pre_nms", C.c_int32), ("post_nms", C.c_int32), ("pool", C.c_int32),
+                ("fc_dim", C.c_int32), ("n_classes", C.c_int32), ("max_det", C.c_int32), ("microbatch", C.c_int32),
+                ("has_lateral", C.c_int32)]
+
+
+class ThiaError(RuntimeError):
+    def __init__(self, code, msg=""):
+        super().__init__(f"{ERRORS.get(code, code)}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load libthia.so (raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
+    L.thia_load_model.argtypes = [vp, sz, i32, C.POINTER(vp)]
+    L.thia_free_model.argtypes = [vp]
+    L.thia_free_model.restype = None
+    L.thia_set_stream.argtypes = [vp, vp]
+    L.thia_set_microbatch.argtypes = [vp, i32]
+    L.thia_get_info.argtypes = [vp, C.POINTER(ThiaInfo)]
+    L.thia_detect_chunk.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
+    L.thia_run_plan.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
+    L.thia_last_error.argtypes = [vp]
+    L.thia_last_error.restype = C.c_char_p
+    L.thia_set_debug.argtypes = [vp, i32]
+    L.thia_debug_tap.argtypes = [vp, i32, vp, sz]
+    L.thia_debug_tap_bytes.argtypes = [vp, i32]
+    L.thia_debug_tap_bytes.restype = sz
+    L.thia_profile_begin.argtypes = [vp]
+    L.thia_profile_read.argtypes = [vp, vp, vp]
+    L.thia_profile_end.argtypes = [vp]
+    L.thia_op_rpn_proposals.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
+    L.thia_op_nms.argtypes = [vp, vp, vp, i32, i32, C.c_float, i32, vp, vp]
+    L.thia_op_roialign.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
+    L.thia_op_select_detections.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    L.thia_op_conv.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i32, i32, i32, vp, i32, i32, vp]
+    L.thia_op_stem.argtypes = [vp, vp, i32, i32, i32, vp]
+    for name in EXPORTS:
+        getattr(L, name)
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _dev(t, dtype):
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), (t.device, t.dtype, dtype)
+    return t
+
+
+class Model:
+    """One resident multi-exit detector (thia_model*)."""
+
+    def __init__(self, blob, n_exits, device="cuda:0"):
+        blob = np.ascontiguousarray(blob, dtype=np.uint8)
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        torch.zeros(1, device=self.device)          # make sure the HIP context exists
+        self._h = C.c_void_p()
+        rc = lib().thia_load_model(blob.ctypes.data, blob.nbytes, n_exits, C.byref(self._h))
+        if rc:
+            self._h = None
+            raise ThiaError(rc, "thia_load_model")
+        self.info = ThiaInfo()
+        self._check(lib().thia_get_info(self._h, C.byref(self.info)))
+        self.precision = self.info.precision
+        self.elem = torch.bfloat16 if self.precision else torch.float32
+        self.D = self.info.max_det
+        self.set_stream(torch.cuda.current_stream(self.device))
+
+    # -- lifetime
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().thia_free_model(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc):
+        if rc:
+            raise ThiaError(rc, lib().thia_last_error(self._h).decode())
+
+    # -- the boundary calls
+    def set_stream(self, stream):
+        self._check(lib().thia_set_stream(self._h, C.c_void_p(stream.cuda_stream if stream is not None else 0)))
+
+    def set_microbatch(self, frames):
+        self._check(lib().thia_set_microbatch(self._h, frames))
+
+    def alloc_outputs(self, n):
+        D = self.D
+        return (torch.empty((n, D, 4), dtype=torch.float32, device=self.device),
+                torch.empty((n, D), dtype=torch.float32, device=self.device),
+                torch.empty((n, D), dtype=torch.int32, device=self.device))
+
+    def detect_chunk(self, frames, ep, out=None):
+        """frames: cuda uint8 [n,3,H,W]; returns (boxes [n,D,4], scores [n,D], labels [n,D]) on the device."""
+        _dev(frames, torch.uint8)
+        n, c, H, W = frames.shape
+        assert c == 3
+        out = out or self.alloc_outputs(n)
+        self._check(lib().thia_detect_chunk(self._h, _ptr(frames), n, H, W, ep, _ptr(out[0]), _ptr(out[1]), _ptr(out[2])))
+        return out
+
+    def run_plan(self, frames, chunk_len, chunk_ep, out=None):
+        _dev(frames, torch.uint8)
+        n, c, H, W = frames.shape
+        ce = np.ascontiguousarray(chunk_ep, dtype=np.int32)
+        assert c == 3 and n == chunk_len * ce.size
+        out = out or self.alloc_outputs(n)
+        self._check(lib().thia_run_plan(self._h, _ptr(frames), ce.size, chunk_len, H, W, ce.ctypes.data, _ptr(out[0]),
+                                        _ptr(out[1]), _ptr(out[2])))
+        return out
+
+    # -- inspection
+    def set_debug(self, on):
+        self._check(lib().thia_set_debug(self._h, int(on)))
+
+    def tap(self, name):
+        """Flat numpy array of a recorded intermediate (float32 / int32; bf16 taps are widened to float32)."""
+        which = TAPS[name]
+        nbytes = lib().thia_debug_tap_bytes(self._h, which)
+        kind = _TAP_ELEM.get(name, "f")
+        if kind == "T" and self.precision:
+            raw = np.empty(nbytes // 2, np.uint16)
+        elif kind == "i":
+            raw = np.empty(nbytes // 4, np.int32)
+        else:
+            raw = np.empty(nbytes // 4, np.float32)
+        self._check(lib().thia_debug_tap(self._h, which, raw.ctypes.data, nbytes))
+        if raw.dtype == np.uint16:
+            return (raw.astype(np.uint32) << 16).view(np.float32)
+        return raw
+
+    def profile_begin(self):
+        self._check(lib().thia_profile_begin(self._h))
+
+    def profile_read(self):
+        ms = np.zeros(len(KERNEL_CLASSES), np.float32)
+        cnt = np.zeros(len(KERNEL_CLASSES), np.int32)
+        self._check(lib().thia_profile_read(self._h, ms.ctypes.data, cnt.ctypes.data))
+        return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(KERNEL_CLASSES)}
+
+    def profile_end(self):
+        self._check(lib().thia_profile_end(self._h))
+
+    # -- single steps
+    def op_rpn_proposals(self, logits, deltas, H, W, ep):
+        _dev(logits, torch.float32), _dev(deltas, torch.float32)
+        n, pre = logits.shape[0], self.info.pre_nms
+        idx = torch.empty((n, pre), dtype=torch.int32, device=self.device)
+        boxes = torch.empty((n, pre, 4), dtype=torch.float32, device=self.device)
+        cnt = torch.empty((n,), dtype=torch.int32, device=self.device)
+        self._check(lib().thia_op_rpn_proposals(self._h, _ptr(logits), _ptr(deltas), n, H, W, ep, _ptr(idx), _ptr(boxes), _ptr(cnt)))
+        return idx, boxes, cnt
+
+    def op_nms(self, boxes, counts, thr, max_keep):
+        _dev(boxes, torch.float32), _dev(counts, torch.int32)
+        n, cap = boxes.shape[0], boxes.shape[1]
+        keep = torch.empty((n, max_keep), dtype=torch.int32, device=self.device)
+        cnt = torch.empty((n,), dtype=torch.int32, device=self.device)
+        self._check(lib().thia_op_nms(self._h, _ptr(boxes), _ptr(counts), n, cap, thr, max_keep, _ptr(keep), _ptr(cnt)))
+        return keep, cnt
+
+    def op_roialign(self, feat, rois, stride):
+        _dev(feat, self.elem), _dev(rois, torch.float32)
+        n, Hk, Wk, Ch = feat.shape
+        P = self.info.pool
+        out = torch.empty((n, self.info.post_nms, P * P, Ch), dtype=self.elem, device=self.device)
+        self._check(lib().thia_op_roialign(self._h, _ptr(feat), _ptr(rois), n, Hk, Wk, stride, _ptr(out)))
+        return out
+
+    def op_select_detections(self, scores, boxes, roi_n):
+        _dev(scores, torch.float32), _dev(boxes, torch.float32), _dev(roi_n, torch.int32)
+        n = scores.shape[0]
+        out = self.alloc_outputs(n)
+        cnt = torch.empty((n,), dtype=torch.int32, device=self.device)
+        self._check(lib().thia_op_select_detections(self._h, _ptr(scores), _ptr(boxes), _ptr(roi_n), n, _ptr(out[0]),
+                                                    _ptr(out[1]), _ptr(out[2]), _ptr(cnt)))
+        return out + (cnt,)
+
+    def op_conv(self, x, w, b, stride=1, pad=0, residual=None, relu=False, out_f32=False):
+        """x: cuda [n,H,W,Cin] in the model's element type; w: numpy [Cout,Cin,k,k]; b: numpy [Cout]."""
+        _dev(x, self.elem)
+        n, H, W, Cin = x.shape
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        b = np.ascontiguousarray(b, dtype=np.float32)
+        Cout, _, k, _ = w.shape
+        Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+        out = torch.empty((n, Ho, Wo, Cout), dtype=torch.float32 if out_f32 else self.elem, device=self.device)
+        if residual is not None:
+            _dev(residual, self.elem)
+        self._check(lib().thia_op_conv(self._h, _ptr(x), n, H, W, Cin, w.ctypes.data, b.ctypes.data, Cout, k, stride, pad,
+                                       _ptr(residual), int(relu), int(out_f32), _ptr(out)))
+        return out
+
+    def op_stem(self, frames):
+        _dev(frames, torch.uint8)
+        n, _, H, W = frames.shape
+        Hs, Ws = (H - 1) // 2 + 1, (W - 1) // 2 + 1
+        Hp, Wp = (Hs - 1) // 2 + 1, (Ws - 1) // 2 + 1
+        out = torch.empty((n, Hp, Wp, 64), dtype=self.elem, device=self.device)
+        self._check(lib().thia_op_stem(self._h, _ptr(frames), n, H, W, _ptr(out)))
+        return out

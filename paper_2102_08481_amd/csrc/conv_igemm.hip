@@ -1,0 +1,269 @@
+// Implicit-GEMM convolution on the CDNA4 matrix cores (gfx950).
+//
+// Every convolution and fully connected layer of the detector (bottleneck 1x1/3x3,
+// shortcut, exit lateral, RPN 3x3 and heads, FC layers and predictors) is the
+// contraction  out[m, n] = sum_k W[n, k] * X[m, k]  with m = (image, oy, ox),
+// n = output channel and k = (ky, kx, ci); activations are NHWC so a K tile of one
+// filter tap is a contiguous run of input channels of one input pixel.
+//
+// Tiling: a 256-thread block (4 wavefronts of 64) owns 128 pixels x BN channels and
+// walks K in 128-byte steps (64 bf16 / 32 fp32 per row).  Global loads are 16 bytes
+// per lane, staged in registers and written to a double-buffered LDS tile whose rows
+// are padded to 144 bytes so that the 16-byte fragment reads of 32 consecutive rows
+// fall in distinct banks.  Each wavefront owns 64 pixels x BN/2 channels as 32x32 MFMA
+// tiles.  The weights are the MFMA "A" operand (rows = channels) and the activations the
+// "B" operand (columns = pixels): each lane then holds 4 consecutive channels of one
+// pixel per accumulator quad, which is the contiguous direction of the NHWC output.
+// Epilogue: + bias (fp32) [+ residual] [ReLU], then one rounding to the output type.
+#include "thia_internal.h"
+
+namespace thia {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
+constexpr int BM = 128;       // pixels per block
+constexpr int BKB = 128;      // bytes of K per tile row
+constexpr int LDS_ROW = 144;  // padded row pitch in bytes
+
+template <typename T>
+__device__ inline void mma_step(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b);
+
+template <>
+__device__ inline void mma_step<bf16_t>(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), acc, 0, 0, 0);
+}
+template <>
+__device__ inline void mma_step<float>(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b) {
+    // 16 bytes = 4 consecutive k per lane half; MFMA step j contracts k = {j, 4 + j} of the 8-wide group
+    const f32x4_t fa = __builtin_bit_cast(f32x4_t, a), fb = __builtin_bit_cast(f32x4_t, b);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.x, fb.x, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.y, fb.y, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.z, fb.z, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.w, fb.w, acc, 0, 0, 0);
+}
+
+__device__ inline float load_elem(const float* p) { return *p; }
+__device__ inline float load_elem(const bf16_t* p) { return bf16_to_f32(*p); }
+__device__ inline void store_elem(float* p, float v) { *p = v; }
+__device__ inline void store_elem(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+__device__ inline void load4(const float* p, float r[4]) {
+    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(p);
+    r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
+}
+__device__ inline void load4(const bf16_t* p, float r[4]) {
+    const u32x2_t v = *reinterpret_cast<const u32x2_t*>(p);
+    r[0] = __uint_as_float(v.x << 16); r[1] = __uint_as_float(v.x & 0xffff0000u);
+    r[2] = __uint_as_float(v.y << 16); r[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+__device__ inline void store4(float* p, const float r[4]) {
+    f32x4_t v = {r[0], r[1], r[2], r[3]};
+    *reinterpret_cast<f32x4_t*>(p) = v;
+}
+__device__ inline void store4(bf16_t* p, const float r[4]) {
+    u32x2_t v;
+    v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
+    v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+    *reinterpret_cast<u32x2_t*>(p) = v;
+}
+
+template <typename T, int BN, typename OutT>
+__global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
+    constexpr int BK = BKB / (int)sizeof(T);   // K elements per tile row
+    constexpr int EPC = 16 / (int)sizeof(T);   // elements per 16-byte chunk
+    constexpr int TN = BN / 64;                // 32-channel MFMA tiles per wavefront
+    constexpr int TM = 2;                      // 32-pixel MFMA tiles per wavefront
+    constexpr int PA = BN / 32;                // 16-byte weight chunks staged per thread
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* sA = smem;                     // [2][BN][LDS_ROW]
+    unsigned char* sB = smem + 2 * BN * LDS_ROW;  // [2][BM][LDS_ROW]
+
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int wm = wv & 1, wn = wv >> 1;
+    const int HoWo = a.Ho * a.Wo;
+    const int M = a.N * HoWo;
+    const int K = a.kh * a.kw * a.Cin;
+    const int tiles_n = (a.Cout + BN - 1) / BN;
+    const int tile_n = blockIdx.x % tiles_n, tile_m = blockIdx.x / tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const T* __restrict__ in = static_cast<const T*>(a.in);
+    const T* __restrict__ wgt = static_cast<const T*>(a.w);
+
+    // ---- per-thread load coordinates: row = lrow + 32 p, 16-byte chunk lchunk of the 128-byte row
+    const int lrow = t >> 3, lchunk = t & 7;
+    size_t b_base[4];
+    int b_iy0[4], b_ix0[4];
+    bool b_ok[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int m = m0 + lrow + 32 * p;
+        b_ok[p] = m < M;
+        const int mm = b_ok[p] ? m : 0;
+        const int img = mm / HoWo, rem = mm - img * HoWo;
+        const int oy = rem / a.Wo, ox = rem - oy * a.Wo;
+        b_iy0[p] = oy * a.stride - a.pad;
+        b_ix0[p] = ox * a.stride - a.pad;
+        b_base[p] = (size_t)img * a.H * a.W * a.Cin + (size_t)lchunk * EPC;
+    }
+    size_t a_base[PA];
+    bool a_ok[PA];
+#pragma unroll
+    for (int p = 0; p < PA; ++p) {
+        const int n = n0 + lrow + 32 * p;
+        a_ok[p] = n < a.Cout;
+        a_base[p] = (size_t)(a_ok[p] ? n : 0) * K + (size_t)lchunk * EPC;
+    }
+    const int cin_tiles = a.Cin / BK;
+    const int KT = K / BK;
+
+    u32x4_t ra[PA], rb[4];
+    auto load_tiles = [&](int kt) {
+        const int tap = kt / cin_tiles;
+        const int c0 = (kt - tap * cin_tiles) * BK;
+        const int ky = tap / a.kw, kx = tap - ky * a.kw;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int iy = b_iy0[p] + ky, ix = b_ix0[p] + kx;
+            const bool ok = b_ok[p] && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (ok) v = *reinterpret_cast<const u32x4_t*>(in + b_base[p] + ((size_t)iy * a.W + ix) * a.Cin + c0);
+            rb[p] = v;
+        }
+#pragma unroll
+        for (int p = 0; p < PA; ++p) {
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (a_ok[p]) v = *reinterpret_cast<const u32x4_t*>(wgt + a_base[p] + (size_t)kt * BK);
+            ra[p] = v;
+        }
+    };
+    auto store_tiles = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            *reinterpret_cast<u32x4_t*>(sA + (size_t)(buf * BN + lrow + 32 * p) * LDS_ROW + lchunk * 16) = ra[p];
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            *reinterpret_cast<u32x4_t*>(sB + (size_t)(buf * BM + lrow + 32 * p) * LDS_ROW + lchunk * 16) = rb[p];
+    };
+
+    f32x16_t acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    load_tiles(0);
+    store_tiles(0);
+    __syncthreads();
+
+    const int frag_row = lane & 31, frag_off = (lane >> 5) * 16;
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < KT) load_tiles(kt + 1);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            u32x4_t fa[TN], fb[TM];
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+                fa[i] = *reinterpret_cast<const u32x4_t*>(
+                    sA + (size_t)(buf * BN + wn * (BN / 2) + i * 32 + frag_row) * LDS_ROW + kk * 32 + frag_off);
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+                fb[j] = *reinterpret_cast<const u32x4_t*>(
+                    sB + (size_t)(buf * BM + wm * 64 + j * 32 + frag_row) * LDS_ROW + kk * 32 + frag_off);
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j) mma_step<T>(acc[i][j], fa[i], fb[j]);
+        }
+        if (kt + 1 < KT) store_tiles(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue.  Accumulator element e of lane l: channel 8*(e/4) + 4*(l/32) + e%4, pixel l%32.
+    const T* __restrict__ res = static_cast<const T*>(a.res);
+    OutT* __restrict__ out0 = static_cast<OutT*>(a.out0);
+    OutT* __restrict__ out1 = static_cast<OutT*>(a.out1);
+    const bool vec = (a.out1 == nullptr) && ((a.Cout & 3) == 0) && ((a.ld0 & 3) == 0);
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int pix = m0 + wm * 64 + j * 32 + frag_row;
+            if (pix >= M) continue;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int ch = n0 + wn * (BN / 2) + i * 32 + 8 * v + 4 * (lane >> 5);
+                if (ch >= a.Cout) continue;
+                float r[4] = {acc[i][j][4 * v], acc[i][j][4 * v + 1], acc[i][j][4 * v + 2], acc[i][j][4 * v + 3]};
+                if (vec) {
+                    const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(a.bias + ch);
+                    r[0] += bv.x; r[1] += bv.y; r[2] += bv.z; r[3] += bv.w;
+                    if (res) {
+                        float q[4];
+                        load4(res + (size_t)pix * a.Cout + ch, q);
+                        r[0] += q[0]; r[1] += q[1]; r[2] += q[2]; r[3] += q[3];
+                    }
+                    if (a.relu) {
+                        r[0] = fmaxf(r[0], 0.f); r[1] = fmaxf(r[1], 0.f); r[2] = fmaxf(r[2], 0.f); r[3] = fmaxf(r[3], 0.f);
+                    }
+                    store4(out0 + (size_t)pix * a.ld0 + ch, r);
+                } else {
+                    for (int q = 0; q < 4; ++q) {
+                        const int c = ch + q;
+                        if (c >= a.Cout) break;
+                        float val = r[q] + a.bias[c];
+                        if (res) val += load_elem(res + (size_t)pix * a.Cout + c);
+                        if (a.relu) val = fmaxf(val, 0.f);
+                        if (c < a.n_split) store_elem(out0 + (size_t)pix * a.ld0 + c, val);
+                        else store_elem(out1 + (size_t)pix * a.ld1 + (c - a.n_split), val);
+                    }
+                }
+            }
+        }
+}
+
+bool conv_supported(const ConvArgs& a, int precision) {
+    const int bk = precision ? 64 : 32;
+    if (a.Cin <= 0 || a.Cin % bk) return false;
+    if (a.N <= 0 || a.Cout <= 0 || a.Ho <= 0 || a.Wo <= 0) return false;
+    if ((long long)a.N * a.Ho * a.Wo >= (1ll << 31)) return false;
+    if ((long long)a.N * a.H * a.W * a.Cin >= (1ll << 40)) return false;
+    return true;
+}
+
+template <typename T, int BN, typename OutT>
+static hipError_t launch_one(const ConvArgs& a, hipStream_t s) {
+    static bool attr_set = false;
+    const size_t lds = (size_t)2 * (BN + BM) * LDS_ROW;
+    auto kern = conv_igemm_kernel<T, BN, OutT>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long long M = (long long)a.N * a.Ho * a.Wo;
+    const long long tiles = ((M + BM - 1) / BM) * ((a.Cout + BN - 1) / BN);
+    if (tiles <= 0 || tiles >= (1ll << 31)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(256), lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream_t s) {
+    if (!conv_supported(a, precision)) return hipErrorInvalidValue;
+    const bool narrow = a.Cout <= 64;
+    if (precision == 0) {
+        return narrow ? launch_one<float, 64, float>(a, s) : launch_one<float, 128, float>(a, s);
+    }
+    if (out_f32) return narrow ? launch_one<bf16_t, 64, float>(a, s) : launch_one<bf16_t, 128, float>(a, s);
+    return narrow ? launch_one<bf16_t, 64, bf16_t>(a, s) : launch_one<bf16_t, 128, bf16_t>(a, s);
+}
+
+}  // namespace thia

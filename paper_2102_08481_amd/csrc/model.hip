@@ -1,0 +1,804 @@
+// Host side of libthia: weights-blob parsing and repacking, workspace planning, the
+// per-exit forward pass (micro-batched, one stream), plan execution and the C ABI.
+// Every arithmetic step runs in the HIP kernels of this library; there is no CPU path.
+#include <algorithm>
+#include <cmath>
+#include <new>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/thia.h"
+#include "thia_internal.h"
+
+using namespace thia;
+
+namespace {
+
+constexpr int32_t kMagic = 0x41494854;
+constexpr size_t kHeaderBytes = 256;
+
+struct Layer {
+    void* w = nullptr;     // device, element type per precision, [Cout][k][k][Cin]
+    float* b = nullptr;    // device fp32 [Cout]
+    int co = 0, ci = 0, k = 1;
+};
+struct Block {
+    Layer c1, c2, c3, sc;
+    bool has_sc = false;
+    int stride = 1;
+};
+struct ExitUnit {
+    Layer lateral, rpn_conv, rpn_head /* obj (A) ++ delta (4A) */, fc1, fc2, pred /* cls (Kc) ++ box (4Kc) */;
+};
+
+struct Tap {
+    void* buf = nullptr;
+    size_t cap = 0, bytes = 0, per_frame = 0;
+};
+
+struct Workspace {
+    int H = 0, W = 0, mb = 0;
+    char* arena = nullptr;
+    size_t bytes = 0;
+    void *act[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    void *hf = nullptr, *rpn_t = nullptr;
+    float *logits = nullptr, *deltas = nullptr;
+    TopkWork topk{};
+    int32_t *idx = nullptr, *prop_n = nullptr, *keep = nullptr, *roi_n = nullptr, *det_n = nullptr;
+    float *prop_boxes = nullptr, *rois = nullptr;
+    uint64_t *mask = nullptr, *sel_keys = nullptr;
+    void *roi_feat = nullptr, *h1 = nullptr, *h2 = nullptr;
+    float *cls = nullptr, *box = nullptr, *cand_scores = nullptr, *cand_boxes = nullptr;
+    int key_cap = 0;
+};
+
+}  // namespace
+
+struct thia_model {
+    int precision = 0, n_exits = 0, blocks_n[4] = {0, 0, 0, 0}, stem_ch = 64, has_lateral = 0, head_ch = 256;
+    AnchorSpec anc{};
+    int pre = 0, post = 0, pool = 7, sampling = 2, fc_dim = 0, Kc = 0, D = 0, base_width = 64;
+    float rpn_thr = 0.7f, score_thr = 0.05f, det_thr = 0.5f, mean = 0.f, stdv = 1.f;
+    size_t esz = 4;
+    float* stem_w = nullptr;  // device fp32 [147][64]
+    float* stem_b = nullptr;
+    std::vector<Block> stage[4];
+    ExitUnit ex[4];
+    char* warena = nullptr;
+    hipStream_t stream = nullptr;
+    int user_mb = 0;
+    Workspace ws;
+    bool debug = false;
+    Tap taps[THIA_TAP_COUNT];
+    bool profiling = false;
+    std::vector<hipEvent_t> ev_pool;
+    std::vector<int> ev_class;  // class of pair i (events 2i, 2i+1)
+    size_t ev_used = 0;
+    std::string err;
+};
+
+namespace {
+
+int fail(thia_model* m, int code, const std::string& msg) {
+    if (m) m->err = msg;
+    return code;
+}
+int fail_hip(thia_model* m, hipError_t e, const char* what) {
+    return fail(m, THIA_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(m, expr)                                          \
+    do {                                                          \
+        hipError_t e__ = (expr);                                  \
+        if (e__ != hipSuccess) return fail_hip((m), e__, #expr);  \
+    } while (0)
+
+inline int conv_out(int n, int k, int s, int p) { return (n + 2 * p - k) / s + 1; }
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- weights
+struct BlobReader {
+    const float* p;
+    const float* end;
+    bool take(size_t n, const float** out) {
+        if ((size_t)(end - p) < n) return false;
+        *out = p;
+        p += n;
+        return true;
+    }
+};
+
+struct HostLayer {
+    const float *w = nullptr, *b = nullptr;
+    int co = 0, ci = 0, k = 1;
+};
+bool take_layer(BlobReader& r, HostLayer& L, int co, int ci, int k) {
+    L.co = co; L.ci = ci; L.k = k;
+    return r.take((size_t)co * ci * k * k, &L.w) && r.take((size_t)co, &L.b);
+}
+
+struct ArenaPlan {
+    size_t off = 0;
+    size_t add(size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes);
+        return o;
+    }
+};
+
+// Convert OIHW fp32 -> [O][kh][kw][I] in the model's element type, appended to `dst`.
+void repack(const HostLayer& L, int precision, std::vector<unsigned char>& dst) {
+    const size_t n = (size_t)L.co * L.ci * L.k * L.k, esz = precision ? 2 : 4;
+    const size_t base = dst.size();
+    dst.resize(base + n * esz);
+    const int kk = L.k * L.k;
+    for (int o = 0; o < L.co; ++o)
+        for (int t = 0; t < kk; ++t)
+            for (int i = 0; i < L.ci; ++i) {
+                const float v = L.w[((size_t)o * L.ci + i) * kk + t];
+                const size_t d = ((size_t)o * kk + t) * L.ci + i;
+                if (precision) reinterpret_cast<bf16_t*>(dst.data() + base)[d] = f32_to_bf16(v);
+                else reinterpret_cast<float*>(dst.data() + base)[d] = v;
+            }
+}
+
+// Upload one layer (optionally the row-wise concatenation of two layers with equal ci, k).
+int upload_layer(thia_model* m, const HostLayer& a, const HostLayer* b2, Layer& out) {
+    std::vector<unsigned char> host;
+    repack(a, m->precision, host);
+    std::vector<float> bias(a.b, a.b + a.co);
+    int co = a.co;
+    if (b2) {
+        repack(*b2, m->precision, host);
+        bias.insert(bias.end(), b2->b, b2->b + b2->co);
+        co += b2->co;
+    }
+    out.co = co; out.ci = a.ci; out.k = a.k;
+    HIP_TRY(m, hipMalloc(&out.w, host.size()));
+    HIP_TRY(m, hipMemcpy(out.w, host.data(), host.size(), hipMemcpyHostToDevice));
+    HIP_TRY(m, hipMalloc(reinterpret_cast<void**>(&out.b), bias.size() * 4));
+    HIP_TRY(m, hipMemcpy(out.b, bias.data(), bias.size() * 4, hipMemcpyHostToDevice));
+    return THIA_OK;
+}
+void free_layer(Layer& L) {
+    if (L.w) (void)hipFree(L.w);
+    if (L.b) (void)hipFree(L.b);
+    L.w = nullptr; L.b = nullptr;
+}
+
+// ---------------------------------------------------------------- geometry
+struct ExitGeom { int C, Hk, Wk, stride; };
+ExitGeom exit_geom(const thia_model* m, int ep, int H, int W) {
+    int h = conv_out(conv_out(H, 7, 2, 3), 3, 2, 1), w = conv_out(conv_out(W, 7, 2, 3), 3, 2, 1);
+    for (int s = 1; s < ep; ++s) { h = conv_out(h, 3, 2, 1); w = conv_out(w, 3, 2, 1); }
+    return {4 * (m->base_width << (ep - 1)), h, w, 4 << (ep - 1)};
+}
+int head_channels(const thia_model* m, int ep) { return m->has_lateral ? m->head_ch : 4 * (m->base_width << (ep - 1)); }
+
+int next_pow2(int v) {
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+// Largest activation tensor (elements per frame) among all layers of the backbone.
+size_t max_act_elems(const thia_model* m, int H, int W) {
+    int h = conv_out(H, 7, 2, 3), w = conv_out(W, 7, 2, 3);
+    size_t mx = (size_t)h * w * m->stem_ch;
+    h = conv_out(h, 3, 2, 1); w = conv_out(w, 3, 2, 1);
+    for (int s = 0; s < m->n_exits; ++s) {
+        const int width = m->base_width << s;
+        if (s > 0) {
+            mx = std::max(mx, (size_t)h * w * width);  // conv1 output before the strided 3x3
+            h = conv_out(h, 3, 2, 1); w = conv_out(w, 3, 2, 1);
+        }
+        mx = std::max(mx, (size_t)h * w * 4 * width);
+    }
+    return mx;
+}
+
+int default_microbatch(const thia_model* m, int H, int W) {
+    const double per_frame = (double)max_act_elems(m, H, W) * m->esz;
+    int mb = (int)std::floor(72.0e6 / per_frame + 0.5);
+    return std::min(32, std::max(1, mb));
+}
+
+void free_workspace(thia_model* m) {
+    if (m->ws.arena) (void)hipFree(m->ws.arena);
+    m->ws = Workspace{};
+}
+
+int ensure_workspace(thia_model* m, int H, int W) {
+    const int mb = m->user_mb > 0 ? m->user_mb : default_microbatch(m, H, W);
+    Workspace& ws = m->ws;
+    if (ws.arena && ws.H == H && ws.W == W && ws.mb == mb) return THIA_OK;
+    if (ws.arena) {
+        HIP_TRY(m, hipStreamSynchronize(m->stream));
+        free_workspace(m);
+    }
+    const size_t esz = m->esz;
+    ArenaPlan ap;
+    const size_t act_bytes = (size_t)mb * max_act_elems(m, H, W) * esz;
+    size_t o_act[5];
+    for (int i = 0; i < 5; ++i) o_act[i] = ap.add(act_bytes);
+    // head buffers sized for the largest exit (exit 1 has the largest map)
+    size_t hw_max = 0, na_max = 0, hf_max = 0;
+    const int A = m->anc.n_sizes * m->anc.n_ratios;
+    for (int ep = 1; ep <= m->n_exits; ++ep) {
+        const ExitGeom g = exit_geom(m, ep, H, W);
+        const size_t hw = (size_t)g.Hk * g.Wk;
+        hw_max = std::max(hw_max, hw);
+        na_max = std::max(na_max, hw * A);
+        hf_max = std::max(hf_max, hw * head_channels(m, ep));
+    }
+    if (na_max >= (1u << 22)) return fail(m, THIA_E_SHAPE, "frame too large: more than 2^22 anchors per frame");
+    int ch_max = 0;
+    for (int ep = 1; ep <= m->n_exits; ++ep) ch_max = std::max(ch_max, head_channels(m, ep));
+    const size_t o_hf = ap.add((size_t)mb * hf_max * esz), o_rt = ap.add((size_t)mb * hf_max * esz);
+    const size_t o_lg = ap.add((size_t)mb * na_max * 4), o_dl = ap.add((size_t)mb * na_max * 16);
+    const int cap = next_pow2(m->pre);
+    const size_t o_hist = ap.add((size_t)mb * 2048 * 4), o_state = ap.add((size_t)mb * 4 * 8), o_cand = ap.add((size_t)mb * cap * 8);
+    const size_t o_idx = ap.add((size_t)mb * m->pre * 4), o_pb = ap.add((size_t)mb * m->pre * 16), o_pn = ap.add((size_t)mb * 4);
+    const int words = (m->pre + 63) / 64;
+    const size_t o_mask = ap.add((size_t)mb * m->pre * words * 8);
+    const size_t o_keep = ap.add((size_t)mb * m->post * 4), o_rois = ap.add((size_t)mb * m->post * 16), o_rn = ap.add((size_t)mb * 4);
+    const size_t o_dn = ap.add((size_t)mb * 4);
+    const size_t rows = (size_t)mb * m->post;
+    const size_t o_rf = ap.add(rows * m->pool * m->pool * ch_max * esz);
+    const size_t o_h1 = ap.add(rows * m->fc_dim * esz), o_h2 = ap.add(rows * m->fc_dim * esz);
+    const size_t o_cls = ap.add(rows * m->Kc * 4), o_box = ap.add(rows * m->Kc * 16);
+    const size_t o_cs = ap.add(rows * m->Kc * 4), o_cb = ap.add(rows * m->Kc * 16);
+    const int key_cap = next_pow2(m->post * m->Kc);
+    const size_t o_keys = ap.add((size_t)mb * key_cap * 8);
+
+    void* base = nullptr;
+    hipError_t e = hipMalloc(&base, ap.off);
+    if (e != hipSuccess) return fail(m, THIA_E_NOMEM, std::string("workspace hipMalloc: ") + hipGetErrorString(e));
+    char* a = static_cast<char*>(base);
+    ws.arena = a; ws.bytes = ap.off; ws.H = H; ws.W = W; ws.mb = mb;
+    for (int i = 0; i < 5; ++i) ws.act[i] = a + o_act[i];
+    ws.hf = a + o_hf; ws.rpn_t = a + o_rt;
+    ws.logits = reinterpret_cast<float*>(a + o_lg); ws.deltas = reinterpret_cast<float*>(a + o_dl);
+    ws.topk.hist = reinterpret_cast<uint32_t*>(a + o_hist);
+    ws.topk.state = reinterpret_cast<uint64_t*>(a + o_state);
+    ws.topk.cand = reinterpret_cast<uint64_t*>(a + o_cand);
+    ws.idx = reinterpret_cast<int32_t*>(a + o_idx); ws.prop_boxes = reinterpret_cast<float*>(a + o_pb);
+    ws.prop_n = reinterpret_cast<int32_t*>(a + o_pn); ws.mask = reinterpret_cast<uint64_t*>(a + o_mask);
+    ws.keep = reinterpret_cast<int32_t*>(a + o_keep); ws.rois = reinterpret_cast<float*>(a + o_rois);
+    ws.roi_n = reinterpret_cast<int32_t*>(a + o_rn); ws.det_n = reinterpret_cast<int32_t*>(a + o_dn);
+    ws.roi_feat = a + o_rf; ws.h1 = a + o_h1; ws.h2 = a + o_h2;
+    ws.cls = reinterpret_cast<float*>(a + o_cls); ws.box = reinterpret_cast<float*>(a + o_box);
+    ws.cand_scores = reinterpret_cast<float*>(a + o_cs); ws.cand_boxes = reinterpret_cast<float*>(a + o_cb);
+    ws.sel_keys = reinterpret_cast<uint64_t*>(a + o_keys); ws.key_cap = key_cap;
+    return THIA_OK;
+}
+
+// ---------------------------------------------------------------- launch bookkeeping
+struct Scope {  // brackets one launch (group) with events when profiling is on
+    thia_model* m;
+    bool on;
+    Scope(thia_model* m_, int cls) : m(m_), on(m_->profiling) {
+        if (!on) return;
+        if (m->ev_used + 2 > m->ev_pool.size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+            m->ev_pool.push_back(a);
+            m->ev_pool.push_back(b);
+        }
+        m->ev_class.resize(m->ev_used / 2 + 1);
+        m->ev_class[m->ev_used / 2] = cls;
+        (void)hipEventRecord(m->ev_pool[m->ev_used], m->stream);
+    }
+    ~Scope() {
+        if (!on) return;
+        (void)hipEventRecord(m->ev_pool[m->ev_used + 1], m->stream);
+        m->ev_used += 2;
+    }
+};
+
+int run_conv(thia_model* m, int cls, const Layer& L, const void* in, int n, int H, int W, int stride, int pad, const void* res,
+             bool relu, bool out_f32, void* out0, void* out1 = nullptr, int n_split = -1) {
+    ConvArgs a{};
+    a.in = in; a.w = L.w; a.bias = L.b; a.res = res; a.out0 = out0; a.out1 = out1;
+    a.N = n; a.H = H; a.W = W; a.Cin = L.ci; a.Cout = L.co; a.kh = L.k; a.kw = L.k; a.stride = stride; a.pad = pad;
+    a.Ho = conv_out(H, L.k, stride, pad); a.Wo = conv_out(W, L.k, stride, pad);
+    a.relu = relu ? 1 : 0;
+    if (out1) { a.n_split = n_split; a.ld0 = n_split; a.ld1 = L.co - n_split; }
+    else { a.n_split = L.co; a.ld0 = L.co; a.ld1 = 0; }
+    Scope sc(m, cls);
+    HIP_TRY(m, launch_conv(a, m->precision, out_f32, m->stream));
+    return THIA_OK;
+}
+
+int tap_prepare(thia_model* m, int which, int n, size_t per_frame) {
+    Tap& t = m->taps[which];
+    const size_t need = (size_t)n * per_frame;
+    if (need > t.cap) {
+        if (t.buf) { HIP_TRY(m, hipStreamSynchronize(m->stream)); (void)hipFree(t.buf); t.buf = nullptr; t.cap = 0; }
+        HIP_TRY(m, hipMalloc(&t.buf, need));
+        t.cap = need;
+    }
+    t.bytes = need; t.per_frame = per_frame;
+    return THIA_OK;
+}
+int tap_copy(thia_model* m, int which, int f0, int nb, const void* src) {
+    Tap& t = m->taps[which];
+    HIP_TRY(m, hipMemcpyAsync(static_cast<char*>(t.buf) + (size_t)f0 * t.per_frame, src, (size_t)nb * t.per_frame,
+                              hipMemcpyDeviceToDevice, m->stream));
+    return THIA_OK;
+}
+
+#define TRY(expr)                     \
+    do {                              \
+        int rc__ = (expr);            \
+        if (rc__ != THIA_OK) return rc__; \
+    } while (0)
+
+// Backbone truncated at exit ep for nb frames; returns the exit-stage tensor (NHWC) in *feat.
+int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int ep, const void** feat) {
+    Workspace& ws = m->ws;
+    const int Hs = conv_out(H, 7, 2, 3), Ws = conv_out(W, 7, 2, 3);
+    {
+        Scope sc(m, THIA_K_STEM);
+        HIP_TRY(m, launch_stem(frames, nb, H, W, m->stem_w, m->stem_b, m->mean, m->stdv, m->precision, ws.act[2], m->stream));
+    }
+    int h = conv_out(Hs, 3, 2, 1), w = conv_out(Ws, 3, 2, 1);
+    {
+        Scope sc(m, THIA_K_POOL);
+        HIP_TRY(m, launch_maxpool(ws.act[2], nb, Hs, Ws, m->stem_ch, m->precision, ws.act[0], m->stream));
+    }
+    void *x = ws.act[0], *y = ws.act[1];
+    for (int s = 0; s < ep; ++s)
+        for (const Block& B : m->stage[s]) {
+            const int ho = conv_out(h, 3, B.stride, 1), wo = conv_out(w, 3, B.stride, 1);
+            TRY(run_conv(m, THIA_K_CONV, B.c1, x, nb, h, w, 1, 0, nullptr, true, false, ws.act[2]));
+            TRY(run_conv(m, THIA_K_CONV, B.c2, ws.act[2], nb, h, w, B.stride, 1, nullptr, true, false, ws.act[3]));
+            const void* shortcut = x;
+            if (B.has_sc) {
+                TRY(run_conv(m, THIA_K_CONV, B.sc, x, nb, h, w, B.stride, 0, nullptr, false, false, ws.act[4]));
+                shortcut = ws.act[4];
+            }
+            TRY(run_conv(m, THIA_K_CONV, B.c3, ws.act[3], nb, ho, wo, 1, 0, shortcut, true, false, y));
+            std::swap(x, y);
+            h = ho; w = wo;
+        }
+    *feat = x;
+    return THIA_OK;
+}
+
+// Heads of exit ep on nb frames whose exit-stage tensor is `feat`.
+int run_heads(thia_model* m, const void* feat, int f0, int nb, int H, int W, int ep, float* out_boxes, float* out_scores,
+              int32_t* out_labels) {
+    Workspace& ws = m->ws;
+    const ExitUnit& E = m->ex[ep - 1];
+    const ExitGeom g = exit_geom(m, ep, H, W);
+    const int A = m->anc.n_sizes * m->anc.n_ratios, Ch = head_channels(m, ep), P = m->pool;
+    const long nA = (long)g.Hk * g.Wk * A;
+    const void* hf = feat;
+    if (m->has_lateral) {
+        TRY(run_conv(m, THIA_K_CONV, E.lateral, feat, nb, g.Hk, g.Wk, 1, 0, nullptr, false, false, ws.hf));
+        hf = ws.hf;
+    }
+    TRY(run_conv(m, THIA_K_CONV, E.rpn_conv, hf, nb, g.Hk, g.Wk, 1, 1, nullptr, true, false, ws.rpn_t));
+    TRY(run_conv(m, THIA_K_CONV, E.rpn_head, ws.rpn_t, nb, g.Hk, g.Wk, 1, 0, nullptr, false, true, ws.logits, ws.deltas, A));
+    {
+        Scope sc(m, THIA_K_TOPK);
+        HIP_TRY(m, launch_rpn_proposals(ws.logits, ws.deltas, nb, nA, m->pre, g.Wk, g.stride, (float)W, (float)H, m->anc, ws.topk,
+                                        ws.idx, ws.prop_boxes, ws.prop_n, m->stream));
+    }
+    {
+        Scope sc(m, THIA_K_NMS);
+        HIP_TRY(m, launch_nms(ws.prop_boxes, ws.prop_n, nb, m->pre, m->rpn_thr, m->post, ws.mask, ws.keep, ws.roi_n, ws.rois,
+                              m->stream));
+    }
+    {
+        Scope sc(m, THIA_K_ROIALIGN);
+        HIP_TRY(m, launch_roialign(hf, ws.rois, nb, m->post, g.Hk, g.Wk, Ch, g.stride, P, m->precision, ws.roi_feat, m->stream));
+    }
+    const int rows = nb * m->post;
+    TRY(run_conv(m, THIA_K_FC, E.fc1, ws.roi_feat, rows, 1, 1, 1, 0, nullptr, true, false, ws.h1));
+    TRY(run_conv(m, THIA_K_FC, E.fc2, ws.h1, rows, 1, 1, 1, 0, nullptr, true, false, ws.h2));
+    TRY(run_conv(m, THIA_K_FC, E.pred, ws.h2, rows, 1, 1, 1, 0, nullptr, false, true, ws.cls, ws.box, m->Kc));
+    {
+        Scope sc(m, THIA_K_POST);
+        HIP_TRY(m, launch_scores_boxes(ws.cls, ws.box, ws.rois, nb, m->post, m->Kc, (float)W, (float)H, ws.cand_scores,
+                                       ws.cand_boxes, m->stream));
+        HIP_TRY(m, launch_select(ws.cand_scores, ws.cand_boxes, ws.roi_n, nb, m->post, m->Kc, m->score_thr, m->det_thr, m->D,
+                                 ws.sel_keys, ws.key_cap, out_boxes, out_scores, out_labels, ws.det_n, m->stream));
+    }
+    if (m->debug) {
+        const size_t esz = m->esz, hw = (size_t)g.Hk * g.Wk;
+        TRY(tap_copy(m, THIA_TAP_FEAT, f0, nb, feat));
+        TRY(tap_copy(m, THIA_TAP_HEAD_FEAT, f0, nb, hf));
+        TRY(tap_copy(m, THIA_TAP_RPN_LOGITS, f0, nb, ws.logits));
+        TRY(tap_copy(m, THIA_TAP_RPN_DELTAS, f0, nb, ws.deltas));
+        TRY(tap_copy(m, THIA_TAP_TOPK_IDX, f0, nb, ws.idx));
+        TRY(tap_copy(m, THIA_TAP_PROP_BOXES, f0, nb, ws.prop_boxes));
+        TRY(tap_copy(m, THIA_TAP_PROP_N, f0, nb, ws.prop_n));
+        TRY(tap_copy(m, THIA_TAP_ROIS, f0, nb, ws.rois));
+        TRY(tap_copy(m, THIA_TAP_ROI_N, f0, nb, ws.roi_n));
+        TRY(tap_copy(m, THIA_TAP_ROI_FEAT, f0, nb, ws.roi_feat));
+        TRY(tap_copy(m, THIA_TAP_CLS_LOGITS, f0, nb, ws.cls));
+        TRY(tap_copy(m, THIA_TAP_BOX_DELTAS, f0, nb, ws.box));
+        TRY(tap_copy(m, THIA_TAP_CAND_SCORES, f0, nb, ws.cand_scores));
+        TRY(tap_copy(m, THIA_TAP_CAND_BOXES, f0, nb, ws.cand_boxes));
+        TRY(tap_copy(m, THIA_TAP_DET_N, f0, nb, ws.det_n));
+        (void)esz; (void)hw;
+    }
+    return THIA_OK;
+}
+
+int prepare_taps(thia_model* m, int n, int H, int W, int ep) {
+    const ExitGeom g = exit_geom(m, ep, H, W);
+    const size_t esz = m->esz, hw = (size_t)g.Hk * g.Wk;
+    const int A = m->anc.n_sizes * m->anc.n_ratios, Ch = head_channels(m, ep);
+    const size_t post = m->post, Kc = m->Kc;
+    TRY(tap_prepare(m, THIA_TAP_FEAT, n, hw * g.C * esz));
+    TRY(tap_prepare(m, THIA_TAP_HEAD_FEAT, n, hw * Ch * esz));
+    TRY(tap_prepare(m, THIA_TAP_RPN_LOGITS, n, hw * A * 4));
+    TRY(tap_prepare(m, THIA_TAP_RPN_DELTAS, n, hw * A * 16));
+    TRY(tap_prepare(m, THIA_TAP_TOPK_IDX, n, (size_t)m->pre * 4));
+    TRY(tap_prepare(m, THIA_TAP_PROP_BOXES, n, (size_t)m->pre * 16));
+    TRY(tap_prepare(m, THIA_TAP_PROP_N, n, 4));
+    TRY(tap_prepare(m, THIA_TAP_ROIS, n, post * 16));
+    TRY(tap_prepare(m, THIA_TAP_ROI_N, n, 4));
+    TRY(tap_prepare(m, THIA_TAP_ROI_FEAT, n, post * m->pool * m->pool * Ch * esz));
+    TRY(tap_prepare(m, THIA_TAP_CLS_LOGITS, n, post * Kc * 4));
+    TRY(tap_prepare(m, THIA_TAP_BOX_DELTAS, n, post * Kc * 16));
+    TRY(tap_prepare(m, THIA_TAP_CAND_SCORES, n, post * Kc * 4));
+    TRY(tap_prepare(m, THIA_TAP_CAND_BOXES, n, post * Kc * 16));
+    TRY(tap_prepare(m, THIA_TAP_DET_N, n, 4));
+    return THIA_OK;
+}
+
+int check_frame_args(thia_model* m, const void* frames, int n, int H, int W, const void* ob, const void* os, const void* ol) {
+    if (!m) return THIA_E_BADARG;
+    if (n < 0) return fail(m, THIA_E_BADARG, "negative frame count");
+    if (n > 0 && (!frames || !ob || !os || !ol)) return fail(m, THIA_E_BADARG, "null pointer");
+    if (H < 32 || W < 32 || H > 16384 || W > 16384) return fail(m, THIA_E_SHAPE, "frame size must be within 32..16384");
+    return THIA_OK;
+}
+
+// n frames at exit ep (1..n_exits), micro-batched.  Assumes arguments were validated.
+int detect_frames(thia_model* m, const uint8_t* frames, int n, int H, int W, int ep, float* ob, float* os, int32_t* ol) {
+    TRY(ensure_workspace(m, H, W));
+    if (m->debug) TRY(prepare_taps(m, n, H, W, ep));
+    const int mb = m->ws.mb, D = m->D;
+    for (int f0 = 0; f0 < n; f0 += mb) {
+        const int nb = std::min(mb, n - f0);
+        const void* feat = nullptr;
+        TRY(run_backbone(m, frames + (size_t)f0 * 3 * H * W, nb, H, W, ep, &feat));
+        TRY(run_heads(m, feat, f0, nb, H, W, ep, ob + (size_t)f0 * D * 4, os + (size_t)f0 * D, ol + (size_t)f0 * D));
+    }
+    return THIA_OK;
+}
+
+}  // namespace
+
+// =================================================================== C ABI
+extern "C" {
+
+int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model** out) {
+    if (!weights || !out) return THIA_E_BADARG;
+    *out = nullptr;
+    if (nbytes < kHeaderBytes || (nbytes - kHeaderBytes) % 4) return THIA_E_BLOB;
+    int32_t h[64];
+    float hf[64];
+    std::memcpy(h, weights, 256);
+    std::memcpy(hf, weights, 256);
+    if (h[0] != kMagic || h[1] != 1) return THIA_E_BLOB;
+    if (h[3] != n_exits || n_exits < 1 || n_exits > 4) return THIA_E_BLOB;
+    thia_model* m = new (std::nothrow) thia_model();
+    if (!m) return THIA_E_NOMEM;
+    m->precision = h[2];
+    m->esz = m->precision ? 2 : 4;
+    m->n_exits = n_exits;
+    for (int i = 0; i < 4; ++i) m->blocks_n[i] = h[4 + i];
+    m->stem_ch = h[8]; m->has_lateral = h[9]; m->head_ch = h[10];
+    m->anc.n_sizes = h[11]; m->anc.n_ratios = h[12];
+    m->pre = h[25]; m->post = h[26]; m->rpn_thr = hf[27]; m->pool = h[28]; m->sampling = h[29];
+    m->fc_dim = h[30]; m->Kc = h[31]; m->score_thr = hf[32]; m->det_thr = hf[33]; m->D = h[34];
+    m->mean = hf[35]; m->stdv = hf[36]; m->base_width = h[37];
+    auto bad = [&](int code) { thia_free_model(m); return code; };
+    if ((m->precision != 0 && m->precision != 1) || m->anc.n_sizes < 1 || m->anc.n_sizes > 8 || m->anc.n_ratios < 1 ||
+        m->anc.n_ratios > 4 || m->pre < 1 || m->pre > 4096 || m->post < 1 || m->post > m->pre || m->Kc < 2 || m->Kc > 256 ||
+        m->D < 1 || m->D > 512 || m->pool < 1 || m->pool > 16 || !(m->stdv > 0.f))
+        return bad(THIA_E_BLOB);
+    // kernel limits: channel counts multiples of 64, 64 stem channels, 2x2 sampling
+    if (m->stem_ch != 64 || m->base_width % 64 || m->head_ch % 64 || m->fc_dim % 64 || m->sampling != 2) return bad(THIA_E_SHAPE);
+    for (int i = 0; i < 8; ++i) m->anc.sizes[i] = hf[13 + i];
+    for (int i = 0; i < 4; ++i) m->anc.sqrt_ratios[i] = i < m->anc.n_ratios ? sqrtf(hf[21 + i]) : 1.f;
+
+    BlobReader r{reinterpret_cast<const float*>(static_cast<const char*>(weights) + kHeaderBytes),
+                 reinterpret_cast<const float*>(static_cast<const char*>(weights) + nbytes)};
+    HostLayer stem;
+    if (!take_layer(r, stem, m->stem_ch, 3, 7)) return bad(THIA_E_BLOB);
+    {   // stem weights as fp32 [(c*7+ky)*7+kx][64]; bf16 precision keeps bf16-representable values
+        std::vector<float> w(147 * 64);
+        for (int o = 0; o < 64; ++o)
+            for (int t = 0; t < 147; ++t) {
+                float v = stem.w[(size_t)o * 147 + t];
+                if (m->precision) v = bf16_to_f32(f32_to_bf16(v));
+                w[(size_t)t * 64 + o] = v;
+            }
+        if (hipMalloc(reinterpret_cast<void**>(&m->stem_w), w.size() * 4) != hipSuccess) return bad(THIA_E_NOMEM);
+        if (hipMalloc(reinterpret_cast<void**>(&m->stem_b), 64 * 4) != hipSuccess) return bad(THIA_E_NOMEM);
+        if (hipMemcpy(m->stem_w, w.data(), w.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return bad(THIA_E_HIP);
+        if (hipMemcpy(m->stem_b, stem.b, 64 * 4, hipMemcpyHostToDevice) != hipSuccess) return bad(THIA_E_HIP);
+    }
+    int cin = m->stem_ch;
+    for (int s = 0; s < n_exits; ++s) {
+        const int w = m->base_width << s;
+        if (m->blocks_n[s] < 1 || m->blocks_n[s] > 64) return bad(THIA_E_BLOB);
+        m->stage[s].resize(m->blocks_n[s]);
+        for (int b = 0; b < m->blocks_n[s]; ++b) {
+            Block& B = m->stage[s][b];
+            B.stride = (b == 0 && s > 0) ? 2 : 1;  // the stride sits on the 3x3 of a stage's first block
+            HostLayer c1, c2, c3, sc;
+            if (!take_layer(r, c1, w, cin, 1) || !take_layer(r, c2, w, w, 3) || !take_layer(r, c3, 4 * w, w, 1)) return bad(THIA_E_BLOB);
+            int rc = upload_layer(m, c1, nullptr, B.c1);
+            if (!rc) rc = upload_layer(m, c2, nullptr, B.c2);
+            if (!rc) rc = upload_layer(m, c3, nullptr, B.c3);
+            if (b == 0) {
+                if (!take_layer(r, sc, 4 * w, cin, 1)) return bad(THIA_E_BLOB);
+                B.has_sc = true;
+                if (!rc) rc = upload_layer(m, sc, nullptr, B.sc);
+            }
+            if (rc) return bad(rc);
+            cin = 4 * w;
+        }
+    }
+    const int A = m->anc.n_sizes * m->anc.n_ratios;
+    for (int e = 0; e < n_exits; ++e) {
+        ExitUnit& E = m->ex[e];
+        const int ce = 4 * (m->base_width << e);
+        int hc = ce, rc = THIA_OK;
+        HostLayer lat, rc3, obj, dl, fc1, fc2, cls, box;
+        if (m->has_lateral) {
+            if (!take_layer(r, lat, m->head_ch, ce, 1)) return bad(THIA_E_BLOB);
+            hc = m->head_ch;
+            rc = upload_layer(m, lat, nullptr, E.lateral);
+        }
+        if (!take_layer(r, rc3, hc, hc, 3) || !take_layer(r, obj, A, hc, 1) || !take_layer(r, dl, 4 * A, hc, 1) ||
+            !take_layer(r, fc1, m->fc_dim, hc, m->pool) || !take_layer(r, fc2, m->fc_dim, m->fc_dim, 1) ||
+            !take_layer(r, cls, m->Kc, m->fc_dim, 1) || !take_layer(r, box, 4 * m->Kc, m->fc_dim, 1))
+            return bad(THIA_E_BLOB);
+        if (!rc) rc = upload_layer(m, rc3, nullptr, E.rpn_conv);
+        if (!rc) rc = upload_layer(m, obj, &dl, E.rpn_head);
+        // FC1 reads ROI features laid out [(ph*P+pw)][c]: the same O,(kh,kw),I repack as a PxP convolution,
+        // after which it is a plain matrix product over K = P*P*hc
+        if (!rc) rc = upload_layer(m, fc1, nullptr, E.fc1);
+        E.fc1.ci = hc * m->pool * m->pool; E.fc1.k = 1;
+        if (!rc) rc = upload_layer(m, fc2, nullptr, E.fc2);
+        if (!rc) rc = upload_layer(m, cls, &box, E.pred);
+        if (rc) return bad(rc);
+    }
+    if (r.p != r.end) return bad(THIA_E_BLOB);
+    *out = m;
+    return THIA_OK;
+}
+
+void thia_free_model(thia_model* m) {
+    if (!m) return;
+    (void)hipStreamSynchronize(m->stream);
+    free_workspace(m);
+    for (auto& t : m->taps) if (t.buf) (void)hipFree(t.buf);
+    for (auto e : m->ev_pool) (void)hipEventDestroy(e);
+    if (m->stem_w) (void)hipFree(m->stem_w);
+    if (m->stem_b) (void)hipFree(m->stem_b);
+    for (int s = 0; s < 4; ++s)
+        for (Block& B : m->stage[s]) { free_layer(B.c1); free_layer(B.c2); free_layer(B.c3); free_layer(B.sc); }
+    for (int e = 0; e < 4; ++e) {
+        ExitUnit& E = m->ex[e];
+        free_layer(E.lateral); free_layer(E.rpn_conv); free_layer(E.rpn_head); free_layer(E.fc1); free_layer(E.fc2); free_layer(E.pred);
+    }
+    delete m;
+}
+
+int thia_set_stream(thia_model* m, void* hip_stream) {
+    if (!m) return THIA_E_BADARG;
+    HIP_TRY(m, hipStreamSynchronize(m->stream));
+    m->stream = static_cast<hipStream_t>(hip_stream);
+    return THIA_OK;
+}
+
+int thia_set_microbatch(thia_model* m, int frames) {
+    if (!m) return THIA_E_BADARG;
+    if (frames < 0 || frames > 256) return fail(m, THIA_E_BADARG, "microbatch must be within 0..256");
+    m->user_mb = frames;
+    return THIA_OK;
+}
+
+int thia_get_info(const thia_model* m, thia_info* o) {
+    if (!m || !o) return THIA_E_BADARG;
+    o->precision = m->precision; o->n_exits = m->n_exits;
+    for (int i = 0; i < 4; ++i) o->blocks[i] = m->blocks_n[i];
+    o->head_ch = m->head_ch; o->n_anchors = m->anc.n_sizes * m->anc.n_ratios;
+    o->pre_nms = m->pre; o->post_nms = m->post; o->pool = m->pool; o->fc_dim = m->fc_dim; o->n_classes = m->Kc;
+    o->max_det = m->D; o->microbatch = m->user_mb > 0 ? m->user_mb : m->ws.mb; o->has_lateral = m->has_lateral;
+    return THIA_OK;
+}
+
+int thia_detect_chunk(thia_model* m, const uint8_t* frames, int n, int H, int W, int ep, float* out_boxes, float* out_scores,
+                      int32_t* out_labels) {
+    TRY(check_frame_args(m, frames, n, H, W, out_boxes, out_scores, out_labels));
+    if (ep < 0 || ep > m->n_exits) return fail(m, THIA_E_BADEP, "exit outside 0..n_exits");
+    if (n == 0) return THIA_OK;
+    if (ep == 0) {
+        HIP_TRY(m, launch_fill_empty(n, m->D, out_boxes, out_scores, out_labels, m->stream));
+        return THIA_OK;
+    }
+    return detect_frames(m, frames, n, H, W, ep, out_boxes, out_scores, out_labels);
+}
+
+int thia_run_plan(thia_model* m, const uint8_t* frames, int n_chunks, int chunk_len, int H, int W, const int32_t* chunk_ep,
+                  float* out_boxes, float* out_scores, int32_t* out_labels) {
+    if (!m) return THIA_E_BADARG;
+    if (n_chunks < 0 || chunk_len < 0 || (n_chunks > 0 && !chunk_ep)) return fail(m, THIA_E_BADARG, "bad plan arguments");
+    if ((long long)n_chunks * chunk_len > (1ll << 30)) return fail(m, THIA_E_BADARG, "plan too long");
+    TRY(check_frame_args(m, frames, n_chunks * chunk_len, H, W, out_boxes, out_scores, out_labels));
+    for (int c = 0; c < n_chunks; ++c)
+        if (chunk_ep[c] < 0 || chunk_ep[c] > m->n_exits) return fail(m, THIA_E_BADEP, "plan holds an exit outside 0..n_exits");
+    if (n_chunks == 0 || chunk_len == 0) return THIA_OK;
+    const int D = m->D;
+    const size_t fbytes = (size_t)3 * H * W;
+    // group chunks by exit: one group after the other on the one stream, outputs at the frames' own positions
+    for (int ep = 0; ep <= m->n_exits; ++ep)
+        for (int c = 0; c < n_chunks; ++c) {
+            if (chunk_ep[c] != ep) continue;
+            const size_t f0 = (size_t)c * chunk_len;
+            if (ep == 0) {
+                HIP_TRY(m, launch_fill_empty(chunk_len, D, out_boxes + f0 * D * 4, out_scores + f0 * D, out_labels + f0 * D, m->stream));
+            } else {
+                TRY(detect_frames(m, frames + f0 * fbytes, chunk_len, H, W, ep, out_boxes + f0 * D * 4, out_scores + f0 * D,
+                                  out_labels + f0 * D));
+            }
+        }
+    return THIA_OK;
+}
+
+const char* thia_last_error(const thia_model* m) { return m ? m->err.c_str() : "null model"; }
+
+int thia_set_debug(thia_model* m, int enable) {
+    if (!m) return THIA_E_BADARG;
+    m->debug = enable != 0;
+    return THIA_OK;
+}
+
+size_t thia_debug_tap_bytes(const thia_model* m, int which) {
+    if (!m || which < 0 || which >= THIA_TAP_COUNT) return 0;
+    return m->taps[which].bytes;
+}
+
+int thia_debug_tap(thia_model* m, int which, void* dst, size_t nbytes) {
+    if (!m || !dst) return THIA_E_BADARG;
+    if (which < 0 || which >= THIA_TAP_COUNT) return fail(m, THIA_E_BADARG, "unknown tap");
+    const Tap& t = m->taps[which];
+    if (!t.buf || t.bytes == 0) return fail(m, THIA_E_BADARG, "tap not recorded (call thia_set_debug first)");
+    if (nbytes != t.bytes) return fail(m, THIA_E_BADARG, "tap size mismatch");
+    HIP_TRY(m, hipStreamSynchronize(m->stream));
+    HIP_TRY(m, hipMemcpy(dst, t.buf, nbytes, hipMemcpyDeviceToHost));
+    return THIA_OK;
+}
+
+int thia_profile_begin(thia_model* m) {
+    if (!m) return THIA_E_BADARG;
+    HIP_TRY(m, hipStreamSynchronize(m->stream));
+    m->profiling = true;
+    m->ev_used = 0;
+    return THIA_OK;
+}
+
+int thia_profile_read(thia_model* m, float* ms, int32_t* launches) {
+    if (!m || !ms || !launches) return THIA_E_BADARG;
+    HIP_TRY(m, hipStreamSynchronize(m->stream));
+    for (int i = 0; i < THIA_K_COUNT; ++i) { ms[i] = 0.f; launches[i] = 0; }
+    for (size_t i = 0; i + 1 < m->ev_used; i += 2) {
+        float t = 0.f;
+        HIP_TRY(m, hipEventElapsedTime(&t, m->ev_pool[i], m->ev_pool[i + 1]));
+        const int c = m->ev_class[i / 2];
+        ms[c] += t;
+        launches[c] += 1;
+    }
+    m->ev_used = 0;
+    return THIA_OK;
+}
+
+int thia_profile_end(thia_model* m) {
+    if (!m) return THIA_E_BADARG;
+    m->profiling = false;
+    m->ev_used = 0;
+    return THIA_OK;
+}
+
+// ------------------------------------------------------------------ single steps
+int thia_op_rpn_proposals(thia_model* m, const float* logits, const float* deltas, int n, int H, int W, int ep, int32_t* out_idx,
+                          float* out_boxes, int32_t* out_n) {
+    if (!m || !logits || !deltas || !out_idx || !out_boxes || !out_n || n <= 0) return fail(m, THIA_E_BADARG, "bad arguments");
+    if (ep < 1 || ep > m->n_exits) return fail(m, THIA_E_BADEP, "exit outside 1..n_exits");
+    if (H < 32 || W < 32) return fail(m, THIA_E_SHAPE, "frame too small");
+    TRY(ensure_workspace(m, H, W));
+    const ExitGeom g = exit_geom(m, ep, H, W);
+    const long nA = (long)g.Hk * g.Wk * m->anc.n_sizes * m->anc.n_ratios;
+    for (int f0 = 0; f0 < n; f0 += m->ws.mb) {
+        const int nb = std::min(m->ws.mb, n - f0);
+        HIP_TRY(m, launch_rpn_proposals(logits + (size_t)f0 * nA, deltas + (size_t)f0 * nA * 4, nb, nA, m->pre, g.Wk, g.stride, (float)W,
+                                        (float)H, m->anc, m->ws.topk, out_idx + (size_t)f0 * m->pre, out_boxes + (size_t)f0 * m->pre * 4,
+                                        out_n + f0, m->stream));
+    }
+    return THIA_OK;
+}
+
+int thia_op_nms(thia_model* m, const float* boxes, const int32_t* counts, int n, int cap, float thr, int max_keep, int32_t* out_keep,
+                int32_t* out_n) {
+    if (!m || !boxes || !counts || !out_keep || !out_n || n <= 0) return fail(m, THIA_E_BADARG, "bad arguments");
+    if (cap < 1 || cap > 4096 || max_keep < 1 || max_keep > 4096) return fail(m, THIA_E_SHAPE, "cap and max_keep must be within 1..4096");
+    const int words = (cap + 63) / 64;
+    void* mask = nullptr;
+    if (hipMalloc(&mask, (size_t)n * cap * words * 8) != hipSuccess) return fail(m, THIA_E_NOMEM, "nms mask allocation failed");
+    hipError_t e = launch_nms(boxes, counts, n, cap, thr, max_keep, static_cast<uint64_t*>(mask), out_keep, out_n, nullptr, m->stream);
+    hipError_t e2 = hipStreamSynchronize(m->stream);
+    (void)hipFree(mask);
+    if (e != hipSuccess) return fail_hip(m, e, "launch_nms");
+    if (e2 != hipSuccess) return fail_hip(m, e2, "nms sync");
+    return THIA_OK;
+}
+
+int thia_op_roialign(thia_model* m, const void* feat, const float* rois, int n, int Hk, int Wk, int stride, void* out) {
+    if (!m || !feat || !rois || !out || n <= 0 || Hk <= 0 || Wk <= 0 || stride <= 0) return fail(m, THIA_E_BADARG, "bad arguments");
+    const int Ch = m->has_lateral ? m->head_ch : 0;
+    if (!Ch) return fail(m, THIA_E_SHAPE, "thia_op_roialign needs a model with a lateral (fixed head channels)");
+    HIP_TRY(m, launch_roialign(feat, rois, n, m->post, Hk, Wk, Ch, stride, m->pool, m->precision, out, m->stream));
+    return THIA_OK;
+}
+
+int thia_op_select_detections(thia_model* m, const float* scores, const float* boxes, const int32_t* roi_n, int n, float* out_boxes,
+                              float* out_scores, int32_t* out_labels, int32_t* out_n) {
+    if (!m || !scores || !boxes || !roi_n || !out_boxes || !out_scores || !out_labels || n <= 0) return fail(m, THIA_E_BADARG, "bad arguments");
+    const int key_cap = next_pow2(m->post * m->Kc);
+    void* keys = nullptr;
+    if (hipMalloc(&keys, (size_t)n * key_cap * 8) != hipSuccess) return fail(m, THIA_E_NOMEM, "key allocation failed");
+    hipError_t e = launch_select(scores, boxes, roi_n, n, m->post, m->Kc, m->score_thr, m->det_thr, m->D, static_cast<uint64_t*>(keys),
+                                 key_cap, out_boxes, out_scores, out_labels, out_n, m->stream);
+    hipError_t e2 = hipStreamSynchronize(m->stream);
+    (void)hipFree(keys);
+    if (e != hipSuccess) return fail_hip(m, e, "launch_select");
+    if (e2 != hipSuccess) return fail_hip(m, e2, "select sync");
+    return THIA_OK;
+}
+
+int thia_op_conv(thia_model* m, const void* in, int n, int H, int W, int Cin, const float* weights, const float* bias, int Cout, int k,
+                 int stride, int pad, const void* residual, int relu, int out_f32, void* out) {
+    if (!m || !in || !weights || !bias || !out || n <= 0 || H <= 0 || W <= 0 || Cout <= 0 || k <= 0 || stride <= 0 || pad < 0)
+        return fail(m, THIA_E_BADARG, "bad arguments");
+    if (Cin <= 0 || Cin % 64) return fail(m, THIA_E_SHAPE, "Cin must be a multiple of 64");
+    if (conv_out(H, k, stride, pad) <= 0 || conv_out(W, k, stride, pad) <= 0) return fail(m, THIA_E_SHAPE, "empty output");
+    HostLayer hl;
+    hl.w = weights; hl.b = bias; hl.co = Cout; hl.ci = Cin; hl.k = k;
+    Layer L;
+    int rc = upload_layer(m, hl, nullptr, L);
+    if (rc == THIA_OK) rc = run_conv(m, THIA_K_CONV, L, in, n, H, W, stride, pad, residual, relu != 0, out_f32 != 0, out);
+    hipError_t e2 = hipStreamSynchronize(m->stream);
+    free_layer(L);
+    if (rc != THIA_OK) return rc;
+    if (e2 != hipSuccess) return fail_hip(m, e2, "conv sync");
+    return THIA_OK;
+}
+
+int thia_op_stem(thia_model* m, const uint8_t* frames, int n, int H, int W, void* out) {
+    if (!m || !frames || !out || n <= 0) return fail(m, THIA_E_BADARG, "bad arguments");
+    if (H < 32 || W < 32) return fail(m, THIA_E_SHAPE, "frame too small");
+    const int Hs = conv_out(H, 7, 2, 3), Ws = conv_out(W, 7, 2, 3);
+    void* tmp = nullptr;
+    if (hipMalloc(&tmp, (size_t)n * Hs * Ws * 64 * m->esz) != hipSuccess) return fail(m, THIA_E_NOMEM, "stem scratch allocation failed");
+    hipError_t e = launch_stem(frames, n, H, W, m->stem_w, m->stem_b, m->mean, m->stdv, m->precision, tmp, m->stream);
+    if (e == hipSuccess) e = launch_maxpool(tmp, n, Hs, Ws, 64, m->precision, out, m->stream);
+    hipError_t e2 = hipStreamSynchronize(m->stream);
+    (void)hipFree(tmp);
+    if (e != hipSuccess) return fail_hip(m, e, "stem launch");
+    if (e2 != hipSuccess) return fail_hip(m, e2, "stem sync");
+    return THIA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,246 @@
+// ROI head kernels: ROIAlign gather on the NHWC head feature map, class scores and
+// per-class box decoding, and the final detection selection (threshold, ordering,
+// same-class greedy NMS, top-D).
+#include "device_util.h"
+
+namespace thia {
+
+// ------------------------------------------------------------------ ROIAlign
+// One block per ROI; threads run over channels, so every tap is one contiguous run of Ch
+// elements of the NHWC map.  The P*P*4 sample positions (4 texel offsets + 4 bilinear
+// weights each) are computed once per ROI into LDS.  Convention: texel j has centre
+// j + 0.5; a sample more than one texel outside the map contributes zero; otherwise its
+// coordinates are clamped to the texel-centre range.  Output layout [(ph*P + pw)][c].
+template <typename T>
+__global__ __launch_bounds__(256) void roialign_kernel(const T* __restrict__ feat, const float* __restrict__ rois, int post,
+                                                       int Hk, int Wk, int Ch, float scale, int P, T* __restrict__ out) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int ns = P * P * 4;
+    int* s_off = reinterpret_cast<int*>(smem_raw);             // [ns][4] texel offsets (in pixels of the map)
+    float* s_w = reinterpret_cast<float*>(s_off + 4 * ns);     // [ns][4]
+    const int roi = blockIdx.x, f = roi / post;
+    const float4 r = *reinterpret_cast<const float4*>(rois + 4 * (size_t)roi);
+    const float x1 = r.x * scale, y1 = r.y * scale;
+    const float bw = (r.z * scale - x1) / (float)P, bh = (r.w * scale - y1) / (float)P;
+    for (int s = threadIdx.x; s < ns; s += blockDim.x) {
+        const int bin = s >> 2, ph = bin / P, pw = bin - ph * P, iy = (s >> 1) & 1, ix = s & 1;
+        const float fy = y1 + (float)ph * bh + ((float)iy + 0.5f) * bh * 0.5f;
+        const float fx = x1 + (float)pw * bw + ((float)ix + 0.5f) * bw * 0.5f;
+        float u = fx - 0.5f, v = fy - 0.5f;
+        int o[4] = {0, 0, 0, 0};
+        float w[4] = {0.f, 0.f, 0.f, 0.f};
+        if (!(u < -1.f || u > (float)Wk || v < -1.f || v > (float)Hk)) {
+            u = fminf(fmaxf(u, 0.f), (float)(Wk - 1));
+            v = fminf(fmaxf(v, 0.f), (float)(Hk - 1));
+            const int x0 = (int)floorf(u), y0 = (int)floorf(v);
+            const int xb = x0 + 1 < Wk ? x0 + 1 : Wk - 1, yb = y0 + 1 < Hk ? y0 + 1 : Hk - 1;
+            const float lx = u - (float)x0, ly = v - (float)y0;
+            o[0] = y0 * Wk + x0; o[1] = y0 * Wk + xb; o[2] = yb * Wk + x0; o[3] = yb * Wk + xb;
+            w[0] = (1.f - ly) * (1.f - lx); w[1] = (1.f - ly) * lx; w[2] = ly * (1.f - lx); w[3] = ly * lx;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { s_off[4 * s + q] = o[q]; s_w[4 * s + q] = w[q]; }
+    }
+    __syncthreads();
+    const T* fm = feat + (size_t)f * Hk * Wk * Ch;
+    T* o = out + (size_t)roi * P * P * Ch;
+    for (int c = threadIdx.x; c < Ch; c += blockDim.x) {
+        for (int bin = 0; bin < P * P; ++bin) {
+            float sum = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int q = 4 * (4 * bin + s);
+                float a = 0.f;
+#pragma unroll
+                for (int tp = 0; tp < 4; ++tp) {
+                    float x;
+                    if constexpr (sizeof(T) == 2) x = bf16_to_f32(fm[(size_t)s_off[q + tp] * Ch + c]);
+                    else x = fm[(size_t)s_off[q + tp] * Ch + c];
+                    a += s_w[q + tp] * x;
+                }
+                sum += a;
+            }
+            const float val = sum * 0.25f;
+            if constexpr (sizeof(T) == 2) o[(size_t)bin * Ch + c] = f32_to_bf16(val);
+            else o[(size_t)bin * Ch + c] = val;
+        }
+    }
+}
+
+hipError_t launch_roialign(const void* feat, const float* rois, int n, int post, int Hk, int Wk, int Ch, int stride, int P,
+                           int precision, void* out, hipStream_t s) {
+    if (n <= 0 || post <= 0 || P <= 0 || P > 16) return hipErrorInvalidValue;
+    const size_t lds = (size_t)P * P * 4 * 4 * 8;
+    const float scale = 1.0f / (float)stride;
+    const unsigned blocks = (unsigned)n * (unsigned)post;
+    if (precision)
+        hipLaunchKernelGGL(roialign_kernel<bf16_t>, dim3(blocks), dim3(256), lds, s, static_cast<const bf16_t*>(feat), rois, post,
+                           Hk, Wk, Ch, scale, P, static_cast<bf16_t*>(out));
+    else
+        hipLaunchKernelGGL(roialign_kernel<float>, dim3(blocks), dim3(256), lds, s, static_cast<const float*>(feat), rois, post, Hk,
+                           Wk, Ch, scale, P, static_cast<float*>(out));
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ scores + per-class boxes
+// One thread per ROI: softmax over Kc logits (max subtracted) and, for every foreground
+// class, the ROI decoded with that class's deltas and clipped.
+__global__ void scores_boxes_kernel(const float* __restrict__ cls, const float* __restrict__ deltas,
+                                    const float* __restrict__ rois, int total, int Kc, float imgW, float imgH,
+                                    float* __restrict__ scores, float* __restrict__ boxes) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= total) return;
+    const float* x = cls + (size_t)r * Kc;
+    float mx = x[0];
+    for (int c = 1; c < Kc; ++c) mx = fmaxf(mx, x[c]);
+    float sum = 0.f;
+    for (int c = 0; c < Kc; ++c) sum += expf(x[c] - mx);
+    const float4 q = *reinterpret_cast<const float4*>(rois + 4 * (size_t)r);
+    const float rw = q.z - q.x, rh = q.w - q.y;
+    const float cx = q.x + 0.5f * rw, cy = q.y + 0.5f * rh;
+    for (int c = 0; c < Kc; ++c) {
+        scores[(size_t)r * Kc + c] = expf(x[c] - mx) / sum;
+        Box b = {0.f, 0.f, 0.f, 0.f};
+        if (c > 0) {
+            const float4 d = *reinterpret_cast<const float4*>(deltas + ((size_t)r * Kc + c) * 4);
+            decode_box(cx, cy, rw, rh, d.x, d.y, d.z, d.w, imgW, imgH, b);
+        }
+        *reinterpret_cast<float4*>(boxes + ((size_t)r * Kc + c) * 4) = make_float4(b.x1, b.y1, b.x2, b.y2);
+    }
+}
+
+hipError_t launch_scores_boxes(const float* cls, const float* deltas, const float* rois, int n, int post, int Kc, float imgW,
+                               float imgH, float* scores, float* boxes, hipStream_t s) {
+    const int total = n * post;
+    if (total <= 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(scores_boxes_kernel, dim3((total + 127) / 128), dim3(128), 0, s, cls, deltas, rois, total, Kc, imgW, imgH,
+                       scores, boxes);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ detection selection
+// One block per frame.  Candidates (roi < roi_n, class >= 1, score > thr, non-empty box)
+// get the key (order-preserving score) << 32 | (2^32 - 1 - (roi*Kc + class)); the keys are
+// sorted descending (LDS when they fit, else in the global scratch), then wavefront 0
+// runs greedy same-class NMS 64 candidates at a time against the list of kept boxes.
+constexpr int SEL_LDS_KEYS = 4096;
+constexpr int SEL_MAX_D = 512;
+
+__global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ scores, const float* __restrict__ boxes,
+                                                      const int32_t* __restrict__ roi_n, int post, int Kc, float score_thr,
+                                                      float nms_thr, int D, uint64_t* __restrict__ gkeys, int key_cap,
+                                                      float* __restrict__ out_boxes, float* __restrict__ out_scores,
+                                                      int32_t* __restrict__ out_labels, int32_t* __restrict__ out_n) {
+    __shared__ uint64_t lkeys[SEL_LDS_KEYS];
+    __shared__ Box kbox[SEL_MAX_D];
+    __shared__ int klab[SEL_MAX_D];
+    __shared__ float kscore[SEL_MAX_D];
+    __shared__ int s_count, s_nk;
+    const int f = blockIdx.x, t = threadIdx.x;
+    int nr = roi_n[f];
+    nr = nr < post ? nr : post;
+    const float* sc = scores + (size_t)f * post * Kc;
+    const float* bx = boxes + (size_t)f * post * Kc * 4;
+    uint64_t* gk = gkeys + (size_t)f * key_cap;
+    if (t == 0) { s_count = 0; s_nk = 0; }
+    __syncthreads();
+    const int total = nr * Kc;
+    for (int j = t; j < total; j += 1024) {
+        const int c = j % Kc;
+        if (c == 0) continue;
+        const float s = sc[j];
+        if (!(s > score_thr)) continue;
+        const float4 b = *reinterpret_cast<const float4*>(bx + 4 * (size_t)j);
+        if (!((b.z - b.x >= 1e-3f) && (b.w - b.y >= 1e-3f))) continue;
+        const int slot = atomicAdd(&s_count, 1);
+        gk[slot] = ((uint64_t)score_key(s) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)j);
+    }
+    __syncthreads();
+    const int nc = s_count;
+    int n2 = 1;
+    while (n2 < nc) n2 <<= 1;
+    uint64_t* keys;
+    if (n2 <= SEL_LDS_KEYS) {
+        for (int i = t; i < n2; i += 1024) lkeys[i] = i < nc ? gk[i] : 0ull;
+        keys = lkeys;
+    } else {
+        for (int i = nc + t; i < n2; i += 1024) gk[i] = 0ull;
+        keys = gk;
+    }
+    __syncthreads();
+    bitonic_sort_desc(keys, n2);
+
+    if (t < 64) {
+        const int lane = t;
+        int nk = 0;
+        for (int s0 = 0; s0 < nc && nk < D; s0 += 64) {
+            const int i = s0 + lane;
+            bool alive = i < nc;
+            Box me = {0.f, 0.f, 0.f, 0.f};
+            int lab = -1;
+            float myscore = 0.f;
+            if (alive) {
+                const uint64_t key = keys[i];
+                const uint32_t j = 0xFFFFFFFFu - (uint32_t)(key & 0xFFFFFFFFull);
+                const float4 b = *reinterpret_cast<const float4*>(bx + 4 * (size_t)j);
+                me = {b.x, b.y, b.z, b.w};
+                lab = (int)(j % (uint32_t)Kc);
+                myscore = key_score((uint32_t)(key >> 32));
+                for (int q = 0; q < nk; ++q)
+                    if (klab[q] == lab && iou_over(kbox[q], me, nms_thr)) { alive = false; break; }
+            }
+            for (int b = 0; b < 64 && nk < D; ++b) {
+                const int ab = __shfl((int)alive, b);
+                if (!ab) continue;
+                const Box kb = {__shfl(me.x1, b), __shfl(me.y1, b), __shfl(me.x2, b), __shfl(me.y2, b)};
+                const int kl = __shfl(lab, b);
+                const float ks = __shfl(myscore, b);
+                if (lane == 0) { kbox[nk] = kb; klab[nk] = kl; kscore[nk] = ks; }
+                ++nk;
+                if (lane > b && alive && lab == kl && iou_over(kb, me, nms_thr)) alive = false;
+            }
+            __builtin_amdgcn_wave_barrier();
+            __threadfence_block();
+        }
+        if (lane == 0) s_nk = nk;
+    }
+    __syncthreads();
+    const int nk = s_nk;
+    for (int d = t; d < D; d += 1024) {
+        float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+        float s = 0.f;
+        int l = -1;
+        if (d < nk) { b = make_float4(kbox[d].x1, kbox[d].y1, kbox[d].x2, kbox[d].y2); s = kscore[d]; l = klab[d]; }
+        *reinterpret_cast<float4*>(out_boxes + ((size_t)f * D + d) * 4) = b;
+        out_scores[(size_t)f * D + d] = s;
+        out_labels[(size_t)f * D + d] = l;
+    }
+    if (t == 0 && out_n) out_n[f] = nk;
+}
+
+hipError_t launch_select(const float* scores, const float* boxes, const int32_t* roi_n, int n, int post, int Kc,
+                         float score_thr, float nms_thr, int D, uint64_t* keys, int key_cap, float* out_boxes,
+                         float* out_scores, int32_t* out_labels, int32_t* out_n, hipStream_t s) {
+    if (n <= 0 || D <= 0 || D > SEL_MAX_D || key_cap < post * Kc) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(select_kernel, dim3(n), dim3(1024), 0, s, scores, boxes, roi_n, post, Kc, score_thr, nms_thr, D, keys,
+                       key_cap, out_boxes, out_scores, out_labels, out_n);
+    return hipGetLastError();
+}
+
+__global__ void fill_empty_kernel(int total, float* __restrict__ out_boxes, float* __restrict__ out_scores,
+                                  int32_t* __restrict__ out_labels) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    *reinterpret_cast<float4*>(out_boxes + 4 * (size_t)i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    out_scores[i] = 0.f;
+    out_labels[i] = -1;
+}
+
+hipError_t launch_fill_empty(int n, int D, float* out_boxes, float* out_scores, int32_t* out_labels, hipStream_t s) {
+    const int total = n * D;
+    if (total <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_empty_kernel, dim3((total + 255) / 256), dim3(256), 0, s, total, out_boxes, out_scores, out_labels);
+    return hipGetLastError();
+}
+
+}  // namespace thia

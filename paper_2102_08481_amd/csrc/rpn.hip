@@ -1,0 +1,286 @@
+// Proposal path of one exit: exact top-k of the RPN logits, anchor decoding, clipping
+// and greedy NMS.
+//
+// Top-k: an element's rank key is 54 bits = (order-preserving map of the logit) << 22 |
+// (2^22 - 1 - anchor index), so keys are unique and "largest key first" is exactly
+// (logit descending, index ascending).  The k-th largest key is found by a most-significant
+// -digit-first radix select (digits of 11,11,10,11,11 bits): each pass histograms, with
+// many blocks per frame and integer atomics only, the digit of the elements that still match
+// the prefix, then one block per frame picks the digit holding the k-th element.  A pass
+// ends the search early when the whole digit bucket is needed (always the case after
+// the three logit digits unless logits tie at the cut).  All elements with key >= the
+// threshold are then gathered (any order) and sorted by key in LDS with a bitonic network,
+// which makes the output order deterministic.  The same block decodes the k anchors and
+// compacts the non-empty boxes in order.
+//
+// NMS: a k x k upper-triangular overlap bit matrix (64-bit words) is computed by
+// 64-thread blocks, then one wavefront per frame scans it 64 rows at a time from LDS,
+// holding the "removed" bit vector one word per lane.
+#include "device_util.h"
+
+namespace thia {
+
+constexpr int IDX_BITS = 22;
+constexpr uint32_t IDX_MASK = (1u << IDX_BITS) - 1u;
+constexpr int N_PASS = 5;
+__host__ __device__ inline int pass_shift(int p) { return p == 0 ? 43 : p == 1 ? 32 : p == 2 ? 22 : p == 3 ? 11 : 0; }
+__host__ __device__ inline int pass_bits(int p) { return p == 2 ? 10 : 11; }
+constexpr int HIST_BINS = 2048;
+constexpr int HIST_CHUNK = 8192;  // elements per histogram block
+
+__device__ inline uint64_t rank_key(float logit, uint32_t idx) {
+    return ((uint64_t)score_key(logit) << IDX_BITS) | (uint64_t)(IDX_MASK - idx);
+}
+
+// state[f]: [0] prefix, [1] k remaining, [2] done, [3] gathered count
+__global__ void topk_init_kernel(uint32_t* hist, uint64_t* state, int k) {
+    const int f = blockIdx.x;
+    for (int i = threadIdx.x; i < HIST_BINS; i += blockDim.x) hist[(size_t)f * HIST_BINS + i] = 0u;
+    if (threadIdx.x == 0) {
+        state[4 * f + 0] = 0ull;
+        state[4 * f + 1] = (uint64_t)k;
+        state[4 * f + 2] = 0ull;
+        state[4 * f + 3] = 0ull;
+    }
+}
+
+__global__ __launch_bounds__(256) void topk_hist_kernel(const float* __restrict__ logits, long nA, int pass,
+                                                        uint32_t* __restrict__ hist, const uint64_t* __restrict__ state) {
+    const int f = blockIdx.y;
+    if (state[4 * f + 2]) return;
+    __shared__ uint32_t lh[HIST_BINS];
+    for (int i = threadIdx.x; i < HIST_BINS; i += 256) lh[i] = 0u;
+    __syncthreads();
+    const int shift = pass_shift(pass), bits = pass_bits(pass);
+    const uint64_t prefix = state[4 * f + 0];
+    const int hi_shift = shift + bits;  // bits above the current digit must equal the prefix
+    const long i0 = (long)blockIdx.x * HIST_CHUNK;
+    const long i1 = i0 + HIST_CHUNK < nA ? i0 + HIST_CHUNK : nA;
+    const float* lg = logits + (size_t)f * nA;
+    for (long i = i0 + threadIdx.x; i < i1; i += 256) {
+        const uint64_t key = rank_key(lg[i], (uint32_t)i);
+        if (pass == 0 || (key >> hi_shift) == (prefix >> hi_shift)) atomicAdd(&lh[(key >> shift) & ((1u << bits) - 1u)], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < HIST_BINS; i += 256)
+        if (lh[i]) atomicAdd(&hist[(size_t)f * HIST_BINS + i], lh[i]);
+}
+
+// One block per frame: find digit d with  #(digit > d) < k_rem <= #(digit >= d); clears the histogram.
+__global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ hist, uint64_t* __restrict__ state, int pass) {
+    const int f = blockIdx.x;
+    if (state[4 * f + 2]) return;  // uniform: written only by this block in earlier launches
+    __shared__ uint32_t part[256];
+    __shared__ uint32_t above[256];
+    const int t = threadIdx.x;
+    uint32_t h[8], sum = 0;
+    uint32_t* hf = hist + (size_t)f * HIST_BINS;
+    const uint32_t k_rem = (uint32_t)state[4 * f + 1];  // read before the barriers: written below by one thread
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { h[q] = hf[8 * t + q]; sum += h[q]; hf[8 * t + q] = 0u; }
+    part[t] = sum;
+    __syncthreads();
+    if (t == 0) {
+        uint32_t run = 0;
+        for (int i = 255; i >= 0; --i) { above[i] = run; run += part[i]; }
+    }
+    __syncthreads();
+    uint32_t run = above[t];  // elements in bins above this thread's 8 bins
+    for (int q = 7; q >= 0; --q) {
+        if (run < k_rem && k_rem <= run + h[q]) {
+            const uint64_t digit = (uint64_t)(8 * t + q);
+            state[4 * f + 0] |= digit << pass_shift(pass);
+            state[4 * f + 1] = (uint64_t)(k_rem - run);
+            if (h[q] == k_rem - run || pass == N_PASS - 1) state[4 * f + 2] = 1ull;
+        }
+        run += h[q];
+    }
+}
+
+__global__ __launch_bounds__(256) void topk_gather_kernel(const float* __restrict__ logits, long nA,
+                                                          uint64_t* __restrict__ state, uint64_t* __restrict__ cand, int cap) {
+    const int f = blockIdx.y;
+    const uint64_t thr = state[4 * f + 0];
+    const long i0 = (long)blockIdx.x * HIST_CHUNK;
+    const long i1 = i0 + HIST_CHUNK < nA ? i0 + HIST_CHUNK : nA;
+    const float* lg = logits + (size_t)f * nA;
+    for (long i = i0 + threadIdx.x; i < i1; i += 256) {
+        const uint64_t key = rank_key(lg[i], (uint32_t)i);
+        if (key >= thr) {
+            const unsigned long long slot = atomicAdd(reinterpret_cast<unsigned long long*>(&state[4 * f + 3]), 1ull);
+            if (slot < (unsigned long long)cap) cand[(size_t)f * cap + slot] = key;
+        }
+    }
+}
+
+// One block per frame: sort the gathered keys, emit indices, decode, clip, compact non-empty boxes.
+__global__ __launch_bounds__(1024) void topk_sort_decode_kernel(const uint64_t* __restrict__ cand, const uint64_t* __restrict__ state,
+                                                                int cap, int pre, long nA, const float* __restrict__ deltas,
+                                                                int Wk, int stride, float imgW, float imgH, AnchorSpec anc,
+                                                                int32_t* __restrict__ out_idx, float* __restrict__ out_boxes,
+                                                                int32_t* __restrict__ out_n) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint64_t* keys = reinterpret_cast<uint64_t*>(smem_raw);  // [cap]
+    __shared__ int wave_tot[16];
+    __shared__ int base_sh;
+    const int f = blockIdx.x, t = threadIdx.x;
+    int k = (int)state[4 * f + 3];
+    if (k > pre) k = pre;
+    for (int i = t; i < cap; i += 1024) keys[i] = i < k ? cand[(size_t)f * cap + i] : 0ull;
+    if (t == 0) base_sh = 0;
+    __syncthreads();
+    bitonic_sort_desc(keys, cap);
+
+    const int A = anc.n_sizes * anc.n_ratios;
+    const float* dl = deltas + (size_t)f * nA * 4;
+    for (int j0 = 0; j0 < pre; j0 += 1024) {
+        const int j = j0 + t;
+        bool ok = false;
+        Box b = {0.f, 0.f, 0.f, 0.f};
+        if (j < pre) {
+            int32_t idx = -1;
+            if (j < k) {
+                idx = (int32_t)(IDX_MASK - (uint32_t)(keys[j] & IDX_MASK));
+                const int a = idx % A, loc = idx / A, x = loc % Wk, y = loc / Wk;
+                const float size = anc.sizes[a / anc.n_ratios], sr = anc.sqrt_ratios[a % anc.n_ratios];
+                const float cx = ((float)x + 0.5f) * (float)stride, cy = ((float)y + 0.5f) * (float)stride;
+                const float w = size / sr, h = size * sr;
+                const float4 d = *reinterpret_cast<const float4*>(dl + 4 * (size_t)idx);
+                ok = decode_box(cx, cy, w, h, d.x, d.y, d.z, d.w, imgW, imgH, b);
+            }
+            out_idx[(size_t)f * pre + j] = idx;
+        }
+        // ordered compaction: position = valid boxes before j
+        const unsigned long long bal = __ballot(ok);
+        const int lane = t & 63, wv = t >> 6;
+        const int before = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_tot[wv] = __popcll(bal);
+        __syncthreads();
+        int off = base_sh;
+        for (int q = 0; q < wv; ++q) off += wave_tot[q];
+        if (ok) *reinterpret_cast<float4*>(out_boxes + ((size_t)f * pre + off + before) * 4) = make_float4(b.x1, b.y1, b.x2, b.y2);
+        __syncthreads();
+        if (t == 0) {
+            int tot = 0;
+            for (int q = 0; q < 16; ++q) tot += wave_tot[q];
+            base_sh += tot;
+        }
+        __syncthreads();
+    }
+    const int total = base_sh;
+    for (int j = total + t; j < pre; j += 1024)
+        *reinterpret_cast<float4*>(out_boxes + ((size_t)f * pre + j) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (t == 0) out_n[f] = total;
+}
+
+static int next_pow2(int v) {
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+hipError_t launch_rpn_proposals(const float* logits, const float* deltas, int n, long nA, int pre, int Wk, int stride,
+                                float imgW, float imgH, const AnchorSpec& anc, const TopkWork& work, int32_t* out_idx,
+                                float* out_boxes, int32_t* out_n, hipStream_t s) {
+    if (n <= 0 || nA <= 0 || nA > (long)IDX_MASK || pre <= 0 || pre > 4096) return hipErrorInvalidValue;
+    const int k = (long)pre < nA ? pre : (int)nA;
+    const int cap = next_pow2(pre);
+    const unsigned bpf = (unsigned)((nA + HIST_CHUNK - 1) / HIST_CHUNK);
+    if (n > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(topk_init_kernel, dim3(n), dim3(256), 0, s, work.hist, work.state, k);
+    for (int pass = 0; pass < N_PASS; ++pass) {
+        hipLaunchKernelGGL(topk_hist_kernel, dim3(bpf, n), dim3(256), 0, s, logits, nA, pass, work.hist, work.state);
+        hipLaunchKernelGGL(topk_scan_kernel, dim3(n), dim3(256), 0, s, work.hist, work.state, pass);
+    }
+    hipLaunchKernelGGL(topk_gather_kernel, dim3(bpf, n), dim3(256), 0, s, logits, nA, work.state, work.cand, cap);
+    hipLaunchKernelGGL(topk_sort_decode_kernel, dim3(n), dim3(1024), (size_t)cap * 8, s, work.cand, work.state, cap, pre, nA,
+                       deltas, Wk, stride, imgW, imgH, anc, out_idx, out_boxes, out_n);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------- NMS
+__global__ __launch_bounds__(64) void nms_mask_kernel(const float* __restrict__ boxes, const int32_t* __restrict__ counts,
+                                                      int cap, int words, float thr, uint64_t* __restrict__ mask) {
+    const int bx = blockIdx.x, by = blockIdx.y, f = blockIdx.z;
+    if (bx < by) return;
+    const int cnt = counts[f] < cap ? counts[f] : cap;
+    if (64 * by >= cnt || 64 * bx >= cnt) return;
+    __shared__ Box cb[64];
+    const int t = threadIdx.x;
+    const float* bf = boxes + (size_t)f * cap * 4;
+    const int cj = 64 * bx + t;
+    if (cj < cnt) {
+        const float4 v = *reinterpret_cast<const float4*>(bf + 4 * (size_t)cj);
+        cb[t] = {v.x, v.y, v.z, v.w};
+    }
+    __syncthreads();
+    const int i = 64 * by + t;
+    if (i >= cnt) return;
+    const float4 v = *reinterpret_cast<const float4*>(bf + 4 * (size_t)i);
+    const Box me = {v.x, v.y, v.z, v.w};
+    uint64_t bits = 0ull;
+    const int jn = (cnt - 64 * bx) < 64 ? (cnt - 64 * bx) : 64;
+    for (int b = 0; b < jn; ++b) {
+        const int j = 64 * bx + b;
+        if (j > i && iou_over(me, cb[b], thr)) bits |= 1ull << b;
+    }
+    mask[((size_t)f * cap + i) * words + bx] = bits;
+}
+
+// One wavefront per frame.  Lane w holds word w of the "removed" set (words <= 64).
+__global__ __launch_bounds__(64) void nms_reduce_kernel(const uint64_t* __restrict__ mask, const float* __restrict__ boxes,
+                                                        const int32_t* __restrict__ counts, int cap, int words, int max_keep,
+                                                        int32_t* __restrict__ out_keep, int32_t* __restrict__ out_n,
+                                                        float* __restrict__ rois_out) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint64_t* tile = reinterpret_cast<uint64_t*>(smem_raw);              // [64][words]
+    int32_t* keep = reinterpret_cast<int32_t*>(tile + (size_t)64 * words);  // [max_keep]
+    const int f = blockIdx.x, lane = threadIdx.x;
+    const int cnt = counts[f] < cap ? counts[f] : cap;
+    const int wc = (cnt + 63) / 64;
+    const uint64_t* mf = mask + (size_t)f * cap * words;
+    uint64_t removed = 0ull;
+    int nk = 0;
+    for (int c = 0; c < wc && nk < max_keep; ++c) {
+        const int rows = (cnt - 64 * c) < 64 ? (cnt - 64 * c) : 64;
+        if (lane < words)
+            for (int r = 0; r < rows; ++r)
+                tile[(size_t)r * words + lane] = (lane >= c && lane < wc) ? mf[(size_t)(64 * c + r) * words + lane] : 0ull;
+        __syncthreads();
+        uint64_t cur = __shfl(removed, c);
+        for (int b = 0; b < rows; ++b) {
+            if ((cur >> b) & 1ull) continue;
+            if (lane == 0) keep[nk] = 64 * c + b;
+            ++nk;
+            if (lane < words) removed |= tile[(size_t)b * words + lane];
+            cur |= tile[(size_t)b * words + c];
+            if (nk == max_keep) break;
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+    const float* bf = boxes + (size_t)f * cap * 4;
+    for (int j = lane; j < max_keep; j += 64) {
+        const int src = j < nk ? keep[j] : -1;
+        out_keep[(size_t)f * max_keep + j] = src;
+        if (rois_out) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (src >= 0) v = *reinterpret_cast<const float4*>(bf + 4 * (size_t)src);
+            *reinterpret_cast<float4*>(rois_out + ((size_t)f * max_keep + j) * 4) = v;
+        }
+    }
+    if (lane == 0) out_n[f] = nk;
+}
+
+hipError_t launch_nms(const float* boxes, const int32_t* counts, int n, int cap, float thr, int max_keep, uint64_t* mask,
+                      int32_t* out_keep, int32_t* out_n, float* rois_out, hipStream_t s) {
+    if (n <= 0 || cap <= 0 || cap > 4096 || max_keep <= 0 || max_keep > 4096 || n > 65535) return hipErrorInvalidValue;
+    const int words = (cap + 63) / 64;
+    hipLaunchKernelGGL(nms_mask_kernel, dim3(words, words, n), dim3(64), 0, s, boxes, counts, cap, words, thr, mask);
+    const size_t lds = (size_t)64 * words * 8 + (size_t)max_keep * 4;
+    hipLaunchKernelGGL(nms_reduce_kernel, dim3(n), dim3(64), lds, s, mask, boxes, counts, cap, words, max_keep, out_keep, out_n,
+                       rois_out);
+    return hipGetLastError();
+}
+
+}  // namespace thia

@@ -1,0 +1,159 @@
+// Backbone entry: pixel normalisation fused into the 7x7 stride-2 stem convolution
+// (+ bias, ReLU), and the 3x3 stride-2 max-pool.  Input frames are planar uint8
+// [n,3,H,W]; outputs are NHWC.
+//
+// The stem contracts only K = 3*7*7 = 147 values per output, so it runs on the vector
+// ALUs: a 256-thread block owns a 16x16 tile of output pixels, stages the normalised
+// 37x37x3 input patch in LDS once, and every thread accumulates all 64 output channels of
+// its pixel in registers.  Weights are indexed uniformly across the wavefront, so they
+// are fetched through the scalar path rather than per lane.
+#include "thia_internal.h"
+
+namespace thia {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+constexpr int ST = 16;               // output tile side
+constexpr int SP = 2 * ST + 5;       // input patch side (stride 2, 7 taps)
+constexpr int SC = 64;               // stem output channels
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void stem_kernel(const uint8_t* __restrict__ frames, int H, int W, int Hs, int Ws,
+                                                   const float* __restrict__ w, const float* __restrict__ bias,
+                                                   float mean, float stdv, void* __restrict__ out_) {
+    __shared__ float patch[3][SP][SP + 1];
+    const int t = threadIdx.x, tx = t & (ST - 1), ty = t / ST;
+    const int ox0 = blockIdx.x * ST, oy0 = blockIdx.y * ST, img = blockIdx.z;
+    const int ix0 = 2 * ox0 - 3, iy0 = 2 * oy0 - 3;
+    const uint8_t* f = frames + (size_t)img * 3 * H * W;
+    for (int i = t; i < 3 * SP * SP; i += 256) {
+        const int c = i / (SP * SP), r = i - c * SP * SP, py = r / SP, px = r - py * SP;
+        const int iy = iy0 + py, ix = ix0 + px;
+        float v = 0.f;  // zero padding applies to the normalised tensor
+        if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) {
+            v = ((float)f[((size_t)c * H + iy) * W + ix] - mean) / stdv;
+            if (BF16) v = bf16_to_f32(f32_to_bf16(v));
+        }
+        patch[c][py][px] = v;
+    }
+    __syncthreads();
+
+    float acc[SC];
+#pragma unroll
+    for (int ch = 0; ch < SC; ++ch) acc[ch] = 0.f;
+    for (int c = 0; c < 3; ++c)
+        for (int ky = 0; ky < 7; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < 7; ++kx) {
+                const float x = patch[c][2 * ty + ky][2 * tx + kx];
+                const float* wt = w + ((c * 7 + ky) * 7 + kx) * SC;
+#pragma unroll
+                for (int ch = 0; ch < SC; ++ch) acc[ch] = fmaf(x, wt[ch], acc[ch]);
+            }
+
+    const int oy = oy0 + ty, ox = ox0 + tx;
+    if (oy >= Hs || ox >= Ws) return;
+    const size_t o = (((size_t)img * Hs + oy) * Ws + ox) * SC;
+    if (BF16) {
+        bf16_t* out = static_cast<bf16_t*>(out_) + o;
+#pragma unroll
+        for (int ch = 0; ch < SC; ch += 8) {
+            u32x4_t v;
+            uint32_t h[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) h[q] = f32_to_bf16(fmaxf(acc[ch + q] + bias[ch + q], 0.f));
+            v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16); v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
+            *reinterpret_cast<u32x4_t*>(out + ch) = v;
+        }
+    } else {
+        float* out = static_cast<float*>(out_) + o;
+#pragma unroll
+        for (int ch = 0; ch < SC; ch += 4) {
+            f32x4_t v = {fmaxf(acc[ch] + bias[ch], 0.f), fmaxf(acc[ch + 1] + bias[ch + 1], 0.f),
+                         fmaxf(acc[ch + 2] + bias[ch + 2], 0.f), fmaxf(acc[ch + 3] + bias[ch + 3], 0.f)};
+            *reinterpret_cast<f32x4_t*>(out + ch) = v;
+        }
+    }
+}
+
+hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const float* bias, float mean, float stdv,
+                       int precision, void* out, hipStream_t s) {
+    const int Hs = (H + 6 - 7) / 2 + 1, Ws = (W + 6 - 7) / 2 + 1;
+    dim3 grid((Ws + ST - 1) / ST, (Hs + ST - 1) / ST, n);
+    if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
+    if (precision)
+        hipLaunchKernelGGL(stem_kernel<true>, grid, dim3(256), 0, s, frames, H, W, Hs, Ws, w, bias, mean, stdv, out);
+    else
+        hipLaunchKernelGGL(stem_kernel<false>, grid, dim3(256), 0, s, frames, H, W, Hs, Ws, w, bias, mean, stdv, out);
+    return hipGetLastError();
+}
+
+// 3x3 / stride 2 / pad 1 max-pool, NHWC; one thread per 16-byte channel chunk of an output pixel.
+template <bool BF16>
+__global__ void maxpool_kernel(const void* __restrict__ in_, int n, int H, int W, int C, int Ho, int Wo,
+                               void* __restrict__ out_) {
+    constexpr int EPC = BF16 ? 8 : 4;
+    const int chunks = C / EPC;
+    const size_t total = (size_t)n * Ho * Wo * chunks;
+    const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int ck = (int)(gid % chunks);
+    size_t r = gid / chunks;
+    const int ox = (int)(r % Wo); r /= Wo;
+    const int oy = (int)(r % Ho);
+    const int img = (int)(r / Ho);
+    float best[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) best[q] = -INFINITY;
+    for (int ky = 0; ky < 3; ++ky) {
+        const int iy = 2 * oy - 1 + ky;
+        if ((unsigned)iy >= (unsigned)H) continue;
+        for (int kx = 0; kx < 3; ++kx) {
+            const int ix = 2 * ox - 1 + kx;
+            if ((unsigned)ix >= (unsigned)W) continue;
+            const size_t off = (((size_t)img * H + iy) * W + ix) * C + (size_t)ck * EPC;
+            if (BF16) {
+                const u32x4_t v = *reinterpret_cast<const u32x4_t*>(static_cast<const bf16_t*>(in_) + off);
+                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    best[2 * q] = fmaxf(best[2 * q], __uint_as_float(wv[q] << 16));
+                    best[2 * q + 1] = fmaxf(best[2 * q + 1], __uint_as_float(wv[q] & 0xffff0000u));
+                }
+            } else {
+                const f32x4_t v = *reinterpret_cast<const f32x4_t*>(static_cast<const float*>(in_) + off);
+                best[0] = fmaxf(best[0], v.x); best[1] = fmaxf(best[1], v.y);
+                best[2] = fmaxf(best[2], v.z); best[3] = fmaxf(best[3], v.w);
+            }
+        }
+    }
+    const size_t o = (((size_t)img * Ho + oy) * Wo + ox) * C + (size_t)ck * EPC;
+    if (BF16) {
+        u32x4_t v;
+        uint32_t h[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) h[q] = __float_as_uint(best[q]) >> 16;  // values are bf16 already
+        v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16); v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
+        *reinterpret_cast<u32x4_t*>(static_cast<bf16_t*>(out_) + o) = v;
+    } else {
+        f32x4_t v = {best[0], best[1], best[2], best[3]};
+        *reinterpret_cast<f32x4_t*>(static_cast<float*>(out_) + o) = v;
+    }
+}
+
+hipError_t launch_maxpool(const void* in, int n, int H, int W, int C, int precision, void* out, hipStream_t s) {
+    const int Ho = (H + 2 - 3) / 2 + 1, Wo = (W + 2 - 3) / 2 + 1;
+    const int epc = precision ? 8 : 4;
+    if (C % epc) return hipErrorInvalidValue;
+    const size_t total = (size_t)n * Ho * Wo * (C / epc);
+    const size_t blocks = (total + 255) / 256;
+    if (blocks == 0 || blocks >= (1ull << 31)) return hipErrorInvalidValue;
+    if (precision)
+        hipLaunchKernelGGL(maxpool_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, in, n, H, W, C, Ho, Wo, out);
+    else
+        hipLaunchKernelGGL(maxpool_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, in, n, H, W, C, Ho, Wo, out);
+    return hipGetLastError();
+}
+
+}  // namespace thia

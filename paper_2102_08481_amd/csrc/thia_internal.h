@@ -1,0 +1,87 @@
+// Internal declarations shared by the HIP translation units of libthia.
+// gfx950 (CDNA4) only.  No part of this library depends on the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace thia {
+
+// ---------------------------------------------------------------- element helpers
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+__host__ __device__ inline bf16_t f32_to_bf16(float x) {
+    union { float f; uint32_t u; } v;
+    v.f = x;
+    uint32_t u = v.u;
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);                                           // round to nearest even
+    return (bf16_t)(u >> 16);
+}
+__host__ __device__ inline float bf16_to_f32(bf16_t h) {
+    union { float f; uint32_t u; } v;
+    v.u = ((uint32_t)h) << 16;
+    return v.f;
+}
+
+// ---------------------------------------------------------------- convolution (implicit GEMM)
+// NHWC activations; weights [Cout][kh][kw][Cin] (K contiguous per output channel).
+// out[m, n] = act(bias[n] + sum_k W[n, k] * im2col(in)[m, k] + res[m, n]),  m = (img, oy, ox).
+// Output columns n < n_split go to out0 (row stride ld0), the others to out1 (row stride ld1).
+struct ConvArgs {
+    const void* in;
+    const void* w;
+    const float* bias;
+    const void* res;  // may be null
+    void* out0;
+    void* out1;       // == nullptr unless the output is split
+    int N, H, W, Cin, Ho, Wo, Cout, kh, kw, stride, pad;
+    int relu, n_split, ld0, ld1;
+};
+// precision 0: float tensors, fp32 MFMA; 1: bf16 tensors, bf16 MFMA with fp32 accumulation.
+// out_f32: store float outputs even when tensors are bf16.  Returns hipSuccess or the launch error.
+hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream_t s);
+// Shapes the kernel accepts.
+bool conv_supported(const ConvArgs& a, int precision);
+
+// ---------------------------------------------------------------- stem + pool
+// frames u8 [n,3,H,W]; w fp32 [(c*7+ky)*7+kx][64] (bf16-representable values when precision == 1);
+// out T [n,Hs,Ws,64] NHWC with ReLU applied.  x = (u8 - mean) / stdv, zero padding after normalisation.
+hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const float* bias, float mean,
+                       float stdv, int precision, void* out, hipStream_t s);
+hipError_t launch_maxpool(const void* in, int n, int H, int W, int C, int precision, void* out, hipStream_t s);
+
+// ---------------------------------------------------------------- RPN proposal path
+struct AnchorSpec {
+    int n_sizes, n_ratios;
+    float sizes[8];
+    float sqrt_ratios[4];
+};
+struct TopkWork {          // device scratch for n frames
+    uint32_t* hist;        // [n][2048]
+    uint64_t* state;       // [n][4]: prefix key, k remaining, done flag, collected count
+    uint64_t* cand;        // [n][cap_pow2]
+};
+// logits [n,nA]; deltas [n,nA,4]; out_idx [n,pre] (-1 pad); out_boxes [n,pre,4] (0 pad); out_n [n].
+hipError_t launch_rpn_proposals(const float* logits, const float* deltas, int n, long nA, int pre, int Wk, int stride,
+                                float imgW, float imgH, const AnchorSpec& anc, const TopkWork& work, int32_t* out_idx,
+                                float* out_boxes, int32_t* out_n, hipStream_t s);
+// boxes [n,cap,4], counts [n]; mask scratch [n][cap][ceil(cap/64)] u64; out_keep [n,max_keep] (-1 pad), out_n [n];
+// rois_out (optional) [n,max_keep,4] gets the kept boxes, zero padded.
+hipError_t launch_nms(const float* boxes, const int32_t* counts, int n, int cap, float thr, int max_keep, uint64_t* mask,
+                      int32_t* out_keep, int32_t* out_n, float* rois_out, hipStream_t s);
+
+// ---------------------------------------------------------------- ROI head
+hipError_t launch_roialign(const void* feat, const float* rois, int n, int post, int Hk, int Wk, int Ch, int stride, int P,
+                           int precision, void* out, hipStream_t s);
+// cls [n*post,Kc] logits, deltas [n*post,4Kc], rois [n,post,4] -> scores [n,post,Kc], boxes [n,post,Kc,4]
+hipError_t launch_scores_boxes(const float* cls, const float* deltas, const float* rois, int n, int post, int Kc, float imgW,
+                               float imgH, float* scores, float* boxes, hipStream_t s);
+// keys scratch [n][pow2 >= post*Kc] u64
+hipError_t launch_select(const float* scores, const float* boxes, const int32_t* roi_n, int n, int post, int Kc,
+                         float score_thr, float nms_thr, int D, uint64_t* keys, int key_cap, float* out_boxes,
+                         float* out_scores, int32_t* out_labels, int32_t* out_n, hipStream_t s);
+// fills the empty pattern for n frames
+hipError_t launch_fill_empty(int n, int D, float* out_boxes, float* out_scores, int32_t* out_labels, hipStream_t s);
+
+}  // namespace thia

@@ -1,0 +1,229 @@
+"""Step-level parity on the GPU: every kernel of the path is fed the ORACLE's upstream
+tensor through the C ABI (thia_op_*) and compared with the oracle's downstream tensor.
+Orderings, indices and NMS keeps must be bit-exact; floating-point tensors within the
+tolerance written next to each check."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_common import MINI_BF16, MINI_FP32, gpu_model, nchw_to_nhwc, nhwc_to_nchw, relerr, to_dev
+from thia_synth import CONFIGS, SceneSpec, make_frames
+
+pytestmark = pytest.mark.gpu
+
+# fp32 tensors: fp32 MFMA accumulation against double accumulation -> 1e-4 (the stated bar);
+# bf16 tensors against the oracle in bf16-storage mode: one bf16 rounding of the output
+# (2^-9 relative) may flip where fp32 and double sums straddle a rounding boundary -> 2^-8.
+TOL_F32 = 1e-4
+TOL_BF16_STEP = 2.0 ** -8
+
+
+def _model(precision):
+    return gpu_model(MINI_BF16 if precision else MINI_FP32, 0xBEEF + 50 + precision)
+
+
+def _bf16(x):
+    return torch.from_numpy(np.asarray(x, np.float32)).to(torch.bfloat16).float().numpy()
+
+
+@pytest.mark.parametrize("precision", [0, 1])
+@pytest.mark.parametrize("case", [
+    dict(n=2, H=13, W=17, Cin=64, Cout=64, k=1, stride=1, pad=0),        # narrow tile, ragged M (442 rows)
+    dict(n=3, H=20, W=23, Cin=64, Cout=256, k=1, stride=1, pad=0),       # several M tiles + tail
+    dict(n=2, H=19, W=21, Cin=64, Cout=64, k=3, stride=1, pad=1),        # 3x3 borders
+    dict(n=2, H=19, W=22, Cin=128, Cout=128, k=3, stride=2, pad=1),      # strided 3x3, odd/even sizes
+    dict(n=2, H=17, W=16, Cin=256, Cout=512, k=1, stride=2, pad=0),      # strided 1x1 shortcut
+    dict(n=1, H=9, W=11, Cin=256, Cout=75, k=1, stride=1, pad=0),        # Cout not a multiple of 4 (scalar epilogue)
+    dict(n=300, H=1, W=1, Cin=1024, Cout=40, k=1, stride=1, pad=0),      # FC-shaped, narrow
+    dict(n=1, H=1, W=1, Cin=64, Cout=64, k=1, stride=1, pad=0),          # single row
+])
+def test_conv_op_matches_oracle(precision, case):
+    m, _ = _model(precision)
+    c = dict(case)
+    rs = np.random.RandomState(c["H"] * 31 + c["Cout"])
+    x = rs.randn(c["n"], c["Cin"], c["H"], c["W"]).astype(np.float32)
+    w = (rs.randn(c["Cout"], c["Cin"], c["k"], c["k"]) * np.sqrt(2.0 / (c["Cin"] * c["k"] ** 2))).astype(np.float32)
+    b = rs.randn(c["Cout"]).astype(np.float32) * 0.1
+    if precision:
+        x = _bf16(x)
+    Ho = (c["H"] + 2 * c["pad"] - c["k"]) // c["stride"] + 1
+    Wo = (c["W"] + 2 * c["pad"] - c["k"]) // c["stride"] + 1
+    res = rs.randn(c["n"], c["Cout"], Ho, Wo).astype(np.float32)
+    if precision:
+        res = _bf16(res)
+    xd = to_dev(nchw_to_nhwc(x), m.elem)
+    rd = to_dev(nchw_to_nhwc(res), m.elem)
+    for (use_res, relu, out_f32) in [(False, False, False), (True, True, False), (False, False, True)]:
+        ref = oracle.conv2d(x, w, b, stride=c["stride"], pad=c["pad"], residual=res if use_res else None, relu=relu,
+                            bf16_weights=precision, round_out=int(bool(precision) and not out_f32))
+        got = m.op_conv(xd, w, b, stride=c["stride"], pad=c["pad"], residual=rd if use_res else None, relu=relu, out_f32=out_f32)
+        torch.cuda.synchronize()
+        got = nhwc_to_nchw(got.float().cpu().numpy())
+        assert got.shape == ref.shape
+        tol = TOL_BF16_STEP if (precision and not out_f32) else TOL_F32
+        assert relerr(got, ref) <= tol, (case, use_res, relu, out_f32, relerr(got, ref))
+
+
+@pytest.mark.parametrize("precision", [0, 1])
+def test_stem_op_matches_oracle(precision):
+    m, blob = _model(precision)
+    spec = MINI_BF16 if precision else MINI_FP32
+    from thia_synth import split_blob
+    w = split_blob(spec, blob)
+    frames = make_frames(SceneSpec(70, 93, 3, 3, 6, 8, 40), 5)        # odd sizes: ragged 16x16 tiles
+    x = oracle.normalize(frames, spec.mean, spec.std, bf16=precision)
+    y = oracle.conv2d(x, w["stem.w"], w["stem.b"], stride=2, pad=3, relu=True, bf16_weights=precision, round_out=precision)
+    ref = oracle.maxpool3x3s2(y)
+    got = m.op_stem(to_dev(frames))
+    torch.cuda.synchronize()
+    got = nhwc_to_nchw(got.float().cpu().numpy())
+    assert got.shape == ref.shape
+    assert relerr(got, ref) <= (TOL_BF16_STEP if precision else TOL_F32), relerr(got, ref)
+
+
+def _rand_boxes(rs, n, size):
+    x1 = rs.rand(n) * size
+    y1 = rs.rand(n) * size
+    w = 2 + rs.rand(n) * size / 3
+    h = 2 + rs.rand(n) * size / 3
+    return np.stack([x1, y1, x1 + w, y1 + h], 1).astype(np.float32)
+
+
+def test_nms_op_is_bit_exact():
+    m, _ = _model(0)
+    rs = np.random.RandomState(3)
+    cap = 1000
+    counts = np.array([1000, 0, 1, 64, 65, 999, 513, 128], np.int32)
+    boxes = np.zeros((len(counts), cap, 4), np.float32)
+    for f, c in enumerate(counts):
+        boxes[f, :c] = _rand_boxes(rs, c, 120.0 if f % 2 == 0 else 400.0)
+    boxes[5, 10:20] = boxes[5, 0]                      # exact duplicates: lowest index wins
+    for thr, max_keep in [(0.7, 300), (0.5, 1000), (0.3, 7)]:
+        keep, cnt = m.op_nms(to_dev(boxes), to_dev(counts), thr, max_keep)
+        torch.cuda.synchronize()
+        keep, cnt = keep.cpu().numpy(), cnt.cpu().numpy()
+        for f, c in enumerate(counts):
+            ref = oracle.nms(boxes[f, :c], thr, max_keep)
+            assert cnt[f] == len(ref), (thr, f)
+            assert np.array_equal(keep[f, :len(ref)], ref), (thr, f)
+            assert np.all(keep[f, len(ref):] == -1)
+
+
+def test_nms_op_large_cap():
+    m, _ = _model(0)
+    rs = np.random.RandomState(4)
+    cap = 2000
+    counts = np.array([2000, 1937], np.int32)
+    boxes = np.zeros((2, cap, 4), np.float32)
+    for f, c in enumerate(counts):
+        boxes[f, :c] = _rand_boxes(rs, c, 300.0)
+    keep, cnt = m.op_nms(to_dev(boxes), to_dev(counts), 0.7, 1000)
+    torch.cuda.synchronize()
+    for f, c in enumerate(counts):
+        ref = oracle.nms(boxes[f, :c], 0.7, 1000)
+        assert cnt[f].item() == len(ref) and np.array_equal(keep[f, :len(ref)].cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("precision", [0, 1])
+def test_rpn_proposals_op_matches_oracle(precision):
+    """Top-k indices are bit-exact on identical logits (including ties and signed zeros);
+    decoded boxes differ only by the exp() implementation."""
+    m, blob = _model(precision)
+    spec = MINI_BF16 if precision else MINI_FP32
+    orc = oracle.Model(blob)
+    H, W, ep = 160, 224, 2
+    Ck, Hk, Wk, stride = orc.exit_shape(ep, H, W)
+    nA = Hk * Wk * spec.n_anchors
+    rs = np.random.RandomState(7)
+    n = 5
+    logits = rs.randn(n, nA).astype(np.float32)
+    logits[1] = np.round(logits[1] * 2) / 2          # heavy ties across the cut
+    logits[2] = 0.0                                   # all equal: the first k indices win
+    logits[2, ::3] = -0.0
+    logits[3, : nA // 2] = -5.0                       # ties below the cut only
+    deltas = (rs.randn(n, nA, 4) * 0.5).astype(np.float32)
+    deltas[4, :, 2:] = -30.0                          # every box collapses: all dropped
+    deltas[0, ::5, 0] = 50.0                          # pushed outside the frame: dropped
+    idx, boxes, cnt = m.op_rpn_proposals(to_dev(logits), to_dev(deltas), H, W, ep)
+    torch.cuda.synchronize()
+    idx, boxes, cnt = idx.cpu().numpy(), boxes.cpu().numpy(), cnt.cpu().numpy()
+    for f in range(n):
+        ridx, _ = oracle.topk(logits[f], spec.pre_nms)
+        assert np.array_equal(idx[f, :len(ridx)], ridx), f
+        assert np.all(idx[f, len(ridx):] == -1)
+        ref = []
+        for i in ridx:
+            bx, ok = oracle.decode(orc.anchor(i, Wk, stride), deltas[f, i], W, H)
+            if ok:
+                ref.append(bx)
+        ref = np.array(ref, np.float32).reshape(-1, 4)
+        assert cnt[f] == len(ref), (f, cnt[f], len(ref))
+        if len(ref):
+            assert np.max(np.abs(boxes[f, :len(ref)] - ref)) <= 1e-5 * max(H, W) * 4
+        assert np.all(boxes[f, len(ref):] == 0)
+    assert cnt[4] == 0 and cnt[2] > 0
+
+
+def test_rpn_proposals_fewer_anchors_than_k():
+    m, blob = _model(0)                                # pre_nms 300, smallest map: 1x1..: use ep 4 on a 64x64 frame
+    orc = oracle.Model(blob)
+    H = W = 64
+    Ck, Hk, Wk, stride = orc.exit_shape(4, H, W)
+    nA = Hk * Wk * MINI_FP32.n_anchors
+    assert nA < MINI_FP32.pre_nms
+    rs = np.random.RandomState(8)
+    logits = rs.randn(2, nA).astype(np.float32)
+    deltas = (rs.randn(2, nA, 4) * 0.1).astype(np.float32)
+    idx, boxes, cnt = m.op_rpn_proposals(to_dev(logits), to_dev(deltas), H, W, 4)
+    torch.cuda.synchronize()
+    for f in range(2):
+        ridx, _ = oracle.topk(logits[f], MINI_FP32.pre_nms)
+        assert len(ridx) == nA and np.array_equal(idx[f, :nA].cpu().numpy(), ridx)
+        assert np.all(idx[f, nA:].cpu().numpy() == -1)
+
+
+@pytest.mark.parametrize("precision", [0, 1])
+def test_roialign_op_matches_oracle(precision):
+    m, _ = _model(precision)
+    spec = MINI_BF16 if precision else MINI_FP32
+    rs = np.random.RandomState(9)
+    n, Hk, Wk, Ch, stride = 2, 23, 31, spec.head_ch, 8
+    feat = rs.randn(n, Ch, Hk, Wk).astype(np.float32)
+    if precision:
+        feat = _bf16(feat)
+    post = spec.post_nms
+    rois = np.zeros((n, post, 4), np.float32)
+    rois[:, : post - 5] = _rand_boxes(rs, n * (post - 5), Wk * stride * 0.8).reshape(n, post - 5, 4)
+    rois[0, 0] = [0, 0, Wk * stride, Hk * stride]                   # whole map, samples at the borders
+    rois[0, 1] = [Wk * stride - 1.5, Hk * stride - 2.5, Wk * stride, Hk * stride]
+    rois[0, 2] = [3.3, 4.4, 3.9, 5.0]                                # tiny box inside one texel
+    out = m.op_roialign(to_dev(nchw_to_nhwc(feat), m.elem), to_dev(rois), stride)
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy()                                  # [n, post, P*P, Ch]
+    P = spec.pool
+    for f in range(n):
+        ref = oracle.roialign(feat[f], rois[f], stride, P, 2, round_out=precision)     # [post, Ch, P, P]
+        ref = np.transpose(ref.reshape(post, Ch, P * P), (0, 2, 1))
+        assert relerr(out[f], ref) <= (TOL_BF16_STEP if precision else 1e-5), relerr(out[f], ref)
+
+
+def test_select_detections_op_is_bit_exact():
+    m, _ = _model(1)
+    spec = MINI_BF16
+    rs = np.random.RandomState(10)
+    n, post, Kc, D = 4, spec.post_nms, spec.n_classes, spec.max_det
+    scores = rs.dirichlet(np.ones(Kc) * 0.7, size=(n, post)).astype(np.float32)
+    scores[1] = np.round(scores[1] * 16) / 16                        # many equal scores: index order decides
+    boxes = _rand_boxes(rs, n * post * Kc, 500.0).reshape(n, post, Kc, 4)
+    boxes[0, :40, 3] = boxes[0, :40, 3]
+    boxes[2, ::7, 2, 2] = boxes[2, ::7, 2, 0]                        # empty boxes are never candidates
+    roi_n = np.array([post, post - 17, 3, 0], np.int32)
+    ob, osc, ol, cnt = m.op_select_detections(to_dev(scores), to_dev(boxes), to_dev(roi_n))
+    torch.cuda.synchronize()
+    ob, osc, ol, cnt = ob.cpu().numpy(), osc.cpu().numpy(), ol.cpu().numpy(), cnt.cpu().numpy()
+    for f in range(n):
+        rb, rs_, rl, rn = oracle.select_detections(scores[f, :roi_n[f]], boxes[f, :roi_n[f]], spec.score_thr, spec.det_nms_thr, D)
+        assert cnt[f] == rn, f
+        assert np.array_equal(ol[f], rl) and np.array_equal(ob[f], rb) and np.array_equal(osc[f], rs_), f
+    assert cnt[0] == D and cnt[3] == 0
