@@ -71,6 +71,32 @@ __device__ inline void store4(bf16_t* p, const float r[4]) {
     *reinterpret_cast<u32x2_t*>(p) = v;
 }
 
+// 8 consecutive elements of T as one register bundle
+template <typename T> struct Vec8;
+template <> struct __attribute__((aligned(16))) Vec8<bf16_t> { u32x4_t v; };
+template <> struct __attribute__((aligned(16))) Vec8<float> { f32x4_t lo, hi; };
+__device__ inline void unpack8(const Vec8<bf16_t>& x, float r[8]) {
+    const uint32_t w[4] = {x.v.x, x.v.y, x.v.z, x.v.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { r[2 * q] = __uint_as_float(w[q] << 16); r[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u); }
+}
+__device__ inline void unpack8(const Vec8<float>& x, float r[8]) {
+    r[0] = x.lo.x; r[1] = x.lo.y; r[2] = x.lo.z; r[3] = x.lo.w; r[4] = x.hi.x; r[5] = x.hi.y; r[6] = x.hi.z; r[7] = x.hi.w;
+}
+__device__ inline void store8(bf16_t* p, const float r[8]) {
+    u32x4_t v;
+    v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
+    v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+    v.z = (uint32_t)f32_to_bf16(r[4]) | ((uint32_t)f32_to_bf16(r[5]) << 16);
+    v.w = (uint32_t)f32_to_bf16(r[6]) | ((uint32_t)f32_to_bf16(r[7]) << 16);
+    *reinterpret_cast<u32x4_t*>(p) = v;
+}
+__device__ inline void store8(float* p, const float r[8]) {
+    f32x4_t lo = {r[0], r[1], r[2], r[3]}, hi = {r[4], r[5], r[6], r[7]};
+    *reinterpret_cast<f32x4_t*>(p) = lo;
+    *reinterpret_cast<f32x4_t*>(p + 4) = hi;
+}
+
 template <typename T, int BN, typename OutT>
 __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
     constexpr int BK = BKB / (int)sizeof(T);   // K elements per tile row
@@ -78,6 +104,12 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
     constexpr int TN = BN / 64;                // 32-channel MFMA tiles per wavefront
     constexpr int TM = 2;                      // 32-pixel MFMA tiles per wavefront
     constexpr int PA = BN / 32;                // 16-byte weight chunks staged per thread
+    constexpr int WN = BN / 2;                 // channels per wavefront
+    constexpr int LPP = WN / 8;                // epilogue: lanes per pixel (8 channels each)
+    constexpr int PPI = 64 / LPP;              // epilogue: pixels per wavefront instruction
+    constexpr int NIT = 64 / PPI;              // epilogue: iterations over the wavefront's 64 pixels
+    constexpr int EPITCH = WN * 4 + 16;        // epilogue: padded fp32 row pitch in LDS (bytes)
+    static_assert(4 * 64 * EPITCH <= 2 * (BN + BM) * LDS_ROW, "epilogue tile must fit in the pipeline buffers");
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* sA = smem;                     // [2][BN][LDS_ROW]
@@ -89,7 +121,13 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
     const int M = a.N * HoWo;
     const int K = a.kh * a.kw * a.Cin;
     const int tiles_n = (a.Cout + BN - 1) / BN;
-    const int tile_n = blockIdx.x % tiles_n, tile_m = blockIdx.x / tiles_n;
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD a
+    // contiguous range of tiles so that tiles sharing an activation tile hit the same L2.
+    const int total_tiles = ((M + BM - 1) / BM) * tiles_n;
+    const int per_xcd = (total_tiles + 7) >> 3;
+    const int tile = (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
+    if (tile >= total_tiles || (int)(blockIdx.x >> 3) >= per_xcd) return;
+    const int tile_n = tile % tiles_n, tile_m = tile / tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const T* __restrict__ in = static_cast<const T*>(a.in);
@@ -159,6 +197,18 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // 8-channel-per-lane epilogue needs Cout, ld0 multiples of 8 and one dense output
+    const bool vec = (a.out1 == nullptr) && ((a.Cout & 7) == 0) && ((a.ld0 & 7) == 0);
+    Vec8<T> rres[NIT];
+    if (vec && a.res != nullptr) {  // residual tile: issued now, consumed after the K loop
+        const T* __restrict__ resp = static_cast<const T*>(a.res);
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int pix = m0 + wm * 64 + it * PPI + lane / LPP, ch = n0 + wn * WN + (lane % LPP) * 8;
+            if (pix < M && ch < a.Cout) rres[it] = *reinterpret_cast<const Vec8<T>*>(resp + (size_t)pix * a.Cout + ch);
+        }
+    }
+
     load_tiles(0);
     store_tiles(0);
     __syncthreads();
@@ -173,7 +223,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
 #pragma unroll
             for (int i = 0; i < TN; ++i)
                 fa[i] = *reinterpret_cast<const u32x4_t*>(
-                    sA + (size_t)(buf * BN + wn * (BN / 2) + i * 32 + frag_row) * LDS_ROW + kk * 32 + frag_off);
+                    sA + (size_t)(buf * BN + wn * WN + i * 32 + frag_row) * LDS_ROW + kk * 32 + frag_off);
 #pragma unroll
             for (int j = 0; j < TM; ++j)
                 fb[j] = *reinterpret_cast<const u32x4_t*>(
@@ -191,7 +241,49 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
     const T* __restrict__ res = static_cast<const T*>(a.res);
     OutT* __restrict__ out0 = static_cast<OutT*>(a.out0);
     OutT* __restrict__ out1 = static_cast<OutT*>(a.out1);
-    const bool vec = (a.out1 == nullptr) && ((a.Cout & 3) == 0) && ((a.ld0 & 3) == 0);
+    if (vec) {
+        // Coalesced path: every wavefront parks its 64 pixel x WN channel fp32 tile (+ bias) in its own
+        // LDS region (the pipeline buffers are free now), then re-reads it so that each lane owns 8
+        // consecutive channels of one pixel: residual loads and output stores are 16-byte, and the
+        // lanes of one instruction cover whole 128-byte lines of the NHWC tensors.
+        unsigned char* ep = smem + (size_t)wv * (64 * EPITCH);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int chl = i * 32 + 8 * v + 4 * (lane >> 5);
+                    const int ch = n0 + wn * WN + chl;
+                    f32x4_t bv = {0.f, 0.f, 0.f, 0.f};
+                    if (ch < a.Cout) bv = *reinterpret_cast<const f32x4_t*>(a.bias + ch);
+                    f32x4_t r = {acc[i][j][4 * v] + bv.x, acc[i][j][4 * v + 1] + bv.y, acc[i][j][4 * v + 2] + bv.z,
+                                 acc[i][j][4 * v + 3] + bv.w};
+                    *reinterpret_cast<f32x4_t*>(ep + (size_t)(j * 32 + frag_row) * EPITCH + chl * 4) = r;
+                }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int pxl = it * PPI + lane / LPP, chunk = lane % LPP;
+            const int pix = m0 + wm * 64 + pxl, ch = n0 + wn * WN + chunk * 8;
+            if (pix >= M || ch >= a.Cout) continue;
+            const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(ep + (size_t)pxl * EPITCH + chunk * 32);
+            const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(ep + (size_t)pxl * EPITCH + chunk * 32 + 16);
+            float r[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            if (res) {
+                float q[8];
+                unpack8(rres[it], q);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) r[e] += q[e];
+            }
+            if (a.relu) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) r[e] = fmaxf(r[e], 0.f);
+            }
+            store8(out0 + (size_t)pix * a.ld0 + ch, r);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -200,31 +292,17 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
             if (pix >= M) continue;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int ch = n0 + wn * (BN / 2) + i * 32 + 8 * v + 4 * (lane >> 5);
+                const int ch = n0 + wn * WN + i * 32 + 8 * v + 4 * (lane >> 5);
                 if (ch >= a.Cout) continue;
-                float r[4] = {acc[i][j][4 * v], acc[i][j][4 * v + 1], acc[i][j][4 * v + 2], acc[i][j][4 * v + 3]};
-                if (vec) {
-                    const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(a.bias + ch);
-                    r[0] += bv.x; r[1] += bv.y; r[2] += bv.z; r[3] += bv.w;
-                    if (res) {
-                        float q[4];
-                        load4(res + (size_t)pix * a.Cout + ch, q);
-                        r[0] += q[0]; r[1] += q[1]; r[2] += q[2]; r[3] += q[3];
-                    }
-                    if (a.relu) {
-                        r[0] = fmaxf(r[0], 0.f); r[1] = fmaxf(r[1], 0.f); r[2] = fmaxf(r[2], 0.f); r[3] = fmaxf(r[3], 0.f);
-                    }
-                    store4(out0 + (size_t)pix * a.ld0 + ch, r);
-                } else {
-                    for (int q = 0; q < 4; ++q) {
-                        const int c = ch + q;
-                        if (c >= a.Cout) break;
-                        float val = r[q] + a.bias[c];
-                        if (res) val += load_elem(res + (size_t)pix * a.Cout + c);
-                        if (a.relu) val = fmaxf(val, 0.f);
-                        if (c < a.n_split) store_elem(out0 + (size_t)pix * a.ld0 + c, val);
-                        else store_elem(out1 + (size_t)pix * a.ld1 + (c - a.n_split), val);
-                    }
+                const float r[4] = {acc[i][j][4 * v], acc[i][j][4 * v + 1], acc[i][j][4 * v + 2], acc[i][j][4 * v + 3]};
+                for (int q = 0; q < 4; ++q) {
+                    const int c = ch + q;
+                    if (c >= a.Cout) break;
+                    float val = r[q] + a.bias[c];
+                    if (res) val += load_elem(res + (size_t)pix * a.Cout + c);
+                    if (a.relu) val = fmaxf(val, 0.f);
+                    if (c < a.n_split) store_elem(out0 + (size_t)pix * a.ld0 + c, val);
+                    else store_elem(out1 + (size_t)pix * a.ld1 + (c - a.n_split), val);
                 }
             }
         }
@@ -251,8 +329,9 @@ static hipError_t launch_one(const ConvArgs& a, hipStream_t s) {
     }
     const long long M = (long long)a.N * a.Ho * a.Wo;
     const long long tiles = ((M + BM - 1) / BM) * ((a.Cout + BN - 1) / BN);
-    if (tiles <= 0 || tiles >= (1ll << 31)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(256), lds, s, a);
+    if (tiles <= 0 || tiles >= (1ll << 30)) return hipErrorInvalidValue;
+    const long long grid = ((tiles + 7) / 8) * 8;  // 8 XCDs x equal ranges; surplus workgroups exit at once
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, a);
     return hipGetLastError();
 }
 

@@ -62,7 +62,8 @@ struct thia_model {
     int pre = 0, post = 0, pool = 7, sampling = 2, fc_dim = 0, Kc = 0, D = 0, base_width = 64;
     float rpn_thr = 0.7f, score_thr = 0.05f, det_thr = 0.5f, mean = 0.f, stdv = 1.f;
     size_t esz = 4;
-    float* stem_w = nullptr;  // device fp32 [147][64]
+    float* stem_w = nullptr;  // device fp32 [147][64] (fp32 path)
+    bf16_t* stem_wk = nullptr;  // device bf16 [64][22][8] (matrix-core path)
     float* stem_b = nullptr;
     std::vector<Block> stage[4];
     ExitUnit ex[4];
@@ -200,7 +201,7 @@ size_t max_act_elems(const thia_model* m, int H, int W) {
 
 int default_microbatch(const thia_model* m, int H, int W) {
     const double per_frame = (double)max_act_elems(m, H, W) * m->esz;
-    int mb = (int)std::floor(72.0e6 / per_frame + 0.5);
+    int mb = (int)std::floor(600.0e6 / per_frame + 0.5);
     return std::min(32, std::max(1, mb));
 }
 
@@ -341,7 +342,7 @@ int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int
     const int Hs = conv_out(H, 7, 2, 3), Ws = conv_out(W, 7, 2, 3);
     {
         Scope sc(m, THIA_K_STEM);
-        HIP_TRY(m, launch_stem(frames, nb, H, W, m->stem_w, m->stem_b, m->mean, m->stdv, m->precision, ws.act[2], m->stream));
+        HIP_TRY(m, launch_stem(frames, nb, H, W, m->stem_w, m->stem_wk, m->stem_b, m->mean, m->stdv, m->precision, ws.act[2], m->stream));
     }
     int h = conv_out(Hs, 3, 2, 1), w = conv_out(Ws, 3, 2, 1);
     {
@@ -526,6 +527,12 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
         if (hipMalloc(reinterpret_cast<void**>(&m->stem_b), 64 * 4) != hipSuccess) return bad(THIA_E_NOMEM);
         if (hipMemcpy(m->stem_w, w.data(), w.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return bad(THIA_E_HIP);
         if (hipMemcpy(m->stem_b, stem.b, 64 * 4, hipMemcpyHostToDevice) != hipSuccess) return bad(THIA_E_HIP);
+        std::vector<bf16_t> wk((size_t)64 * 22 * 8, (bf16_t)0);
+        for (int o = 0; o < 64; ++o)
+            for (int r = 0; r < 21; ++r)
+                for (int kx = 0; kx < 7; ++kx) wk[((size_t)o * 22 + r) * 8 + kx + 1] = f32_to_bf16(stem.w[(size_t)o * 147 + r * 7 + kx]);
+        if (hipMalloc(reinterpret_cast<void**>(&m->stem_wk), wk.size() * 2) != hipSuccess) return bad(THIA_E_NOMEM);
+        if (hipMemcpy(m->stem_wk, wk.data(), wk.size() * 2, hipMemcpyHostToDevice) != hipSuccess) return bad(THIA_E_HIP);
     }
     int cin = m->stem_ch;
     for (int s = 0; s < n_exits; ++s) {
@@ -586,6 +593,7 @@ void thia_free_model(thia_model* m) {
     for (auto& t : m->taps) if (t.buf) (void)hipFree(t.buf);
     for (auto e : m->ev_pool) (void)hipEventDestroy(e);
     if (m->stem_w) (void)hipFree(m->stem_w);
+    if (m->stem_wk) (void)hipFree(m->stem_wk);
     if (m->stem_b) (void)hipFree(m->stem_b);
     for (int s = 0; s < 4; ++s)
         for (Block& B : m->stage[s]) { free_layer(B.c1); free_layer(B.c2); free_layer(B.c3); free_layer(B.sc); }
@@ -792,7 +800,7 @@ int thia_op_stem(thia_model* m, const uint8_t* frames, int n, int H, int W, void
     const int Hs = conv_out(H, 7, 2, 3), Ws = conv_out(W, 7, 2, 3);
     void* tmp = nullptr;
     if (hipMalloc(&tmp, (size_t)n * Hs * Ws * 64 * m->esz) != hipSuccess) return fail(m, THIA_E_NOMEM, "stem scratch allocation failed");
-    hipError_t e = launch_stem(frames, n, H, W, m->stem_w, m->stem_b, m->mean, m->stdv, m->precision, tmp, m->stream);
+    hipError_t e = launch_stem(frames, n, H, W, m->stem_w, m->stem_wk, m->stem_b, m->mean, m->stdv, m->precision, tmp, m->stream);
     if (e == hipSuccess) e = launch_maxpool(tmp, n, Hs, Ws, 64, m->precision, out, m->stream);
     hipError_t e2 = hipStreamSynchronize(m->stream);
     (void)hipFree(tmp);

@@ -44,32 +44,56 @@ __global__ __launch_bounds__(256) void roialign_kernel(const T* __restrict__ fea
     __syncthreads();
     const T* fm = feat + (size_t)f * Hk * Wk * Ch;
     T* o = out + (size_t)roi * P * P * Ch;
-    for (int c = threadIdx.x; c < Ch; c += blockDim.x) {
-        for (int bin = 0; bin < P * P; ++bin) {
-            float sum = 0.f;
+    // one work item = one bin x one 16-byte run of channels; consecutive threads take consecutive runs
+    constexpr int VEC = 16 / (int)sizeof(T);
+    const int runs = Ch / VEC;
+    for (int i = threadIdx.x; i < P * P * runs; i += blockDim.x) {
+        const int bin = i / runs, c = (i - bin * runs) * VEC;
+        float sum[VEC];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int q = 4 * (4 * bin + s);
-                float a = 0.f;
+        for (int e = 0; e < VEC; ++e) sum[e] = 0.f;
 #pragma unroll
-                for (int tp = 0; tp < 4; ++tp) {
-                    float x;
-                    if constexpr (sizeof(T) == 2) x = bf16_to_f32(fm[(size_t)s_off[q + tp] * Ch + c]);
-                    else x = fm[(size_t)s_off[q + tp] * Ch + c];
-                    a += s_w[q + tp] * x;
+        for (int s = 0; s < 4; ++s) {
+            const int q = 4 * (4 * bin + s);
+            float a[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) a[e] = 0.f;
+#pragma unroll
+            for (int tp = 0; tp < 4; ++tp) {
+                const float w = s_w[q + tp];
+                const uint4 raw = *reinterpret_cast<const uint4*>(fm + (size_t)s_off[q + tp] * Ch + c);
+                if constexpr (sizeof(T) == 2) {
+                    const uint32_t wd[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        a[2 * e] += w * __uint_as_float(wd[e] << 16);
+                        a[2 * e + 1] += w * __uint_as_float(wd[e] & 0xffff0000u);
+                    }
+                } else {
+                    a[0] += w * __uint_as_float(raw.x); a[1] += w * __uint_as_float(raw.y);
+                    a[2] += w * __uint_as_float(raw.z); a[3] += w * __uint_as_float(raw.w);
                 }
-                sum += a;
             }
-            const float val = sum * 0.25f;
-            if constexpr (sizeof(T) == 2) o[(size_t)bin * Ch + c] = f32_to_bf16(val);
-            else o[(size_t)bin * Ch + c] = val;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) sum[e] += a[e];
         }
+        uint4 pk;
+        if constexpr (sizeof(T) == 2) {
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = f32_to_bf16(sum[e] * 0.25f);
+            pk = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+        } else {
+            pk = make_uint4(__float_as_uint(sum[0] * 0.25f), __float_as_uint(sum[1] * 0.25f), __float_as_uint(sum[2] * 0.25f),
+                            __float_as_uint(sum[3] * 0.25f));
+        }
+        *reinterpret_cast<uint4*>(o + (size_t)bin * Ch + c) = pk;
     }
 }
 
 hipError_t launch_roialign(const void* feat, const float* rois, int n, int post, int Hk, int Wk, int Ch, int stride, int P,
                            int precision, void* out, hipStream_t s) {
-    if (n <= 0 || post <= 0 || P <= 0 || P > 16) return hipErrorInvalidValue;
+    if (n <= 0 || post <= 0 || P <= 0 || P > 16 || Ch % 8) return hipErrorInvalidValue;
     const size_t lds = (size_t)P * P * 4 * 4 * 8;
     const float scale = 1.0f / (float)stride;
     const unsigned blocks = (unsigned)n * (unsigned)post;

@@ -227,40 +227,80 @@ __global__ __launch_bounds__(64) void nms_mask_kernel(const float* __restrict__ 
     mask[((size_t)f * cap + i) * words + bx] = bits;
 }
 
-// One wavefront per frame.  Lane w holds word w of the "removed" set (words <= 64).
-__global__ __launch_bounds__(64) void nms_reduce_kernel(const uint64_t* __restrict__ mask, const float* __restrict__ boxes,
-                                                        const int32_t* __restrict__ counts, int cap, int words, int max_keep,
-                                                        int32_t* __restrict__ out_keep, int32_t* __restrict__ out_n,
-                                                        float* __restrict__ rois_out) {
+// One 256-thread block per frame.  The bit matrix is consumed 64 rows at a time: all threads
+// fetch the next 64 x words tile into registers while wavefront 0 resolves the current one from
+// LDS.  Within a tile the greedy decisions only need the diagonal word of each row, which is
+// held one row per lane and broadcast with readlane, so the serial chain is register-only; the
+// rows that were kept are then OR-ed into the "removed" vector (one 64-bit word per lane).
+__global__ __launch_bounds__(256) void nms_reduce_kernel(const uint64_t* __restrict__ mask, const float* __restrict__ boxes,
+                                                         const int32_t* __restrict__ counts, int cap, int words, int max_keep,
+                                                         int32_t* __restrict__ out_keep, int32_t* __restrict__ out_n,
+                                                         float* __restrict__ rois_out) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    uint64_t* tile = reinterpret_cast<uint64_t*>(smem_raw);              // [64][words]
+    uint64_t* tile = reinterpret_cast<uint64_t*>(smem_raw);                 // [64][words]
     int32_t* keep = reinterpret_cast<int32_t*>(tile + (size_t)64 * words);  // [max_keep]
-    const int f = blockIdx.x, lane = threadIdx.x;
+    __shared__ int s_nk;
+    const int f = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
     const int cnt = counts[f] < cap ? counts[f] : cap;
     const int wc = (cnt + 63) / 64;
     const uint64_t* mf = mask + (size_t)f * cap * words;
-    uint64_t removed = 0ull;
+    const int per_thread = (64 * words + 255) / 256;   // <= 16 for words <= 64
+    uint64_t stage[16];
+    auto fetch = [&](int c) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            if (q >= per_thread) break;
+            const int e = q * 256 + t, r = e / words, w = e - r * words;
+            uint64_t v = 0ull;
+            if (e < 64 * words && 64 * c + r < cnt && w >= c && w < wc) v = mf[(size_t)(64 * c + r) * words + w];
+            stage[q] = v;
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            if (q >= per_thread) break;
+            const int e = q * 256 + t;
+            if (e < 64 * words) tile[e] = stage[q];
+        }
+    };
+    if (t == 0) s_nk = 0;
+    uint64_t removed = 0ull;  // wavefront 0: lane w holds word w
     int nk = 0;
-    for (int c = 0; c < wc && nk < max_keep; ++c) {
-        const int rows = (cnt - 64 * c) < 64 ? (cnt - 64 * c) : 64;
-        if (lane < words)
-            for (int r = 0; r < rows; ++r)
-                tile[(size_t)r * words + lane] = (lane >= c && lane < wc) ? mf[(size_t)(64 * c + r) * words + lane] : 0ull;
+    if (wc > 0) fetch(0);
+    for (int c = 0; c < wc; ++c) {
+        stash();
         __syncthreads();
-        uint64_t cur = __shfl(removed, c);
-        for (int b = 0; b < rows; ++b) {
-            if ((cur >> b) & 1ull) continue;
-            if (lane == 0) keep[nk] = 64 * c + b;
-            ++nk;
-            if (lane < words) removed |= tile[(size_t)b * words + lane];
-            cur |= tile[(size_t)b * words + c];
-            if (nk == max_keep) break;
+        if (c + 1 < wc) fetch(c + 1);
+        if (wv == 0 && nk < max_keep) {
+            const int rows = (cnt - 64 * c) < 64 ? (cnt - 64 * c) : 64;
+            const uint64_t diag = lane < rows ? tile[(size_t)lane * words + c] : 0ull;
+            const uint32_t dlo = (uint32_t)diag, dhi = (uint32_t)(diag >> 32);
+            const uint32_t rlo = (uint32_t)removed, rhi = (uint32_t)(removed >> 32);
+            uint64_t cur = (uint64_t)(uint32_t)__builtin_amdgcn_readlane(rlo, c) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(rhi, c) << 32);
+            uint64_t kept = 0ull;
+            for (int b = 0; b < rows; ++b) {
+                if ((cur >> b) & 1ull) continue;
+                kept |= 1ull << b;
+                if (lane == 0) keep[nk] = 64 * c + b;
+                ++nk;
+                if (nk == max_keep) break;
+                cur |= (uint64_t)(uint32_t)__builtin_amdgcn_readlane(dlo, b) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(dhi, b) << 32);
+            }
+            if (lane < words) {
+                uint64_t acc = 0ull;
+                for (int b = 0; b < rows; ++b)
+                    if ((kept >> b) & 1ull) acc |= tile[(size_t)b * words + lane];
+                removed |= acc;
+            }
         }
         __syncthreads();
     }
+    if (t == 0) s_nk = nk;
     __syncthreads();
+    nk = s_nk;
     const float* bf = boxes + (size_t)f * cap * 4;
-    for (int j = lane; j < max_keep; j += 64) {
+    for (int j = t; j < max_keep; j += 256) {
         const int src = j < nk ? keep[j] : -1;
         out_keep[(size_t)f * max_keep + j] = src;
         if (rois_out) {
@@ -269,7 +309,7 @@ __global__ __launch_bounds__(64) void nms_reduce_kernel(const uint64_t* __restri
             *reinterpret_cast<float4*>(rois_out + ((size_t)f * max_keep + j) * 4) = v;
         }
     }
-    if (lane == 0) out_n[f] = nk;
+    if (t == 0) out_n[f] = nk;
 }
 
 hipError_t launch_nms(const float* boxes, const int32_t* counts, int n, int cap, float thr, int max_keep, uint64_t* mask,
@@ -278,7 +318,7 @@ hipError_t launch_nms(const float* boxes, const int32_t* counts, int n, int cap,
     const int words = (cap + 63) / 64;
     hipLaunchKernelGGL(nms_mask_kernel, dim3(words, words, n), dim3(64), 0, s, boxes, counts, cap, words, thr, mask);
     const size_t lds = (size_t)64 * words * 8 + (size_t)max_keep * 4;
-    hipLaunchKernelGGL(nms_reduce_kernel, dim3(n), dim3(64), lds, s, mask, boxes, counts, cap, words, max_keep, out_keep, out_n,
+    hipLaunchKernelGGL(nms_reduce_kernel, dim3(n), dim3(256), lds, s, mask, boxes, counts, cap, words, max_keep, out_keep, out_n,
                        rois_out);
     return hipGetLastError();
 }

@@ -77,14 +77,121 @@ __global__ __launch_bounds__(256) void stem_kernel(const uint8_t* __restrict__ f
     }
 }
 
-hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const float* bias, float mean, float stdv,
-                       int precision, void* out, hipStream_t s) {
+// ---------------------------------------------------------------------------------
+// bf16 stem on the matrix cores.  The 7x7x3 window is laid out as K = 22 rows x 8 taps:
+// row r = c*7 + ky (row 21 is padding), tap j <-> input column 2*ox - 4 + j (j = 0 has a
+// zero weight, j = 1..7 are kx = 0..6).  With that layout the 8 consecutive K values a
+// lane feeds to one 32x32x16 MFMA are 8 consecutive pixels of one input row, i.e. four
+// aligned dwords of the normalised bf16 patch held in LDS: no im2col copy is ever built.
+// A 256-thread block owns 16 rows x 32 columns of stem outputs (wavefront w: rows 4w..4w+3,
+// each row one 32-pixel MFMA tile, both 32-channel tiles).  Results (+bias, ReLU, bf16)
+// go through a wavefront-private LDS tile so that the NHWC stores are 16 bytes per lane
+// and cover whole 128-byte pixel rows.
+typedef __attribute__((ext_vector_type(8))) __bf16 sbf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float sf32x16_t;
+
+constexpr int MT_ROWS = 16, MT_COLS = 32;
+constexpr int MP_ROWS = 2 * MT_ROWS + 5;       // 37 patch rows
+constexpr int MP_W = 2 * MT_COLS + 8;          // 72 patch columns (70 used)
+constexpr int MK_ROWS = 22;                    // 21 (c,ky) rows + 1 zero row
+constexpr int MW_PITCH = MK_ROWS * 16 + 16;    // bytes per channel row of the weight tile (padded)
+constexpr int ME_PITCH = 128 + 16;             // epilogue row pitch (64 bf16 + pad)
+
+__global__ __launch_bounds__(256) void stem_mfma_kernel(const uint8_t* __restrict__ frames, int H, int W, int Hs, int Ws,
+                                                        const bf16_t* __restrict__ wk /*[64][22*8]*/,
+                                                        const float* __restrict__ bias, float mean, float stdv,
+                                                        bf16_t* __restrict__ out) {
+    __shared__ __align__(16) bf16_t patch[3 * MP_ROWS * MP_W];
+    __shared__ __align__(16) unsigned char wt[64 * MW_PITCH];
+    __shared__ __align__(16) unsigned char etile[4 * 32 * ME_PITCH];
+    __shared__ bf16_t lut[256];
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int ox0 = blockIdx.x * MT_COLS, oy0 = blockIdx.y * MT_ROWS, img = blockIdx.z;
+    lut[t] = f32_to_bf16(((float)t - mean) / stdv);
+    for (int i = t; i < 64 * MK_ROWS; i += 256) {  // 16-byte chunks of the weight tile
+        const int ch = i / MK_ROWS, r = i - ch * MK_ROWS;
+        *reinterpret_cast<u32x4_t*>(wt + ch * MW_PITCH + r * 16) = *reinterpret_cast<const u32x4_t*>(wk + (size_t)ch * MK_ROWS * 8 + r * 8);
+    }
+    __syncthreads();
+    const int ix0 = 2 * ox0 - 4, iy0 = 2 * oy0 - 3;
+    const uint8_t* f = frames + (size_t)img * 3 * H * W;
+    for (int i = t; i < 3 * MP_ROWS * MP_W; i += 256) {
+        const int c = i / (MP_ROWS * MP_W), r = i - c * (MP_ROWS * MP_W), py = r / MP_W, px = r - py * MP_W;
+        const int iy = iy0 + py, ix = ix0 + px;
+        bf16_t v = 0;  // zero padding of the normalised tensor
+        if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) v = lut[f[((size_t)c * H + iy) * W + ix]];
+        patch[i] = v;
+    }
+    __syncthreads();
+
+    const int g = lane >> 5, pxl = lane & 31;
+    sf32x16_t acc[4][2];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[r][i][e] = 0.f;
+#pragma unroll
+    for (int s = 0; s < MK_ROWS / 2; ++s) {
+        const int rr = 2 * s + g;                       // K row fed by this lane half
+        const int rq = rr < 21 ? rr : 0;                // padding row: weights are zero, any finite data will do
+        const int c = rq / 7, ky = rq - 7 * c;
+        u32x4_t fa[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const u32x4_t*>(wt + (i * 32 + pxl) * MW_PITCH + rr * 16);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 2 * (4 * wv + r) + ky;      // patch row of this tap row
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(patch + (c * MP_ROWS + row) * MP_W + 2 * pxl);
+            u32x4_t fb = {src[0], src[1], src[2], src[3]};
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                acc[r][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(sbf16x8_t, fa[i]), __builtin_bit_cast(sbf16x8_t, fb),
+                                                                    acc[r][i], 0, 0, 0);
+        }
+    }
+
+    unsigned char* ep = etile + wv * 32 * ME_PITCH;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        // accumulator element e of lane l: channel 8*(e/4) + 4*(l/32) + e%4 (+32 i), pixel l%32
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int ch = i * 32 + 8 * v + 4 * g;
+                const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(bias + ch);
+                const uint32_t h0 = f32_to_bf16(fmaxf(acc[r][i][4 * v] + bv.x, 0.f)), h1 = f32_to_bf16(fmaxf(acc[r][i][4 * v + 1] + bv.y, 0.f));
+                const uint32_t h2 = f32_to_bf16(fmaxf(acc[r][i][4 * v + 2] + bv.z, 0.f)), h3 = f32_to_bf16(fmaxf(acc[r][i][4 * v + 3] + bv.w, 0.f));
+                uint32_t* d = reinterpret_cast<uint32_t*>(ep + pxl * ME_PITCH + ch * 2);
+                d[0] = h0 | (h1 << 16);
+                d[1] = h2 | (h3 << 16);
+            }
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the tile is private to this wavefront
+        __builtin_amdgcn_wave_barrier();
+        const int oy = oy0 + 4 * wv + r;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int p = it * 8 + (lane >> 3), chunk = lane & 7;
+            const int ox = ox0 + p;
+            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(ep + p * ME_PITCH + chunk * 16);
+            if (oy < Hs && ox < Ws) *reinterpret_cast<u32x4_t*>(out + (((size_t)img * Hs + oy) * Ws + ox) * SC + chunk * 8) = v;
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const bf16_t* wk, const float* bias, float mean,
+                       float stdv, int precision, void* out, hipStream_t s) {
     const int Hs = (H + 6 - 7) / 2 + 1, Ws = (W + 6 - 7) / 2 + 1;
     dim3 grid((Ws + ST - 1) / ST, (Hs + ST - 1) / ST, n);
     if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
-    if (precision)
-        hipLaunchKernelGGL(stem_kernel<true>, grid, dim3(256), 0, s, frames, H, W, Hs, Ws, w, bias, mean, stdv, out);
-    else
+    if (precision) {
+        dim3 g2((Ws + MT_COLS - 1) / MT_COLS, (Hs + MT_ROWS - 1) / MT_ROWS, n);
+        hipLaunchKernelGGL(stem_mfma_kernel, g2, dim3(256), 0, s, frames, H, W, Hs, Ws, wk, bias, mean, stdv, static_cast<bf16_t*>(out));
+    } else
         hipLaunchKernelGGL(stem_kernel<false>, grid, dim3(256), 0, s, frames, H, W, Hs, Ws, w, bias, mean, stdv, out);
     return hipGetLastError();
 }

@@ -45,10 +45,11 @@ hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream
 bool conv_supported(const ConvArgs& a, int precision);
 
 // ---------------------------------------------------------------- stem + pool
-// frames u8 [n,3,H,W]; w fp32 [(c*7+ky)*7+kx][64] (bf16-representable values when precision == 1);
-// out T [n,Hs,Ws,64] NHWC with ReLU applied.  x = (u8 - mean) / stdv, zero padding after normalisation.
-hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const float* bias, float mean,
-                       float stdv, int precision, void* out, hipStream_t s);
+// frames u8 [n,3,H,W]; out T [n,Hs,Ws,64] NHWC with ReLU applied.  x = (u8 - mean) / stdv, zero padding
+// after normalisation.  precision 0 uses w: fp32 [(c*7+ky)*7+kx][64]; precision 1 uses wk: bf16
+// [64][22][8] with wk[ch][c*7+ky][j] = weight(ch, c, ky, kx = j-1) for j = 1..7, zero for j = 0 and row 21.
+hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const bf16_t* wk, const float* bias,
+                       float mean, float stdv, int precision, void* out, hipStream_t s);
 hipError_t launch_maxpool(const void* in, int n, int H, int W, int C, int precision, void* out, hipStream_t s);
 
 // ---------------------------------------------------------------- RPN proposal path
