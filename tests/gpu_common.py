@@ -75,3 +75,75 @@ def match_fraction(gb, gl, rb, rl, iou_thr=0.99):
                 hit += 1
                 break
     return hit / max(nr, ng), max(nr, ng)
+
+
+def chain_check(m, blob, spec, H, W, ep, n_frames, frame, gb, gs, gl, step_tol):
+    """Stage-by-stage check INSIDE a full run: every stage of frame `frame` is recomputed by the
+    oracle's step functions from the GPU's own upstream tensors (taps).  Discrete stages (top-k
+    indices, NMS keeps, final selection) must then agree bit-exactly; continuous stages within
+    step_tol (per tensor, max-abs normalised).  This is immune to the rank-order sensitivity of
+    random-init scores, because both sides take each decision on identical numbers."""
+    import oracle
+    from thia_synth import split_blob
+    orc = oracle.Model(blob)
+    bf = spec.precision
+    Ck, Hk, Wk, stride = orc.exit_shape(ep, H, W)
+    Ch = spec.head_ch if spec.has_lateral else Ck
+    A, pre, post, P, Kc, D = spec.n_anchors, spec.pre_nms, spec.post_nms, spec.pool, spec.n_classes, spec.max_det
+    nA = Hk * Wk * A
+    f = frame
+    tap = lambda name, shape: m.tap(name).reshape((n_frames,) + shape)[f]
+    logits, deltas = tap("rpn_logits", (nA,)), tap("rpn_deltas", (nA, 4))
+    # top-k on the GPU's own logits
+    ridx, _ = oracle.topk(logits, pre)
+    gidx = tap("topk_idx", (pre,))
+    assert np.array_equal(gidx[:len(ridx)], ridx) and np.all(gidx[len(ridx):] == -1), "top-k indices"
+    # decode + clip + drop empties
+    ref = []
+    for i in ridx:
+        bx, ok = oracle.decode(orc.anchor(i, Wk, stride), deltas[i], W, H)
+        if ok:
+            ref.append(bx)
+    ref = np.array(ref, np.float32).reshape(-1, 4)
+    pn = int(m.tap("prop_n")[f])
+    pbox = tap("prop_boxes", (pre, 4))
+    assert pn == len(ref), ("proposal count", pn, len(ref))
+    assert np.max(np.abs(pbox[:pn] - ref)) <= 1e-5 * 4 * max(H, W), "decoded proposals"
+    # NMS on the GPU's own proposals
+    keep = oracle.nms(pbox[:pn], spec.rpn_nms_thr, post)
+    rn = int(m.tap("roi_n")[f])
+    rois = tap("rois", (post, 4))
+    assert rn == len(keep) and np.array_equal(rois[:rn], pbox[keep]) and np.all(rois[rn:] == 0), "proposal NMS"
+    # ROIAlign on the GPU's own head feature map and ROIs
+    hf = np.ascontiguousarray(np.transpose(tap("head_feat", (Hk, Wk, Ch)), (2, 0, 1)))
+    rf_ref = oracle.roialign(hf, rois[:rn], stride, P, spec.sampling, round_out=bf)          # [rn, Ch, P, P]
+    rf = tap("roi_feat", (post, P * P, Ch))[:rn]
+    rf_nchw = np.ascontiguousarray(np.transpose(rf, (0, 2, 1))).reshape(rn, Ch * P * P)
+    e_roi = relerr(rf_nchw, rf_ref.reshape(rn, -1))
+    assert e_roi <= step_tol, ("roialign", e_roi)
+    # box head on the GPU's own ROI features
+    w = split_blob(spec, blob)
+    e = f"e{ep}"
+    h1 = oracle.fc(rf_nchw, w[e + ".fc1.w"], w[e + ".fc1.b"], relu=True, bf16_weights=bf, round_out=bf)
+    h2 = oracle.fc(h1, w[e + ".fc2.w"], w[e + ".fc2.b"], relu=True, bf16_weights=bf, round_out=bf)
+    cl_ref = oracle.fc(h2, w[e + ".cls.w"], w[e + ".cls.b"], bf16_weights=bf)
+    bd_ref = oracle.fc(h2, w[e + ".box.w"], w[e + ".box.b"], bf16_weights=bf)
+    cl, bd = tap("cls_logits", (post, Kc))[:rn], tap("box_deltas", (post, 4 * Kc))[:rn]
+    head_tol = 4 * step_tol if bf else step_tol      # two bf16-rounded FC layers in between
+    e_cl, e_bd = relerr(cl, cl_ref), relerr(bd, bd_ref)
+    assert e_cl <= head_tol and e_bd <= head_tol, ("box head", e_cl, e_bd)
+    # scores and per-class boxes from the GPU's own logits / deltas
+    cs, cb = tap("cand_scores", (post, Kc))[:rn], tap("cand_boxes", (post, Kc, 4))[:rn]
+    assert np.max(np.abs(cs - oracle.softmax(cl))) <= 1e-5, "softmax"
+    for r in (0, rn // 2, rn - 1):
+        q = rois[r]
+        anc = [q[0] + np.float32(0.5) * (q[2] - q[0]), q[1] + np.float32(0.5) * (q[3] - q[1]), q[2] - q[0], q[3] - q[1]]
+        for c in range(1, Kc):
+            bx, _ = oracle.decode(anc, bd[r, 4 * c:4 * c + 4], W, H)
+            assert np.max(np.abs(bx - cb[r, c])) <= 1e-5 * 4 * max(H, W), "class boxes"
+    # final selection on the GPU's own candidate scores / boxes
+    ob, osc, ol, nd = oracle.select_detections(cs, cb, spec.score_thr, spec.det_nms_thr, D)
+    assert int(m.tap("det_n")[f]) == nd, "detection count"
+    assert np.array_equal(gl[f].cpu().numpy(), ol) and np.array_equal(gb[f].cpu().numpy(), ob) \
+        and np.array_equal(gs[f].cpu().numpy(), osc), "final selection"
+    return dict(roialign=e_roi, cls=e_cl, box=e_bd, n_rois=rn, n_det=nd)

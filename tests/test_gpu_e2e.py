@@ -8,7 +8,7 @@ import torch
 
 import oracle
 from conftest import get_blob
-from gpu_common import MINI_BF16, MINI_FP32, gpu_model, match_fraction, nhwc_to_nchw, relerr, to_dev
+from gpu_common import MINI_BF16, MINI_FP32, chain_check, gpu_model, match_fraction, nhwc_to_nchw, relerr, to_dev
 from thia_synth import CONFIGS, SceneSpec, make_frames
 
 pytestmark = pytest.mark.gpu
@@ -53,6 +53,8 @@ def test_config1_tiny_fp32_end_to_end():
         assert np.max(np.abs(t["rois"] - ref["rois"])) <= 1e-3
         assert relerr(t["cls_logits"], ref["cls_logits"]) <= TOL_F32
         assert relerr(t["box_deltas"], ref["box_deltas"]) <= TOL_F32
+    for f in range(4):       # every stage re-derived by the oracle from the GPU's own upstream tensors
+        chain_check(m, blob, cfg.model, 128, 128, 1, 4, f, gb, gs, gl, step_tol=TOL_F32)
     m.set_debug(False)
     _check_detections(gb.cpu().numpy(), gs.cpu().numpy(), gl.cpu().numpy(), ref)
 
