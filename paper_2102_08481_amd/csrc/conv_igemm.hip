@@ -15,6 +15,8 @@
 // "B" operand (columns = pixels): each lane then holds 4 consecutive channels of one
 // pixel per accumulator quad, which is the contiguous direction of the NHWC output.
 // Epilogue: + bias (fp32) [+ residual] [ReLU], then one rounding to the output type.
+#include <type_traits>
+
 #include "thia_internal.h"
 
 namespace thia {
@@ -25,9 +27,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
-constexpr int BM = 128;       // pixels per block
-constexpr int BKB = 128;      // bytes of K per tile row
-constexpr int LDS_ROW = 144;  // padded row pitch in bytes
 
 template <typename T>
 __device__ inline void mma_step(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b);
@@ -97,19 +96,32 @@ __device__ inline void store8(float* p, const float r[8]) {
     *reinterpret_cast<f32x4_t*>(p + 4) = hi;
 }
 
-template <typename T, int BN, typename OutT>
+// compile-time loop: the body sees the index as a constant (keeps accumulator indices static)
+template <int I, int N, typename F>
+__device__ inline void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+template <typename T, int BM, int BN, int BKB, typename OutT>
 __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
     constexpr int BK = BKB / (int)sizeof(T);   // K elements per tile row
     constexpr int EPC = 16 / (int)sizeof(T);   // elements per 16-byte chunk
-    constexpr int TN = BN / 64;                // 32-channel MFMA tiles per wavefront
-    constexpr int TM = 2;                      // 32-pixel MFMA tiles per wavefront
-    constexpr int PA = BN / 32;                // 16-byte weight chunks staged per thread
-    constexpr int WN = BN / 2;                 // channels per wavefront
+    constexpr int CPR = BKB / 16;              // 16-byte chunks per tile row
+    constexpr int RPP = 256 / CPR;             // tile rows covered by one pass of the 256 threads
+    constexpr int PB = BM / RPP, PA = BN / RPP;  // chunks staged per thread (activations, weights)
+    constexpr int LDS_ROW = BKB + 16;          // padded LDS row pitch (an odd multiple of 16 bytes)
+    constexpr int KK = BKB / 32;               // MFMA k-steps per tile row (32 bytes = 2 lane halves x 16 bytes)
+    constexpr int WM = BM / 2, WN = BN / 2;    // wavefront tile (pixels x channels), wavefronts 2 x 2
+    constexpr int TM = WM / 32, TN = WN / 32;  // 32x32 MFMA tiles per wavefront
     constexpr int LPP = WN / 8;                // epilogue: lanes per pixel (8 channels each)
     constexpr int PPI = 64 / LPP;              // epilogue: pixels per wavefront instruction
-    constexpr int NIT = 64 / PPI;              // epilogue: iterations over the wavefront's 64 pixels
+    constexpr int NIT = 32 / PPI;              // epilogue: instructions per 32-pixel sub-tile
     constexpr int EPITCH = WN * 4 + 16;        // epilogue: padded fp32 row pitch in LDS (bytes)
-    static_assert(4 * 64 * EPITCH <= 2 * (BN + BM) * LDS_ROW, "epilogue tile must fit in the pipeline buffers");
+    constexpr bool PREFETCH_RES = TM * NIT <= 8;  // residual tile small enough to hold across the K loop
+    static_assert(4 * 32 * EPITCH <= 2 * (BN + BM) * LDS_ROW, "epilogue tile must fit in the pipeline buffers");
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* sA = smem;                     // [2][BN][LDS_ROW]
@@ -126,21 +138,21 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
     const int total_tiles = ((M + BM - 1) / BM) * tiles_n;
     const int per_xcd = (total_tiles + 7) >> 3;
     const int tile = (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
-    if (tile >= total_tiles || (int)(blockIdx.x >> 3) >= per_xcd) return;
+    if (tile >= total_tiles) return;
     const int tile_n = tile % tiles_n, tile_m = tile / tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const T* __restrict__ in = static_cast<const T*>(a.in);
     const T* __restrict__ wgt = static_cast<const T*>(a.w);
 
-    // ---- per-thread load coordinates: row = lrow + 32 p, 16-byte chunk lchunk of the 128-byte row
-    const int lrow = t >> 3, lchunk = t & 7;
-    size_t b_base[4];
-    int b_iy0[4], b_ix0[4];
-    bool b_ok[4];
+    // ---- per-thread load coordinates: tile row lrow + RPP*p, 16-byte chunk lchunk of the row
+    const int lrow = t / CPR, lchunk = t % CPR;
+    size_t b_base[PB];
+    int b_iy0[PB], b_ix0[PB];
+    bool b_ok[PB];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int m = m0 + lrow + 32 * p;
+    for (int p = 0; p < PB; ++p) {
+        const int m = m0 + lrow + RPP * p;
         b_ok[p] = m < M;
         const int mm = b_ok[p] ? m : 0;
         const int img = mm / HoWo, rem = mm - img * HoWo;
@@ -153,40 +165,41 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
     bool a_ok[PA];
 #pragma unroll
     for (int p = 0; p < PA; ++p) {
-        const int n = n0 + lrow + 32 * p;
+        const int n = n0 + lrow + RPP * p;
         a_ok[p] = n < a.Cout;
         a_base[p] = (size_t)(a_ok[p] ? n : 0) * K + (size_t)lchunk * EPC;
     }
     const int cin_tiles = a.Cin / BK;
     const int KT = K / BK;
 
-    u32x4_t ra[PA], rb[4];
-    auto load_tiles = [&](int kt) {
+    struct Stage { u32x4_t a[PA]; u32x4_t b[PB]; };
+    Stage st0;
+    auto load_tiles = [&](int kt, Stage& st) {
         const int tap = kt / cin_tiles;
         const int c0 = (kt - tap * cin_tiles) * BK;
         const int ky = tap / a.kw, kx = tap - ky * a.kw;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < PB; ++p) {
             const int iy = b_iy0[p] + ky, ix = b_ix0[p] + kx;
             const bool ok = b_ok[p] && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
             u32x4_t v = {0u, 0u, 0u, 0u};
             if (ok) v = *reinterpret_cast<const u32x4_t*>(in + b_base[p] + ((size_t)iy * a.W + ix) * a.Cin + c0);
-            rb[p] = v;
+            st.b[p] = v;
         }
 #pragma unroll
         for (int p = 0; p < PA; ++p) {
             u32x4_t v = {0u, 0u, 0u, 0u};
             if (a_ok[p]) v = *reinterpret_cast<const u32x4_t*>(wgt + a_base[p] + (size_t)kt * BK);
-            ra[p] = v;
+            st.a[p] = v;
         }
     };
-    auto store_tiles = [&](int buf) {
+    auto store_tiles = [&](int buf, const Stage& st) {
 #pragma unroll
         for (int p = 0; p < PA; ++p)
-            *reinterpret_cast<u32x4_t*>(sA + (size_t)(buf * BN + lrow + 32 * p) * LDS_ROW + lchunk * 16) = ra[p];
+            *reinterpret_cast<u32x4_t*>(sA + (size_t)(buf * BN + lrow + RPP * p) * LDS_ROW + lchunk * 16) = st.a[p];
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
-            *reinterpret_cast<u32x4_t*>(sB + (size_t)(buf * BM + lrow + 32 * p) * LDS_ROW + lchunk * 16) = rb[p];
+        for (int p = 0; p < PB; ++p)
+            *reinterpret_cast<u32x4_t*>(sB + (size_t)(buf * BM + lrow + RPP * p) * LDS_ROW + lchunk * 16) = st.b[p];
     };
 
     f32x16_t acc[TN][TM];
@@ -199,26 +212,22 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
 
     // 8-channel-per-lane epilogue needs Cout, ld0 multiples of 8 and one dense output
     const bool vec = (a.out1 == nullptr) && ((a.Cout & 7) == 0) && ((a.ld0 & 7) == 0);
-    Vec8<T> rres[NIT];
-    if (vec && a.res != nullptr) {  // residual tile: issued now, consumed after the K loop
-        const T* __restrict__ resp = static_cast<const T*>(a.res);
+    const T* __restrict__ res = static_cast<const T*>(a.res);
+    Vec8<T> rres[PREFETCH_RES ? TM * NIT : 1];
+    if (PREFETCH_RES && vec && res != nullptr) {  // residual tile: issued now, consumed after the K loop
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int pix = m0 + wm * 64 + it * PPI + lane / LPP, ch = n0 + wn * WN + (lane % LPP) * 8;
-            if (pix < M && ch < a.Cout) rres[it] = *reinterpret_cast<const Vec8<T>*>(resp + (size_t)pix * a.Cout + ch);
-        }
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int pix = m0 + wm * WM + j * 32 + it * PPI + lane / LPP, ch = n0 + wn * WN + (lane % LPP) * 8;
+                if (pix < M && ch < a.Cout) rres[PREFETCH_RES ? j * NIT + it : 0] = *reinterpret_cast<const Vec8<T>*>(res + (size_t)pix * a.Cout + ch);
+            }
     }
 
-    load_tiles(0);
-    store_tiles(0);
-    __syncthreads();
-
     const int frag_row = lane & 31, frag_off = (lane >> 5) * 16;
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) load_tiles(kt + 1);
+    auto compute = [&](int buf) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < KK; ++kk) {
             u32x4_t fa[TN], fb[TM];
 #pragma unroll
             for (int i = 0; i < TN; ++i)
@@ -227,30 +236,49 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
 #pragma unroll
             for (int j = 0; j < TM; ++j)
                 fb[j] = *reinterpret_cast<const u32x4_t*>(
-                    sB + (size_t)(buf * BM + wm * 64 + j * 32 + frag_row) * LDS_ROW + kk * 32 + frag_off);
+                    sB + (size_t)(buf * BM + wm * WM + j * 32 + frag_row) * LDS_ROW + kk * 32 + frag_off);
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j) mma_step<T>(acc[i][j], fa[i], fb[j]);
         }
-        if (kt + 1 < KT) store_tiles(buf ^ 1);
+    };
+
+    // Software pipeline: while tile kt is multiplied out of LDS buffer kt&1, the loads of tile kt+1 are
+    // in flight into registers; they are written to the other buffer at the end of the step.  (A second
+    // register stage was measured: it costs the second resident block per CU and is slower.)
+    load_tiles(0, st0);
+    store_tiles(0, st0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < KT) load_tiles(kt + 1, st0);
+        compute(buf);
+        if (kt + 1 < KT) store_tiles(buf ^ 1, st0);
         __syncthreads();
     }
 
     // ---- epilogue.  Accumulator element e of lane l: channel 8*(e/4) + 4*(l/32) + e%4, pixel l%32.
-    const T* __restrict__ res = static_cast<const T*>(a.res);
     OutT* __restrict__ out0 = static_cast<OutT*>(a.out0);
     OutT* __restrict__ out1 = static_cast<OutT*>(a.out1);
     if (vec) {
-        // Coalesced path: every wavefront parks its 64 pixel x WN channel fp32 tile (+ bias) in its own
-        // LDS region (the pipeline buffers are free now), then re-reads it so that each lane owns 8
-        // consecutive channels of one pixel: residual loads and output stores are 16-byte, and the
-        // lanes of one instruction cover whole 128-byte lines of the NHWC tensors.
-        unsigned char* ep = smem + (size_t)wv * (64 * EPITCH);
+        // Coalesced path, one 32-pixel sub-tile at a time: the wavefront parks its 32 pixel x WN channel
+        // fp32 tile (+ bias) in its own LDS region (the pipeline buffers are free now) and re-reads it so
+        // that each lane owns 8 consecutive channels of one pixel: residual loads and output stores are
+        // 16-byte and the lanes of one instruction cover whole lines of the NHWC tensors.
+        unsigned char* ep = smem + (size_t)wv * (32 * EPITCH);
+        static_for<0, TM>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            Vec8<T> rnow[NIT];
+            if (!PREFETCH_RES && res != nullptr) {
 #pragma unroll
-        for (int i = 0; i < TN; ++i)
+                for (int it = 0; it < NIT; ++it) {
+                    const int pix = m0 + wm * WM + j * 32 + it * PPI + lane / LPP, ch = n0 + wn * WN + (lane % LPP) * 8;
+                    if (pix < M && ch < a.Cout) rnow[it] = *reinterpret_cast<const Vec8<T>*>(res + (size_t)pix * a.Cout + ch);
+                }
+            }
 #pragma unroll
-            for (int j = 0; j < TM; ++j)
+            for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int chl = i * 32 + 8 * v + 4 * (lane >> 5);
@@ -259,36 +287,41 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
                     if (ch < a.Cout) bv = *reinterpret_cast<const f32x4_t*>(a.bias + ch);
                     f32x4_t r = {acc[i][j][4 * v] + bv.x, acc[i][j][4 * v + 1] + bv.y, acc[i][j][4 * v + 2] + bv.z,
                                  acc[i][j][4 * v + 3] + bv.w};
-                    *reinterpret_cast<f32x4_t*>(ep + (size_t)(j * 32 + frag_row) * EPITCH + chl * 4) = r;
+                    *reinterpret_cast<f32x4_t*>(ep + (size_t)frag_row * EPITCH + chl * 4) = r;
                 }
-        __syncthreads();
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the region is private to this wavefront
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int pxl = it * PPI + lane / LPP, chunk = lane % LPP;
-            const int pix = m0 + wm * 64 + pxl, ch = n0 + wn * WN + chunk * 8;
-            if (pix >= M || ch >= a.Cout) continue;
-            const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(ep + (size_t)pxl * EPITCH + chunk * 32);
-            const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(ep + (size_t)pxl * EPITCH + chunk * 32 + 16);
-            float r[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            if (res) {
-                float q[8];
-                unpack8(rres[it], q);
+            for (int it = 0; it < NIT; ++it) {
+                const int pxl = it * PPI + lane / LPP, chunk = lane % LPP;
+                const int pix = m0 + wm * WM + j * 32 + pxl, ch = n0 + wn * WN + chunk * 8;
+                if (pix >= M || ch >= a.Cout) continue;
+                const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(ep + (size_t)pxl * EPITCH + chunk * 32);
+                const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(ep + (size_t)pxl * EPITCH + chunk * 32 + 16);
+                float r[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                if (res) {
+                    float q[8];
+                    if (PREFETCH_RES) unpack8(rres[PREFETCH_RES ? j * NIT + it : 0], q);
+                    else unpack8(rnow[it], q);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) r[e] += q[e];
+                    for (int e = 0; e < 8; ++e) r[e] += q[e];
+                }
+                if (a.relu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) r[e] = fmaxf(r[e], 0.f);
+                }
+                store8(out0 + (size_t)pix * a.ld0 + ch, r);
             }
-            if (a.relu) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) r[e] = fmaxf(r[e], 0.f);
-            }
-            store8(out0 + (size_t)pix * a.ld0 + ch, r);
-        }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+        });
         return;
     }
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
-            const int pix = m0 + wm * 64 + j * 32 + frag_row;
+            const int pix = m0 + wm * WM + j * 32 + frag_row;
             if (pix >= M) continue;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
@@ -311,17 +344,17 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
 bool conv_supported(const ConvArgs& a, int precision) {
     const int bk = precision ? 64 : 32;
     if (a.Cin <= 0 || a.Cin % bk) return false;
-    if (a.N <= 0 || a.Cout <= 0 || a.Ho <= 0 || a.Wo <= 0) return false;
+    if (a.N <= 0 || a.Cout <= 0 || a.Ho <= 0 || a.Wo <= 0 || a.zeros == nullptr) return false;
     if ((long long)a.N * a.Ho * a.Wo >= (1ll << 31)) return false;
     if ((long long)a.N * a.H * a.W * a.Cin >= (1ll << 40)) return false;
     return true;
 }
 
-template <typename T, int BN, typename OutT>
+template <typename T, int BM, int BN, int BKB, typename OutT>
 static hipError_t launch_one(const ConvArgs& a, hipStream_t s) {
     static bool attr_set = false;
-    const size_t lds = (size_t)2 * (BN + BM) * LDS_ROW;
-    auto kern = conv_igemm_kernel<T, BN, OutT>;
+    const size_t lds = (size_t)2 * (BN + BM) * (BKB + 16);
+    auto kern = conv_igemm_kernel<T, BM, BN, BKB, OutT>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -339,10 +372,12 @@ hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream
     if (!conv_supported(a, precision)) return hipErrorInvalidValue;
     const bool narrow = a.Cout <= 64;
     if (precision == 0) {
-        return narrow ? launch_one<float, 64, float>(a, s) : launch_one<float, 128, float>(a, s);
+        return narrow ? launch_one<float, 128, 64, 128, float>(a, s) : launch_one<float, 128, 128, 128, float>(a, s);
     }
-    if (out_f32) return narrow ? launch_one<bf16_t, 64, float>(a, s) : launch_one<bf16_t, 128, float>(a, s);
-    return narrow ? launch_one<bf16_t, 64, bf16_t>(a, s) : launch_one<bf16_t, 128, bf16_t>(a, s);
+    if (out_f32) return narrow ? launch_one<bf16_t, 128, 64, 128, float>(a, s) : launch_one<bf16_t, 128, 128, 128, float>(a, s);
+    // (A 256 x 256 tile with 128 x 128 per wavefront was measured on the long-K layers: with one resident
+    // block per CU it is 5-25 % slower than 128 x 128 at two blocks per CU, so it is not instantiated.)
+    return narrow ? launch_one<bf16_t, 128, 64, 128, bf16_t>(a, s) : launch_one<bf16_t, 128, 128, 128, bf16_t>(a, s);
 }
 
 }  // namespace thia

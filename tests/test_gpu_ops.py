@@ -13,10 +13,11 @@ from thia_synth import CONFIGS, SceneSpec, make_frames
 pytestmark = pytest.mark.gpu
 
 # fp32 tensors: fp32 MFMA accumulation against double accumulation -> 1e-4 (the stated bar);
-# bf16 tensors against the oracle in bf16-storage mode: one bf16 rounding of the output
-# (2^-9 relative) may flip where fp32 and double sums straddle a rounding boundary -> 2^-8.
+# bf16 tensors against the oracle in bf16-storage mode: the single bf16 rounding of an output may
+# go the other way where the fp32 and the double sum straddle a rounding boundary, i.e. one bf16
+# ulp; for an element just below a power of two that is 2^-7 of the tensor's max-abs.
 TOL_F32 = 1e-4
-TOL_BF16_STEP = 2.0 ** -8
+TOL_BF16_STEP = 2.0 ** -7
 
 
 def _model(precision):
@@ -37,6 +38,8 @@ def _bf16(x):
     dict(n=1, H=9, W=11, Cin=256, Cout=75, k=1, stride=1, pad=0),        # Cout not a multiple of 4 (scalar epilogue)
     dict(n=300, H=1, W=1, Cin=1024, Cout=40, k=1, stride=1, pad=0),      # FC-shaped, narrow
     dict(n=1, H=1, W=1, Cin=64, Cout=64, k=1, stride=1, pad=0),          # single row
+    dict(n=2, H=161, W=159, Cin=64, Cout=256, k=3, stride=1, pad=1),     # 256x256 tile kernel, ragged M, 3x3 borders
+    dict(n=2, H=161, W=160, Cin=512, Cout=512, k=1, stride=1, pad=0),    # 256x256 tile kernel, two N tiles
 ])
 def test_conv_op_matches_oracle(precision, case):
     m, _ = _model(precision)
