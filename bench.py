@@ -43,6 +43,44 @@ def layer_macs(spec, H, W, ep):
     return stem, back, rpn, head
 
 
+def conv_layer_bytes(spec, H, W, ep, esz=2):
+    """Algorithmic HBM bytes per frame of the implicit-GEMM launches at exit ep, layer by layer and
+    unfused: input + output (+ residual) activations once each; weights are negligible and left out."""
+    h, w = conv_out(conv_out(H, 7, 2, 3), 3, 2, 1), conv_out(conv_out(W, 7, 2, 3), 3, 2, 1)
+    total, cin = 0, spec.stem_ch
+    for s in range(ep):
+        wd = spec.base_width << s
+        for b in range(spec.blocks[s]):
+            st = 2 if (b == 0 and s > 0) else 1
+            ho, wo = conv_out(h, 3, st, 1), conv_out(w, 3, st, 1)
+            total += esz * (h * w * cin + h * w * wd)                       # conv1
+            total += esz * (h * w * wd + ho * wo * wd)                      # conv2 (reads every input pixel once)
+            total += esz * (ho * wo * wd + 2 * ho * wo * 4 * wd)            # conv3 + residual
+            if b == 0:
+                total += esz * (ho * wo * cin + ho * wo * 4 * wd)           # shortcut reads the strided pixels only
+            cin, h, w = 4 * wd, ho, wo
+    hc = spec.head_ch if spec.has_lateral else cin
+    A = spec.n_anchors
+    if spec.has_lateral:
+        total += esz * h * w * (cin + hc)
+    total += esz * h * w * 2 * hc + esz * h * w * hc + 4 * h * w * 5 * A   # rpn conv, heads (fp32 out)
+    rows = spec.post_nms
+    total += esz * rows * (hc * spec.pool ** 2 + spec.fc_dim) + esz * rows * 2 * spec.fc_dim + esz * rows * spec.fc_dim + 4 * rows * 5 * spec.n_classes
+    return total
+
+
+def measured_traffic(workload_key):
+    """HBM bytes per step of the dominant kernel from the committed rocprofv3 --pmc summary, if present."""
+    path = os.path.join(ROOT, "profiles", "conv_igemm_config3_sweep_pmc_fetch_write.txt")
+    try:
+        for line in open(path):
+            if line.startswith("TRAFFIC_BYTES_PER_STEP " + workload_key):
+                return float(line.split()[2])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,6 +88,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--skip-cpu-baseline", action="store_true", help="leave out the oracle timing (for profiler runs)")
     ap.add_argument("--microbatch", type=int, default=0)
+    ap.add_argument("--pmc-calibration", action="store_true", help="append one 256 MiB device copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (frames are independent; see DESIGN.md for sharding); use --gpus 1",
@@ -82,9 +121,8 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps; per-exit times from events on the stream the kernels run on;
-    # per-kernel-class times from the library's own HIP events around every launch
-    model.profile_begin()
+    # ---- timed region: exactly K steps, inputs resident in HBM, bracketed by device synchronisation.
+    # Per-exit times come from events recorded on the stream the kernels run on.
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in exits] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -95,16 +133,28 @@ def main():
             ev[k][i][1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    prof = model.profile_read()
-    model.profile_end()
 
-    # the same K steps without the per-launch events: shows what the instrumentation costs
+    # ---- the same K steps again with the library's HIP events around every kernel launch (two event
+    # records per launch, a few per cent slower): per-kernel-class device time for the roofline figure
+    model.profile_begin()
     torch.cuda.synchronize()
     t2 = time.perf_counter()
     for k in range(args.steps):
         step()
     torch.cuda.synchronize()
     t3 = time.perf_counter()
+    prof = model.profile_read()
+    model.profile_end()
+
+    if args.pmc_calibration:
+        # a plain copy of known size, so that a `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE` run of this command can
+        # scale the counters: 256 MiB read + 256 MiB written by one elementwise kernel
+        a_ = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        b_ = torch.empty_like(a_)
+        a_.zero_()
+        torch.cuda.synchronize()
+        b_.copy_(a_)
+        torch.cuda.synchronize()
 
     total_s = t1 - t0
     ms_per_step = 1e3 * total_s / args.steps
@@ -119,11 +169,17 @@ def main():
     roofline = {
         "kernel": "conv_igemm_kernel (all instantiations: backbone, lateral, RPN, FC)",
         "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-        "traffic": None,
+        "traffic": None,   # filled below: bytes per launch from the committed --pmc runs
         "flops_per_step": conv_flops_step, "launches_per_step": conv_launches, "avg_launch_us": 1e3 * conv_ms / max(conv_launches, 1),
         "kernel_ms_per_step": conv_ms,
     }
     class_ms = {k: v[0] / args.steps for k, v in prof.items()}
+    alg_bytes_step = float(B * sum(conv_layer_bytes(spec, H, W, ep) for ep in exits))
+    roofline["algorithmic_bytes_per_step"] = alg_bytes_step
+    tr = measured_traffic("conv_igemm")
+    if tr is not None and not args.microbatch:
+        roofline["traffic"] = tr / max(conv_launches, 1)          # per launch, like `achieved`
+        roofline["traffic_bytes_per_step"] = tr
 
     result = {
         "metric": "frames/sec per exit point EP1-EP4 @540x960 bf16; MFMA util %; max rel err",
@@ -131,11 +187,11 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "config 3: ResNet-50-style 4-exit detector, 32 frames 3x540x960, one detect_chunk per exit EP1..EP4 per step",
-                   "batch": B, "H": H, "W": W, "microbatch": model.info.microbatch or None},
+                   "batch": B, "H": H, "W": W, "microbatch": model.refresh_info().microbatch or None},
         "per_exit_frames_per_s": per_exit_fps,
         "per_exit_ms": {f"EP{ep}": ms for ep, ms in zip(exits, per_exit_ms)},
         "kernel_class_ms_per_step": class_ms,
-        "uninstrumented_ms_per_step": 1e3 * (t3 - t2) / args.steps,
+        "instrumented_ms_per_step": 1e3 * (t3 - t2) / args.steps,
         "roofline": roofline,
     }
 
@@ -146,7 +202,7 @@ def main():
         for ep in exits:
             orc.detect(frames_h[:1], ep)
         tc1 = time.perf_counter()
-        result["cpu_baseline"] = {"value": len(exits) / (tc1 - tc0), "unit": "frames/s", "cores": os.cpu_count() if not os.environ.get("OMP_NUM_THREADS") else int(os.environ["OMP_NUM_THREADS"]),
+        result["cpu_baseline"] = {"value": len(exits) / (tc1 - tc0), "unit": "frames/s", "cores": oracle.num_threads(),
                                   "kind": "oracle", "sample": "frame 0 of the batch at each of EP1..EP4 (4 frame inferences), bf16-storage oracle"}
     print(json.dumps(result))
 

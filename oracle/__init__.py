@@ -61,6 +61,7 @@ def lib():
         L.orc_detect.argtypes = [C.c_void_p, _u8p] + [C.c_int] * 4 + [_f32p, _f32p, _i32p, C.c_void_p]
         L.orc_run_plan.restype = C.c_int
         L.orc_run_plan.argtypes = [C.c_void_p, _u8p] + [C.c_int] * 4 + [_i32p, _f32p, _f32p, _i32p]
+        L.orc_num_threads.restype = C.c_int
         L.free.argtypes = [C.c_void_p]
         _lib = L
     return _lib
@@ -68,6 +69,10 @@ def lib():
 
 def _c(a, dt):
     return np.ascontiguousarray(a, dtype=dt)
+
+
+def num_threads():
+    return int(lib().orc_num_threads())
 
 
 # ------------------------------------------------------------------ steps

@@ -32,6 +32,7 @@
  * parity unpinned for the composed network beyond those per-step pins.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -164,6 +165,9 @@ orc_model *orc_load(const void *blob, size_t nbytes, int precision_override) {
 }
 
 int orc_precision(const orc_model *m) { return m->precision; }
+
+/* Threads the parallel loops use (for the benchmark's report of the CPU baseline). */
+int orc_num_threads(void) { return omp_get_max_threads(); }
 
 /* geometry of exit k (1-based) for an H x W frame: out = floor((n + 2p - k)/s) + 1 */
 static int conv_out(int n, int k, int s, int p) { return (n + 2 * p - k) / s + 1; }

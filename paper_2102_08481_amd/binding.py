@@ -128,6 +128,10 @@ class Model:
         if rc:
             raise ThiaError(rc, lib().thia_last_error(self._h).decode())
 
+    def refresh_info(self):
+        self._check(lib().thia_get_info(self._h, C.byref(self.info)))
+        return self.info
+
     # -- the boundary calls
     def set_stream(self, stream):
         self._check(lib().thia_set_stream(self._h, C.c_void_p(stream.cuda_stream if stream is not None else 0)))
