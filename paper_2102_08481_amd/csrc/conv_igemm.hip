@@ -105,30 +105,32 @@ __device__ inline void static_for(F&& f) {
     }
 }
 
-template <typename T, int BM, int BN, int BKB, typename OutT>
-__global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
+template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, bool ONE, typename OutT>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(const ConvArgs a) {
+    constexpr int NT = 64 * WAVES_M * WAVES_N;  // threads per block
     constexpr int BK = BKB / (int)sizeof(T);   // K elements per tile row
     constexpr int EPC = 16 / (int)sizeof(T);   // elements per 16-byte chunk
     constexpr int CPR = BKB / 16;              // 16-byte chunks per tile row
-    constexpr int RPP = 256 / CPR;             // tile rows covered by one pass of the 256 threads
+    constexpr int RPP = NT / CPR;              // tile rows covered by one pass of the block's threads
     constexpr int PB = BM / RPP, PA = BN / RPP;  // chunks staged per thread (activations, weights)
     constexpr int LDS_ROW = BKB + 16;          // padded LDS row pitch (an odd multiple of 16 bytes)
     constexpr int KK = BKB / 32;               // MFMA k-steps per tile row (32 bytes = 2 lane halves x 16 bytes)
-    constexpr int WM = BM / 2, WN = BN / 2;    // wavefront tile (pixels x channels), wavefronts 2 x 2
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront tile (pixels x channels)
     constexpr int TM = WM / 32, TN = WN / 32;  // 32x32 MFMA tiles per wavefront
     constexpr int LPP = WN / 8;                // epilogue: lanes per pixel (8 channels each)
     constexpr int PPI = 64 / LPP;              // epilogue: pixels per wavefront instruction
     constexpr int NIT = 32 / PPI;              // epilogue: instructions per 32-pixel sub-tile
     constexpr int EPITCH = WN * 4 + 16;        // epilogue: padded fp32 row pitch in LDS (bytes)
     constexpr bool PREFETCH_RES = TM * NIT <= 8;  // residual tile small enough to hold across the K loop
-    static_assert(4 * 32 * EPITCH <= 2 * (BN + BM) * LDS_ROW, "epilogue tile must fit in the pipeline buffers");
+    static_assert(WAVES_M * WAVES_N * 32 * EPITCH <= 2 * (BN + BM) * LDS_ROW, "epilogue tile must fit in the pipeline buffers");
+    static_assert(BM % RPP == 0 && BN % RPP == 0, "tile rows must be a multiple of the rows staged per pass");
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* sA = smem;                     // [2][BN][LDS_ROW]
     unsigned char* sB = smem + 2 * BN * LDS_ROW;  // [2][BM][LDS_ROW]
 
     const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
-    const int wm = wv & 1, wn = wv >> 1;
+    const int wm = wv % WAVES_M, wn = wv / WAVES_M;
     const int HoWo = a.Ho * a.Wo;
     const int M = a.N * HoWo;
     const int K = a.kh * a.kw * a.Cin;
@@ -160,6 +162,8 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
         b_iy0[p] = oy * a.stride - a.pad;
         b_ix0[p] = ox * a.stride - a.pad;
         b_base[p] = (size_t)img * a.H * a.W * a.Cin + (size_t)lchunk * EPC;
+        // 1x1, unpadded: the row's input pixel is fixed for the whole K loop
+        if constexpr (ONE) b_base[p] += ((size_t)b_iy0[p] * a.W + b_ix0[p]) * a.Cin;
     }
     size_t a_base[PA];
     bool a_ok[PA];
@@ -175,6 +179,21 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
     struct Stage { u32x4_t a[PA]; u32x4_t b[PB]; };
     Stage st0;
     auto load_tiles = [&](int kt, Stage& st) {
+        if constexpr (ONE) {
+#pragma unroll
+            for (int p = 0; p < PB; ++p) {
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (b_ok[p]) v = *reinterpret_cast<const u32x4_t*>(in + b_base[p] + (size_t)kt * BK);
+                st.b[p] = v;
+            }
+#pragma unroll
+            for (int p = 0; p < PA; ++p) {
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (a_ok[p]) v = *reinterpret_cast<const u32x4_t*>(wgt + a_base[p] + (size_t)kt * BK);
+                st.a[p] = v;
+            }
+            return;
+        }
         const int tap = kt / cin_tiles;
         const int c0 = (kt - tap * cin_tiles) * BK;
         const int ky = tap / a.kw, kx = tap - ky * a.kw;
@@ -317,28 +336,37 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvArgs a) {
         });
         return;
     }
+    // General path (split outputs, channel counts that are not multiples of 8): the same LDS round trip,
+    // then one element per lane with consecutive lanes on consecutive channels of a pixel, so that stores
+    // stay contiguous within each output row.
+    {
+        unsigned char* ep = smem + (size_t)wv * (32 * EPITCH);
+        static_for<0, TM>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
+            for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int j = 0; j < TM; ++j) {
-            const int pix = m0 + wm * WM + j * 32 + frag_row;
-            if (pix >= M) continue;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int ch = n0 + wn * WN + i * 32 + 8 * v + 4 * (lane >> 5);
-                if (ch >= a.Cout) continue;
-                const float r[4] = {acc[i][j][4 * v], acc[i][j][4 * v + 1], acc[i][j][4 * v + 2], acc[i][j][4 * v + 3]};
-                for (int q = 0; q < 4; ++q) {
-                    const int c = ch + q;
-                    if (c >= a.Cout) break;
-                    float val = r[q] + a.bias[c];
-                    if (res) val += load_elem(res + (size_t)pix * a.Cout + c);
-                    if (a.relu) val = fmaxf(val, 0.f);
-                    if (c < a.n_split) store_elem(out0 + (size_t)pix * a.ld0 + c, val);
-                    else store_elem(out1 + (size_t)pix * a.ld1 + (c - a.n_split), val);
+                for (int v = 0; v < 4; ++v) {
+                    const int chl = i * 32 + 8 * v + 4 * (lane >> 5);
+                    f32x4_t r = {acc[i][j][4 * v], acc[i][j][4 * v + 1], acc[i][j][4 * v + 2], acc[i][j][4 * v + 3]};
+                    *reinterpret_cast<f32x4_t*>(ep + (size_t)frag_row * EPITCH + chl * 4) = r;
                 }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+            for (int e = lane; e < 32 * WN; e += 64) {
+                const int pxl = e / WN, cl = e - pxl * WN;
+                const int pix = m0 + wm * WM + j * 32 + pxl, c = n0 + wn * WN + cl;
+                if (pix >= M || c >= a.Cout) continue;
+                float val = *reinterpret_cast<const float*>(ep + (size_t)pxl * EPITCH + cl * 4) + a.bias[c];
+                if (res) val += load_elem(res + (size_t)pix * a.Cout + c);
+                if (a.relu) val = fmaxf(val, 0.f);
+                if (c < a.n_split) store_elem(out0 + (size_t)pix * a.ld0 + c, val);
+                else store_elem(out1 + (size_t)pix * a.ld1 + (c - a.n_split), val);
             }
-        }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+        });
+    }
 }
 
 bool conv_supported(const ConvArgs& a, int precision) {
@@ -350,11 +378,11 @@ bool conv_supported(const ConvArgs& a, int precision) {
     return true;
 }
 
-template <typename T, int BM, int BN, int BKB, typename OutT>
-static hipError_t launch_one(const ConvArgs& a, hipStream_t s) {
+template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, bool ONE, typename OutT>
+static hipError_t launch_cfg(const ConvArgs& a, hipStream_t s) {
     static bool attr_set = false;
     const size_t lds = (size_t)2 * (BN + BM) * (BKB + 16);
-    auto kern = conv_igemm_kernel<T, BM, BN, BKB, OutT>;
+    auto kern = conv_igemm_kernel<T, BM, BN, BKB, WAVES_M, WAVES_N, ONE, OutT>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -364,20 +392,37 @@ static hipError_t launch_one(const ConvArgs& a, hipStream_t s) {
     const long long tiles = ((M + BM - 1) / BM) * ((a.Cout + BN - 1) / BN);
     if (tiles <= 0 || tiles >= (1ll << 30)) return hipErrorInvalidValue;
     const long long grid = ((tiles + 7) / 8) * 8;  // 8 XCDs x equal ranges; surplus workgroups exit at once
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), lds, s, a);
     return hipGetLastError();
+}
+
+// 1x1 unpadded convolutions (and the FC layers) get the variant without filter-tap bookkeeping.
+template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, typename OutT>
+static hipError_t launch_one(const ConvArgs& a, hipStream_t s) {
+    if (a.kh == 1 && a.kw == 1 && a.pad == 0) return launch_cfg<T, BM, BN, BKB, WAVES_M, WAVES_N, true, OutT>(a, s);
+    return launch_cfg<T, BM, BN, BKB, WAVES_M, WAVES_N, false, OutT>(a, s);
 }
 
 hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream_t s) {
     if (!conv_supported(a, precision)) return hipErrorInvalidValue;
     const bool narrow = a.Cout <= 64;
     if (precision == 0) {
-        return narrow ? launch_one<float, 128, 64, 128, float>(a, s) : launch_one<float, 128, 128, 128, float>(a, s);
+        return narrow ? launch_one<float, 128, 64, 128, 2, 2, float>(a, s) : launch_one<float, 128, 128, 128, 2, 2, float>(a, s);
     }
-    if (out_f32) return narrow ? launch_one<bf16_t, 128, 64, 128, float>(a, s) : launch_one<bf16_t, 128, 128, 128, float>(a, s);
-    // (A 256 x 256 tile with 128 x 128 per wavefront was measured on the long-K layers: with one resident
-    // block per CU it is 5-25 % slower than 128 x 128 at two blocks per CU, so it is not instantiated.)
-    return narrow ? launch_one<bf16_t, 128, 64, 128, bf16_t>(a, s) : launch_one<bf16_t, 128, 128, 128, bf16_t>(a, s);
+    if (out_f32) return narrow ? launch_one<bf16_t, 128, 64, 128, 2, 2, float>(a, s) : launch_one<bf16_t, 128, 128, 128, 2, 2, float>(a, s);
+    // Long-K layers are bound by L2 -> CU bandwidth with a 128 x 128 tile (64 flop per byte staged); a
+    // 256 x 256 tile halves that traffic.  It runs with 8 wavefronts (128 x 64 each), so that one block per
+    // CU still keeps two wavefronts per SIMD, and with 128-byte K rows, which doubles the bytes in flight
+    // per CU against the 64-byte variant (measured 15 % faster).  (4 wavefronts of 128 x 128, and
+    // 256 x 128 with 64-byte K rows, were measured and are slower; with fewer than ~200 tiles the 256 CUs
+    // are better filled by the 128 x 128 tile, except for very long K.)
+    {
+        const long long M = (long long)a.N * a.Ho * a.Wo;
+        const long long K = (long long)a.kh * a.kw * a.Cin;
+        const long long tiles_l = ((M + 255) / 256) * ((a.Cout + 255) / 256);
+        if (a.Cout % 256 == 0 && K >= 512 && (tiles_l >= 200 || (tiles_l >= 150 && K >= 8192)) && a.out1 == nullptr) return launch_one<bf16_t, 256, 256, 128, 2, 4, bf16_t>(a, s);
+    }
+    return narrow ? launch_one<bf16_t, 128, 64, 128, 2, 2, bf16_t>(a, s) : launch_one<bf16_t, 128, 128, 128, 2, 2, bf16_t>(a, s);
 }
 
 }  // namespace thia

@@ -115,12 +115,50 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(const uint8_t* __restric
     __syncthreads();
     const int ix0 = 2 * ox0 - 4, iy0 = 2 * oy0 - 3;
     const uint8_t* f = frames + (size_t)img * 3 * H * W;
-    for (int i = t; i < 3 * MP_ROWS * MP_W; i += 256) {
-        const int c = i / (MP_ROWS * MP_W), r = i - c * (MP_ROWS * MP_W), py = r / MP_W, px = r - py * MP_W;
-        const int iy = iy0 + py, ix = ix0 + px;
-        bf16_t v = 0;  // zero padding of the normalised tensor
-        if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) v = lut[f[((size_t)c * H + iy) * W + ix]];
-        patch[i] = v;
+    // Patch fill: all global loads of a thread are issued before any of them is consumed.  When the
+    // frame width is a multiple of 4 every patch row starts on a 4-byte boundary (ix0 is a multiple of 4)
+    // and is fetched as dwords; out-of-image pixels become the bf16 zero of the normalised tensor.
+    constexpr int DW_ROW = MP_W / 4;                      // 18 dwords per patch row
+    constexpr int N_DW = 3 * MP_ROWS * DW_ROW;            // 1998 dwords per patch
+    constexpr int PER_T = (N_DW + 255) / 256;             // 8 per thread
+    if ((W & 3) == 0) {
+        uint32_t raw[PER_T];
+#pragma unroll
+        for (int q = 0; q < PER_T; ++q) {
+            const int i = q * 256 + t;
+            raw[q] = 0u;
+            if (i < N_DW) {
+                const int c = i / (MP_ROWS * DW_ROW), r = i - c * (MP_ROWS * DW_ROW), py = r / DW_ROW, pd = r - py * DW_ROW;
+                const int iy = iy0 + py, ix = ix0 + 4 * pd;
+                if ((unsigned)iy < (unsigned)H && ix >= 0 && ix + 3 < W)
+                    raw[q] = *reinterpret_cast<const uint32_t*>(f + ((size_t)c * H + iy) * W + ix);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < PER_T; ++q) {
+            const int i = q * 256 + t;
+            if (i < N_DW) {
+                const int c = i / (MP_ROWS * DW_ROW), r = i - c * (MP_ROWS * DW_ROW), py = r / DW_ROW, pd = r - py * DW_ROW;
+                const int iy = iy0 + py, ix = ix0 + 4 * pd;
+                const bool in = (unsigned)iy < (unsigned)H && ix >= 0 && ix + 3 < W;
+                uint32_t lo = 0u, hi = 0u;
+                if (in) {
+                    lo = (uint32_t)lut[raw[q] & 0xffu] | ((uint32_t)lut[(raw[q] >> 8) & 0xffu] << 16);
+                    hi = (uint32_t)lut[(raw[q] >> 16) & 0xffu] | ((uint32_t)lut[raw[q] >> 24] << 16);
+                }
+                uint32_t* d = reinterpret_cast<uint32_t*>(patch + (c * MP_ROWS + py) * MP_W + 4 * pd);
+                d[0] = lo;
+                d[1] = hi;
+            }
+        }
+    } else {
+        for (int i = t; i < 3 * MP_ROWS * MP_W; i += 256) {
+            const int c = i / (MP_ROWS * MP_W), r = i - c * (MP_ROWS * MP_W), py = r / MP_W, px = r - py * MP_W;
+            const int iy = iy0 + py, ix = ix0 + px;
+            bf16_t v = 0;  // zero padding of the normalised tensor
+            if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) v = lut[f[((size_t)c * H + iy) * W + ix]];
+            patch[i] = v;
+        }
     }
     __syncthreads();
 
