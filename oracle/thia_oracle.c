@@ -516,7 +516,9 @@ float *orc_backbone(const orc_model *m, const uint8_t *frames, int n, int H, int
             float *sc = x;
             if (B->shortcut.w) {
                 sc = falloc((size_t)n * B->shortcut.co * ho * wo);
-                run_layer(&B->shortcut, x, n, h, w, B->stride, 0, NULL, 0, bf, bf, sc);
+                /* the projection shortcut is summed with the residual branch before the block's single
+                 * output rounding: it is not a stored activation, so it is not rounded to bf16 */
+                run_layer(&B->shortcut, x, n, h, w, B->stride, 0, NULL, 0, bf, 0, sc);
             }
             float *o = falloc((size_t)n * B->conv3.co * ho * wo);
             run_layer(&B->conv3, t2, n, ho, wo, 1, 0, sc, 1, bf, bf, o);

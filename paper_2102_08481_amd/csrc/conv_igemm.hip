@@ -105,8 +105,10 @@ __device__ inline void static_for(F&& f) {
     }
 }
 
-template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, bool ONE, typename OutT>
+// MODE 0: any filter size; 1: 1x1 unpadded (no tap bookkeeping); 2: 1x1 with a second source tensor.
+template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, int MODE, typename OutT>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(const ConvArgs a) {
+    constexpr bool ONE = MODE >= 1, DUAL = MODE == 2;
     constexpr int NT = 64 * WAVES_M * WAVES_N;  // threads per block
     constexpr int BK = BKB / (int)sizeof(T);   // K elements per tile row
     constexpr int EPC = 16 / (int)sizeof(T);   // elements per 16-byte chunk
@@ -133,7 +135,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     const int wm = wv % WAVES_M, wn = wv / WAVES_M;
     const int HoWo = a.Ho * a.Wo;
     const int M = a.N * HoWo;
-    const int K = a.kh * a.kw * a.Cin;
+    const int K = a.kh * a.kw * a.Cin + (DUAL ? a.Cin2 : 0);
     const int tiles_n = (a.Cout + BN - 1) / BN;
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD a
     // contiguous range of tiles so that tiles sharing an activation tile hit the same L2.
@@ -150,6 +152,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     // ---- per-thread load coordinates: tile row lrow + RPP*p, 16-byte chunk lchunk of the row
     const int lrow = t / CPR, lchunk = t % CPR;
     size_t b_base[PB];
+    size_t b_base2[DUAL ? PB : 1];
+    const T* __restrict__ in2 = static_cast<const T*>(a.in2);
     int b_iy0[PB], b_ix0[PB];
     bool b_ok[PB];
 #pragma unroll
@@ -164,6 +168,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
         b_base[p] = (size_t)img * a.H * a.W * a.Cin + (size_t)lchunk * EPC;
         // 1x1, unpadded: the row's input pixel is fixed for the whole K loop
         if constexpr (ONE) b_base[p] += ((size_t)b_iy0[p] * a.W + b_ix0[p]) * a.Cin;
+        if constexpr (DUAL)
+            b_base2[p] = (((size_t)img * a.H2 + (size_t)oy * a.stride2) * a.W2 + (size_t)ox * a.stride2) * a.Cin2 + (size_t)lchunk * EPC;
     }
     size_t a_base[PA];
     bool a_ok[PA];
@@ -180,11 +186,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     Stage st0;
     auto load_tiles = [&](int kt, Stage& st) {
         if constexpr (ONE) {
+            const int kt1 = a.Cin / BK;  // K tiles of the first source
+            if (!DUAL || kt < kt1) {
 #pragma unroll
-            for (int p = 0; p < PB; ++p) {
-                u32x4_t v = {0u, 0u, 0u, 0u};
-                if (b_ok[p]) v = *reinterpret_cast<const u32x4_t*>(in + b_base[p] + (size_t)kt * BK);
-                st.b[p] = v;
+                for (int p = 0; p < PB; ++p) {
+                    u32x4_t v = {0u, 0u, 0u, 0u};
+                    if (b_ok[p]) v = *reinterpret_cast<const u32x4_t*>(in + b_base[p] + (size_t)kt * BK);
+                    st.b[p] = v;
+                }
+            } else {
+#pragma unroll
+                for (int p = 0; p < PB; ++p) {
+                    u32x4_t v = {0u, 0u, 0u, 0u};
+                    if (b_ok[p]) v = *reinterpret_cast<const u32x4_t*>(in2 + b_base2[DUAL ? p : 0] + (size_t)(kt - kt1) * BK);
+                    st.b[p] = v;
+                }
             }
 #pragma unroll
             for (int p = 0; p < PA; ++p) {
@@ -373,16 +389,20 @@ bool conv_supported(const ConvArgs& a, int precision) {
     const int bk = precision ? 64 : 32;
     if (a.Cin <= 0 || a.Cin % bk) return false;
     if (a.N <= 0 || a.Cout <= 0 || a.Ho <= 0 || a.Wo <= 0 || a.zeros == nullptr) return false;
+    if (a.in2 != nullptr) {
+        if (a.kh != 1 || a.kw != 1 || a.pad != 0 || a.Cin2 <= 0 || a.Cin2 % bk || a.stride2 < 1) return false;
+        if ((a.Ho - 1) * a.stride2 >= a.H2 || (a.Wo - 1) * a.stride2 >= a.W2) return false;
+    }
     if ((long long)a.N * a.Ho * a.Wo >= (1ll << 31)) return false;
     if ((long long)a.N * a.H * a.W * a.Cin >= (1ll << 40)) return false;
     return true;
 }
 
-template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, bool ONE, typename OutT>
+template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, int MODE, typename OutT>
 static hipError_t launch_cfg(const ConvArgs& a, hipStream_t s) {
     static bool attr_set = false;
     const size_t lds = (size_t)2 * (BN + BM) * (BKB + 16);
-    auto kern = conv_igemm_kernel<T, BM, BN, BKB, WAVES_M, WAVES_N, ONE, OutT>;
+    auto kern = conv_igemm_kernel<T, BM, BN, BKB, WAVES_M, WAVES_N, MODE, OutT>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -397,17 +417,21 @@ static hipError_t launch_cfg(const ConvArgs& a, hipStream_t s) {
 }
 
 // 1x1 unpadded convolutions (and the FC layers) get the variant without filter-tap bookkeeping.
-template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, typename OutT>
+template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, typename OutT, bool ALLOW_DUAL = false>
 static hipError_t launch_one(const ConvArgs& a, hipStream_t s) {
-    if (a.kh == 1 && a.kw == 1 && a.pad == 0) return launch_cfg<T, BM, BN, BKB, WAVES_M, WAVES_N, true, OutT>(a, s);
-    return launch_cfg<T, BM, BN, BKB, WAVES_M, WAVES_N, false, OutT>(a, s);
+    if (a.in2 != nullptr) {
+        if constexpr (ALLOW_DUAL) return launch_cfg<T, BM, BN, BKB, WAVES_M, WAVES_N, 2, OutT>(a, s);
+        else return hipErrorInvalidValue;
+    }
+    if (a.kh == 1 && a.kw == 1 && a.pad == 0) return launch_cfg<T, BM, BN, BKB, WAVES_M, WAVES_N, 1, OutT>(a, s);
+    return launch_cfg<T, BM, BN, BKB, WAVES_M, WAVES_N, 0, OutT>(a, s);
 }
 
 hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream_t s) {
     if (!conv_supported(a, precision)) return hipErrorInvalidValue;
     const bool narrow = a.Cout <= 64;
     if (precision == 0) {
-        return narrow ? launch_one<float, 128, 64, 128, 2, 2, float>(a, s) : launch_one<float, 128, 128, 128, 2, 2, float>(a, s);
+        return narrow ? launch_one<float, 128, 64, 128, 2, 2, float>(a, s) : launch_one<float, 128, 128, 128, 2, 2, float, true>(a, s);
     }
     if (out_f32) return narrow ? launch_one<bf16_t, 128, 64, 128, 2, 2, float>(a, s) : launch_one<bf16_t, 128, 128, 128, 2, 2, float>(a, s);
     // Long-K layers are bound by L2 -> CU bandwidth with a 128 x 128 tile (64 flop per byte staged); a
@@ -418,11 +442,11 @@ hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream
     // are better filled by the 128 x 128 tile, except for very long K.)
     {
         const long long M = (long long)a.N * a.Ho * a.Wo;
-        const long long K = (long long)a.kh * a.kw * a.Cin;
+        const long long K = (long long)a.kh * a.kw * a.Cin + (a.in2 ? a.Cin2 : 0);
         const long long tiles_l = ((M + 255) / 256) * ((a.Cout + 255) / 256);
-        if (a.Cout % 256 == 0 && K >= 512 && (tiles_l >= 200 || (tiles_l >= 150 && K >= 8192)) && a.out1 == nullptr) return launch_one<bf16_t, 256, 256, 128, 2, 4, bf16_t>(a, s);
+        if (a.Cout % 256 == 0 && K >= 64 && (tiles_l >= 200 || (tiles_l >= 150 && K >= 8192)) && a.out1 == nullptr) return launch_one<bf16_t, 256, 256, 128, 2, 4, bf16_t, true>(a, s);
     }
-    return narrow ? launch_one<bf16_t, 128, 64, 128, 2, 2, bf16_t>(a, s) : launch_one<bf16_t, 128, 128, 128, 2, 2, bf16_t>(a, s);
+    return narrow ? launch_one<bf16_t, 128, 64, 128, 2, 2, bf16_t>(a, s) : launch_one<bf16_t, 128, 128, 128, 2, 2, bf16_t, true>(a, s);
 }
 
 }  // namespace thia

@@ -25,8 +25,9 @@ struct Layer {
     int co = 0, ci = 0, k = 1;
 };
 struct Block {
-    Layer c1, c2, c3, sc;
+    Layer c1, c2, c3;  // for a stage's first block c3 holds [conv3 | projection shortcut] concatenated along K
     bool has_sc = false;
+    int sc_ci = 0;     // input channels of the shortcut part
     int stride = 1;
 };
 struct ExitUnit {
@@ -299,11 +300,20 @@ struct Scope {  // brackets one launch (group) with events when profiling is on
     }
 };
 
+struct Second {  // second source of a dual 1x1 convolution
+    const void* in = nullptr;
+    int Cin = 0, H = 0, W = 0, stride = 1;
+};
+
 int run_conv(thia_model* m, int cls, const Layer& L, const void* in, int n, int H, int W, int stride, int pad, const void* res,
-             bool relu, bool out_f32, void* out0, void* out1 = nullptr, int n_split = -1) {
+             bool relu, bool out_f32, void* out0, void* out1 = nullptr, int n_split = -1, const Second* second = nullptr) {
     ConvArgs a{};
     a.in = in; a.w = L.w; a.bias = L.b; a.res = res; a.out0 = out0; a.out1 = out1; a.zeros = m->zeros;
-    a.N = n; a.H = H; a.W = W; a.Cin = L.ci; a.Cout = L.co; a.kh = L.k; a.kw = L.k; a.stride = stride; a.pad = pad;
+    a.N = n; a.H = H; a.W = W; a.Cin = L.ci; a.Cout = L.co;
+    if (second) {
+        a.in2 = second->in; a.Cin2 = second->Cin; a.H2 = second->H; a.W2 = second->W; a.stride2 = second->stride;
+        a.Cin = L.ci - second->Cin;
+    } a.kh = L.k; a.kw = L.k; a.stride = stride; a.pad = pad;
     a.Ho = conv_out(H, L.k, stride, pad); a.Wo = conv_out(W, L.k, stride, pad);
     a.relu = relu ? 1 : 0;
     if (out1) { a.n_split = n_split; a.ld0 = n_split; a.ld1 = L.co - n_split; }
@@ -356,12 +366,14 @@ int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int
             const int ho = conv_out(h, 3, B.stride, 1), wo = conv_out(w, 3, B.stride, 1);
             TRY(run_conv(m, THIA_K_CONV, B.c1, x, nb, h, w, 1, 0, nullptr, true, false, ws.act[2]));
             TRY(run_conv(m, THIA_K_CONV, B.c2, ws.act[2], nb, h, w, B.stride, 1, nullptr, true, false, ws.act[3]));
-            const void* shortcut = x;
             if (B.has_sc) {
-                TRY(run_conv(m, THIA_K_CONV, B.sc, x, nb, h, w, B.stride, 0, nullptr, false, false, ws.act[4]));
-                shortcut = ws.act[4];
+                // last 1x1 and projection shortcut share one accumulator: y = relu(W3 t2 + Ws x(strided) + b3 + bs)
+                Second sec;
+                sec.in = x; sec.Cin = B.sc_ci; sec.H = h; sec.W = w; sec.stride = B.stride;
+                TRY(run_conv(m, THIA_K_CONV, B.c3, ws.act[3], nb, ho, wo, 1, 0, nullptr, true, false, y, nullptr, -1, &sec));
+            } else {
+                TRY(run_conv(m, THIA_K_CONV, B.c3, ws.act[3], nb, ho, wo, 1, 0, x, true, false, y));
             }
-            TRY(run_conv(m, THIA_K_CONV, B.c3, ws.act[3], nb, ho, wo, 1, 0, shortcut, true, false, y));
             std::swap(x, y);
             h = ho; w = wo;
         }
@@ -549,11 +561,22 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
             if (!take_layer(r, c1, w, cin, 1) || !take_layer(r, c2, w, w, 3) || !take_layer(r, c3, 4 * w, w, 1)) return bad(THIA_E_BLOB);
             int rc = upload_layer(m, c1, nullptr, B.c1);
             if (!rc) rc = upload_layer(m, c2, nullptr, B.c2);
-            if (!rc) rc = upload_layer(m, c3, nullptr, B.c3);
             if (b == 0) {
                 if (!take_layer(r, sc, 4 * w, cin, 1)) return bad(THIA_E_BLOB);
                 B.has_sc = true;
-                if (!rc) rc = upload_layer(m, sc, nullptr, B.sc);
+                B.sc_ci = cin;
+                // [W3 | Ws] along K, bias b3 + bs: one contraction over (t2 channels, x channels)
+                std::vector<float> wcat((size_t)4 * w * (w + cin)), bcat((size_t)4 * w);
+                for (int o = 0; o < 4 * w; ++o) {
+                    std::memcpy(&wcat[(size_t)o * (w + cin)], c3.w + (size_t)o * w, sizeof(float) * w);
+                    std::memcpy(&wcat[(size_t)o * (w + cin) + w], sc.w + (size_t)o * cin, sizeof(float) * cin);
+                    bcat[o] = c3.b[o] + sc.b[o];
+                }
+                HostLayer cat;
+                cat.w = wcat.data(); cat.b = bcat.data(); cat.co = 4 * w; cat.ci = w + cin; cat.k = 1;
+                if (!rc) rc = upload_layer(m, cat, nullptr, B.c3);
+            } else {
+                if (!rc) rc = upload_layer(m, c3, nullptr, B.c3);
             }
             if (rc) return bad(rc);
             cin = 4 * w;
@@ -600,7 +623,7 @@ void thia_free_model(thia_model* m) {
     if (m->stem_wk) (void)hipFree(m->stem_wk);
     if (m->stem_b) (void)hipFree(m->stem_b);
     for (int s = 0; s < 4; ++s)
-        for (Block& B : m->stage[s]) { free_layer(B.c1); free_layer(B.c2); free_layer(B.c3); free_layer(B.sc); }
+        for (Block& B : m->stage[s]) { free_layer(B.c1); free_layer(B.c2); free_layer(B.c3); }
     for (int e = 0; e < 4; ++e) {
         ExitUnit& E = m->ex[e];
         free_layer(E.lateral); free_layer(E.rpn_conv); free_layer(E.rpn_head); free_layer(E.fc1); free_layer(E.fc2); free_layer(E.pred);

@@ -38,6 +38,10 @@ struct ConvArgs {
     const void* zeros;  // >= 16 zero bytes on the device: source of padded / out-of-range tile chunks
     int N, H, W, Cin, Ho, Wo, Cout, kh, kw, stride, pad;
     int relu, n_split, ld0, ld1;
+    // Optional second source of a 1x1 convolution: out += W[:, Cin:Cin+Cin2] * in2[pixel (oy*stride2, ox*stride2)].
+    // Used to sum a bottleneck's last 1x1 convolution and its projection shortcut in one accumulator.
+    const void* in2;  // null = single source
+    int Cin2, H2, W2, stride2;
 };
 // precision 0: float tensors, fp32 MFMA; 1: bf16 tensors, bf16 MFMA with fp32 accumulation.
 // out_f32: store float outputs even when tensors are bf16.  Returns hipSuccess or the launch error.
