@@ -446,7 +446,7 @@ hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream
         const long long tiles_l = ((M + 255) / 256) * ((a.Cout + 255) / 256);
         if (a.Cout % 256 == 0 && K >= 64 && (tiles_l >= 200 || (tiles_l >= 150 && K >= 8192)) && a.out1 == nullptr) return launch_one<bf16_t, 256, 256, 128, 2, 4, bf16_t, true>(a, s);
     }
-    return narrow ? launch_one<bf16_t, 128, 64, 64, 2, 2, bf16_t>(a, s) : launch_one<bf16_t, 128, 128, 128, 2, 2, bf16_t, true>(a, s);
+    return narrow ? launch_one<bf16_t, 128, 64, 64, 2, 2, bf16_t>(a, s) : launch_one<bf16_t, 128, 128, 128, 2, 4, bf16_t, true>(a, s);
 }
 
 }  // namespace thia
