@@ -302,16 +302,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
         // that each lane owns 8 consecutive channels of one pixel: residual loads and output stores are
         // 16-byte and the lanes of one instruction cover whole lines of the NHWC tensors.
         unsigned char* ep = smem + (size_t)wv * (32 * EPITCH);
+        // residual tiles that were not held across the K loop are fetched one sub-tile ahead of their use
+        Vec8<T> rq0[NIT], rq1[NIT];
+        auto fetch_res = [&](int j, Vec8<T>* dst) {
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int pix = m0 + wm * WM + j * 32 + it * PPI + lane / LPP, ch = n0 + wn * WN + (lane % LPP) * 8;
+                if (pix < M && ch < a.Cout) dst[it] = *reinterpret_cast<const Vec8<T>*>(res + (size_t)pix * a.Cout + ch);
+            }
+        };
+        if (!PREFETCH_RES && res != nullptr) fetch_res(0, rq0);
         static_for<0, TM>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
-            Vec8<T> rnow[NIT];
-            if (!PREFETCH_RES && res != nullptr) {
-#pragma unroll
-                for (int it = 0; it < NIT; ++it) {
-                    const int pix = m0 + wm * WM + j * 32 + it * PPI + lane / LPP, ch = n0 + wn * WN + (lane % LPP) * 8;
-                    if (pix < M && ch < a.Cout) rnow[it] = *reinterpret_cast<const Vec8<T>*>(res + (size_t)pix * a.Cout + ch);
-                }
-            }
+            Vec8<T>* rnow = (j & 1) ? rq1 : rq0;
+            if (!PREFETCH_RES && res != nullptr && j + 1 < TM) fetch_res(j + 1, (j & 1) ? rq0 : rq1);
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -443,6 +447,9 @@ hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream
     {
         const long long M = (long long)a.N * a.Ho * a.Wo;
         const long long K = (long long)a.kh * a.kw * a.Cin + (a.in2 ? a.Cin2 : 0);
+        // Short-K layers are pure streaming: what matters is how many independent tiles a CU has in
+        // flight, so they take the small-footprint 128 x 64 tile (4 blocks of 4 wavefronts per CU).
+        if (K <= 128 && a.out1 == nullptr && a.in2 == nullptr) return launch_one<bf16_t, 128, 64, 64, 2, 2, bf16_t>(a, s);
         const long long tiles_l = ((M + 255) / 256) * ((a.Cout + 255) / 256);
         if (a.Cout % 256 == 0 && K >= 64 && (tiles_l >= 200 || (tiles_l >= 150 && K >= 8192)) && a.out1 == nullptr) return launch_one<bf16_t, 256, 256, 128, 2, 4, bf16_t, true>(a, s);
     }
