@@ -443,7 +443,8 @@ hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream
     // CU still keeps two wavefronts per SIMD, and with 128-byte K rows, which doubles the bytes in flight
     // per CU against the 64-byte variant (measured 15 % faster).  (4 wavefronts of 128 x 128, and
     // 256 x 128 with 64-byte K rows, were measured and are slower; with fewer than ~200 tiles the 256 CUs
-    // are better filled by the 128 x 128 tile, except for very long K.)
+    // are better filled by the 128 x 128 tile, except for very long K; 16 wavefronts of 64 x 64 on the
+    // 256 x 256 tile spill; 256 x 128 with 8 wavefronts and 64-byte rows is 1.5x slower.)
     {
         const long long M = (long long)a.N * a.Ho * a.Wo;
         const long long K = (long long)a.kh * a.kw * a.Cin + (a.in2 ? a.Cin2 : 0);
