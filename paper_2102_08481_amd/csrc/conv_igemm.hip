@@ -185,29 +185,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     struct Stage { u32x4_t a[PA]; u32x4_t b[PB]; };
     Stage st0;
     auto load_tiles = [&](int kt, Stage& st) {
+        // All loads are unconditional so that a K step is one basic block the scheduler can interleave
+        // with the MFMAs: rows beyond M / Cout are clamped to row 0 (they only feed outputs that are never
+        // stored), padded filter taps are fetched from a clamped in-image address and zeroed by a select.
         if constexpr (ONE) {
             const int kt1 = a.Cin / BK;  // K tiles of the first source
             if (!DUAL || kt < kt1) {
 #pragma unroll
-                for (int p = 0; p < PB; ++p) {
-                    u32x4_t v = {0u, 0u, 0u, 0u};
-                    if (b_ok[p]) v = *reinterpret_cast<const u32x4_t*>(in + b_base[p] + (size_t)kt * BK);
-                    st.b[p] = v;
-                }
+                for (int p = 0; p < PB; ++p) st.b[p] = *reinterpret_cast<const u32x4_t*>(in + b_base[p] + (size_t)kt * BK);
             } else {
 #pragma unroll
-                for (int p = 0; p < PB; ++p) {
-                    u32x4_t v = {0u, 0u, 0u, 0u};
-                    if (b_ok[p]) v = *reinterpret_cast<const u32x4_t*>(in2 + b_base2[DUAL ? p : 0] + (size_t)(kt - kt1) * BK);
-                    st.b[p] = v;
-                }
+                for (int p = 0; p < PB; ++p)
+                    st.b[p] = *reinterpret_cast<const u32x4_t*>(in2 + b_base2[DUAL ? p : 0] + (size_t)(kt - kt1) * BK);
             }
 #pragma unroll
-            for (int p = 0; p < PA; ++p) {
-                u32x4_t v = {0u, 0u, 0u, 0u};
-                if (a_ok[p]) v = *reinterpret_cast<const u32x4_t*>(wgt + a_base[p] + (size_t)kt * BK);
-                st.a[p] = v;
-            }
+            for (int p = 0; p < PA; ++p) st.a[p] = *reinterpret_cast<const u32x4_t*>(wgt + a_base[p] + (size_t)kt * BK);
             return;
         }
         const int tap = kt / cin_tiles;
@@ -216,17 +208,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
 #pragma unroll
         for (int p = 0; p < PB; ++p) {
             const int iy = b_iy0[p] + ky, ix = b_ix0[p] + kx;
-            const bool ok = b_ok[p] && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (ok) v = *reinterpret_cast<const u32x4_t*>(in + b_base[p] + ((size_t)iy * a.W + ix) * a.Cin + c0);
-            st.b[p] = v;
+            const bool ok = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+            const int iyc = min(max(iy, 0), a.H - 1), ixc = min(max(ix, 0), a.W - 1);
+            u32x4_t v = *reinterpret_cast<const u32x4_t*>(in + b_base[p] + ((size_t)iyc * a.W + ixc) * a.Cin + c0);
+            const u32x4_t z = {0u, 0u, 0u, 0u};
+            st.b[p] = ok ? v : z;
         }
 #pragma unroll
-        for (int p = 0; p < PA; ++p) {
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (a_ok[p]) v = *reinterpret_cast<const u32x4_t*>(wgt + a_base[p] + (size_t)kt * BK);
-            st.a[p] = v;
-        }
+        for (int p = 0; p < PA; ++p) st.a[p] = *reinterpret_cast<const u32x4_t*>(wgt + a_base[p] + (size_t)kt * BK);
     };
     auto store_tiles = [&](int buf, const Stage& st) {
 #pragma unroll
