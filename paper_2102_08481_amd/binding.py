@@ -26,7 +26,7 @@ EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_mi
            "thia_detect_chunk", "thia_run_plan", "thia_last_error", "thia_set_debug", "thia_debug_tap",
            "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
            "thia_op_rpn_proposals", "thia_op_nms", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
-           "thia_op_stem"]
+           "thia_op_stem", "thia_op_bottleneck", "thia_set_fusion"]
 
 
 class ThiaInfo(C.Structure):
@@ -77,6 +77,8 @@ def lib():
     L.thia_op_select_detections.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp]
     L.thia_op_conv.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i32, i32, i32, vp, i32, i32, vp]
     L.thia_op_stem.argtypes = [vp, vp, i32, i32, i32, vp]
+    L.thia_op_bottleneck.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.thia_set_fusion.argtypes = [vp, i32]
     for name in EXPORTS:
         getattr(L, name)
     _lib = L
@@ -244,6 +246,18 @@ class Model:
             _dev(residual, self.elem)
         self._check(lib().thia_op_conv(self._h, _ptr(x), n, H, W, Cin, w.ctypes.data, b.ctypes.data, Cout, k, stride, pad,
                                        _ptr(residual), int(relu), int(out_f32), _ptr(out)))
+        return out
+
+    def set_fusion(self, on):
+        self._check(lib().thia_set_fusion(self._h, int(bool(on))))
+
+    def op_bottleneck(self, x, w1, b1, w2, b2, w3, b3):
+        """x: cuda bf16 [n,H,W,4*width]; weights numpy fp32 in [Cout,Cin,k,k] order."""
+        _dev(x, self.elem)
+        n, H, W, C4 = x.shape
+        arrs = [np.ascontiguousarray(v, dtype=np.float32) for v in (w1, b1, w2, b2, w3, b3)]
+        out = torch.empty_like(x)
+        self._check(lib().thia_op_bottleneck(self._h, _ptr(x), n, H, W, C4 // 4, *[v.ctypes.data for v in arrs], _ptr(out)))
         return out
 
     def op_stem(self, frames):

@@ -1,0 +1,308 @@
+// One identity bottleneck block (1x1 -> 3x3 -> 1x1 + input, stride 1) of the backbone in a single
+// kernel on the CDNA4 matrix cores (gfx950), bf16 tensors with fp32 accumulation.
+//
+// Layer by layer the narrow stages are pure HBM streaming: every 1x1 re-reads or re-writes the
+// 4*WD-channel tensor.  Here a 256-thread block (4 wavefronts) owns an 8 x 16 pixel tile of one frame and
+// keeps the two WD-channel intermediates in LDS, so the wide tensor is read once (plus halo) and written
+// once per block:
+//   phase 1  t1 = relu(W1 x + b1) on the 10 x 18 halo tile (192 rows with padding), K = 4*WD walked in
+//            64-channel steps through an LDS staging tile (coalesced 16-byte loads); halo pixels outside
+//            the frame are set to zero, which is the zero padding of the 3x3 that follows;
+//   phase 2  t2 = relu(W2 * t1 + b2): the MFMA pixel operand is read straight from the t1 tile at the
+//            tap's row offset, no im2col copy;
+//   phase 3  y = relu(W3 t2 + b3 + x): per 32-pixel sub-tile the fp32 result goes through a
+//            wavefront-private LDS transpose so that residual loads and stores are 16 bytes per lane
+//            and cover whole lines of the NHWC tensors.
+// Both intermediates are rounded to bf16 exactly where the layer-by-layer path stores them.
+// Weights never pass through LDS: they are pre-packed in MFMA fragment order (one coalesced 1 KiB
+// load per 32-channel x 16-k fragment) and stay in L2.
+#include <type_traits>
+
+#include "thia_internal.h"
+
+namespace thia {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
+namespace {
+
+__device__ inline void mma(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), acc, 0, 0, 0);
+}
+__device__ inline uint32_t pack2(float lo, float hi) { return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16); }
+
+template <int I, int N, typename F>
+__device__ inline void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+constexpr int TH = 8, TW = 16;          // output tile (pixels)
+constexpr int HALO_W = TW + 2;          // halo tile width
+constexpr int NH = (TH + 2) * HALO_W;   // halo pixels (180)
+constexpr int NHP = 192;                // ... padded to whole 32-row MFMA tiles
+constexpr int NPX = TH * TW;            // 128
+
+}  // namespace
+
+template <int WD>
+__global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlockArgs a) {
+    static_assert(WD == 64, "work split below is written for 64-channel intermediates");
+    constexpr int C4 = 4 * WD;
+    constexpr int BK = 64;                 // phase-1 K step (channels)
+    constexpr int XP = BK * 2 + 16;        // LDS row pitch of the x staging tile (bytes)
+    constexpr int TP = WD * 2 + 16;        // LDS row pitch of t1 / t2 (bytes)
+    constexpr int KT1 = C4 / BK;           // phase-1 K steps
+    constexpr int KS1 = C4 / 16, KS2 = 9 * WD / 16, KS3 = WD / 16;  // 16-wide MFMA k-steps per phase
+    constexpr int EPITCH = 64 * 4 + 16;    // fp32 epilogue row: 64 channels + pad (bytes)
+    constexpr int RING = 8;                // weight fragments in flight in phase 2
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* T1 = smem;                        // [NHP][TP]
+    unsigned char* XS = smem + NHP * TP;             // [NHP][XP]
+    unsigned char* T2 = smem + NHP * (TP + XP);      // [NPX][TP]
+    static_assert(4 * 32 * EPITCH <= NHP * (TP + XP), "epilogue tiles reuse the t1 / staging area");
+
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    const int tiles_x = (a.W + TW - 1) / TW, tiles_y = (a.H + TH - 1) / TH;
+    const int total = a.N * tiles_y * tiles_x;
+    const int per_xcd = (total + 7) >> 3;   // contiguous tile range per XCD (block id & 7 selects the XCD)
+    const int tile = (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
+    if (tile >= total) return;
+    const int img = tile / (tiles_y * tiles_x);
+    const int trem = tile - img * (tiles_y * tiles_x);
+    const int y0 = (trem / tiles_x) * TH, x0 = (trem % tiles_x) * TW;
+    const bf16_t* __restrict__ xin = a.x + (size_t)img * a.H * a.W * C4;
+    bf16_t* __restrict__ yout = a.y + (size_t)img * a.H * a.W * C4;
+
+    // ------------------------------------------------------------------ phase 1: t1 on the halo tile
+    // staging coordinates: 16-byte chunk lc of halo rows lr + 32 p; out-of-frame rows read a clamped
+    // pixel (their t1 is forced to zero below)
+    const int lc = t & 7, lr = t >> 3;
+    uint32_t xoff[6];
+#pragma unroll
+    for (int p = 0; p < 6; ++p) {
+        const int r = lr + 32 * p;
+        const int hy = r / HALO_W, hx = r - hy * HALO_W;
+        const int iy = min(max(y0 - 1 + hy, 0), a.H - 1), ix = min(max(x0 - 1 + hx, 0), a.W - 1);
+        xoff[p] = (uint32_t)((iy * a.W + ix) * C4 + lc * 8);
+    }
+    const int cw = wv & 1;        // 32-channel half of the WD intermediates owned in phases 1 and 2
+    const int pw = wv >> 1;       // pixel sub-tiles pw, pw + 2, ...
+    const u32x4_t* __restrict__ w1f = reinterpret_cast<const u32x4_t*>(a.w1f) + (size_t)cw * KS1 * 64 + lane;
+    const u32x4_t* __restrict__ w2f = reinterpret_cast<const u32x4_t*>(a.w2f) + (size_t)cw * KS2 * 64 + lane;
+    const u32x4_t* __restrict__ w3f = reinterpret_cast<const u32x4_t*>(a.w3f) + (size_t)(2 * wv) * KS3 * 64 + lane;
+
+    u32x4_t xs[6];
+    auto load_x = [&](int kt) {
+#pragma unroll
+        for (int p = 0; p < 6; ++p) xs[p] = *reinterpret_cast<const u32x4_t*>(xin + xoff[p] + kt * BK);
+    };
+    load_x(0);
+    u32x4_t wa[KS1];
+#pragma unroll
+    for (int s = 0; s < KS1; ++s) wa[s] = w1f[s * 64];
+
+    f32x16_t acc1[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc1[j][e] = 0.f;
+
+    static_for<0, KT1>([&](auto ktc) {
+        constexpr int kt = decltype(ktc)::value;
+        if (kt > 0) __syncthreads();   // every wavefront is done with the previous staging tile
+#pragma unroll
+        for (int p = 0; p < 6; ++p) *reinterpret_cast<u32x4_t*>(XS + (lr + 32 * p) * XP + lc * 16) = xs[p];
+        if (kt + 1 < KT1) load_x(kt + 1);
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const u32x4_t b = *reinterpret_cast<const u32x4_t*>(XS + ((pw + 2 * j) * 32 + l32) * XP + kk * 32 + lh * 16);
+                mma(acc1[j], wa[kt * (BK / 16) + kk], b);
+            }
+        }
+    });
+
+    // first weight fragments of phase 2 are requested before the t1 epilogue
+    u32x4_t ring[RING];
+#pragma unroll
+    for (int s = 0; s < RING; ++s) ring[s] = w2f[s * 64];
+
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        const int r = (pw + 2 * j) * 32 + l32;
+        const int hy = r / HALO_W, hx = r - hy * HALO_W;
+        const int iy = y0 - 1 + hy, ix = x0 - 1 + hx;
+        const bool ok = r < NH && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int ch = cw * 32 + 8 * v + 4 * lh;
+            const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(a.b1 + ch);
+            const float r0 = ok ? fmaxf(acc1[j][4 * v] + bv.x, 0.f) : 0.f, r1 = ok ? fmaxf(acc1[j][4 * v + 1] + bv.y, 0.f) : 0.f;
+            const float r2 = ok ? fmaxf(acc1[j][4 * v + 2] + bv.z, 0.f) : 0.f, r3 = ok ? fmaxf(acc1[j][4 * v + 3] + bv.w, 0.f) : 0.f;
+            u32x2_t o = {pack2(r0, r1), pack2(r2, r3)};
+            *reinterpret_cast<u32x2_t*>(T1 + r * TP + ch * 2) = o;
+        }
+    }
+    __syncthreads();
+
+    // ------------------------------------------------------------------ phase 2: t2 = relu(W2 * t1 + b2)
+    f32x16_t acc2[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc2[j][e] = 0.f;
+    int hb[2];   // halo row of the tap (0, 0) input of this lane's pixel
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int p = (pw + 2 * j) * 32 + l32;
+        hb[j] = (p / TW) * HALO_W + (p % TW);
+    }
+    static_for<0, KS2>([&](auto sc) {
+        constexpr int s = decltype(sc)::value;
+        constexpr int tap = s / (WD / 16), kk = s % (WD / 16);
+        constexpr int ky = tap / 3, kx = tap % 3;
+        const u32x4_t wfrag = ring[s % RING];
+        if (s + RING < KS2) ring[s % RING] = w2f[(s + RING) * 64];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const u32x4_t b = *reinterpret_cast<const u32x4_t*>(T1 + (hb[j] + ky * HALO_W + kx) * TP + kk * 32 + lh * 16);
+            mma(acc2[j], wfrag, b);
+        }
+    });
+
+    // residual tile and last-layer weights: requested now, used after the barrier
+    u32x4_t w3[2][KS3];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int kk = 0; kk < KS3; ++kk) w3[i][kk] = w3f[(i * KS3 + kk) * 64];
+    u32x4_t rres[4][4];
+    uint32_t ooff[4][4];   // element offset of the lane's 8 output channels; ~0u = outside the frame
+#pragma unroll
+    for (int pt = 0; pt < 4; ++pt)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int item = lane + 64 * it;
+            const int p = pt * 32 + (item >> 3), chunk = item & 7;
+            const int oy = y0 + p / TW, ox = x0 + p % TW;
+            const bool ok = oy < a.H && ox < a.W;
+            const uint32_t off = (uint32_t)((min(oy, a.H - 1) * a.W + min(ox, a.W - 1)) * C4 + wv * 64 + chunk * 8);
+            rres[pt][it] = *reinterpret_cast<const u32x4_t*>(xin + off);
+            ooff[pt][it] = ok ? off : ~0u;
+        }
+
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int p = (pw + 2 * j) * 32 + l32;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int ch = cw * 32 + 8 * v + 4 * lh;
+            const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(a.b2 + ch);
+            u32x2_t o = {pack2(fmaxf(acc2[j][4 * v] + bv.x, 0.f), fmaxf(acc2[j][4 * v + 1] + bv.y, 0.f)),
+                         pack2(fmaxf(acc2[j][4 * v + 2] + bv.z, 0.f), fmaxf(acc2[j][4 * v + 3] + bv.w, 0.f))};
+            *reinterpret_cast<u32x2_t*>(T2 + p * TP + ch * 2) = o;
+        }
+    }
+    __syncthreads();   // t2 complete; t1 and the staging tile are dead from here on
+
+    // ------------------------------------------------------------------ phase 3: y = relu(W3 t2 + b3 + x)
+    // this wavefront: output channels 64 wv .. 64 wv + 63 of all 128 pixels, one 32-pixel sub-tile at a time
+    unsigned char* ep = smem + wv * (32 * EPITCH);
+    static_for<0, 4>([&](auto ptc) {
+        constexpr int pt = decltype(ptc)::value;
+        f32x16_t acc3[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc3[i][e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KS3; ++kk) {
+            const u32x4_t b = *reinterpret_cast<const u32x4_t*>(T2 + (pt * 32 + l32) * TP + kk * 32 + lh * 16);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) mma(acc3[i], w3[i][kk], b);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int chl = i * 32 + 8 * v + 4 * lh;
+                const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(a.b3 + wv * 64 + chl);
+                f32x4_t r = {acc3[i][4 * v] + bv.x, acc3[i][4 * v + 1] + bv.y, acc3[i][4 * v + 2] + bv.z, acc3[i][4 * v + 3] + bv.w};
+                *reinterpret_cast<f32x4_t*>(ep + l32 * EPITCH + chl * 4) = r;
+            }
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the region is private to this wavefront
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int item = lane + 64 * it;
+            const int pxl = item >> 3, chunk = item & 7;
+            const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(ep + pxl * EPITCH + chunk * 32);
+            const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(ep + pxl * EPITCH + chunk * 32 + 16);
+            const uint32_t q[4] = {rres[pt][it].x, rres[pt][it].y, rres[pt][it].z, rres[pt][it].w};
+            const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            u32x4_t o;
+            uint32_t ow[4];
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                const float v0 = fmaxf(f[2 * h] + __uint_as_float(q[h] << 16), 0.f);
+                const float v1 = fmaxf(f[2 * h + 1] + __uint_as_float(q[h] & 0xffff0000u), 0.f);
+                ow[h] = pack2(v0, v1);
+            }
+            o.x = ow[0]; o.y = ow[1]; o.z = ow[2]; o.w = ow[3];
+            if (ooff[pt][it] != ~0u) *reinterpret_cast<u32x4_t*>(yout + ooff[pt][it]) = o;
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_wave_barrier();
+    });
+}
+
+bool fused_block_supported(const FusedBlockArgs& a, int width) {
+    if (width != 64) return false;
+    if (!a.x || !a.y || a.x == a.y || !a.w1f || !a.w2f || !a.w3f || !a.b1 || !a.b2 || !a.b3) return false;
+    if (a.N <= 0 || a.H <= 0 || a.W <= 0) return false;
+    if ((long long)a.H * a.W * 4 * width >= (1ll << 31)) return false;   // 32-bit element offsets within a frame
+    const long long tiles = (long long)a.N * ((a.H + TH - 1) / TH) * ((a.W + TW - 1) / TW);
+    return tiles < (1ll << 30);
+}
+
+hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s) {
+    if (!fused_block_supported(a, width)) return hipErrorInvalidValue;
+    constexpr int WD = 64;
+    constexpr size_t lds = (size_t)NHP * ((WD * 2 + 16) + (64 * 2 + 16)) + (size_t)NPX * (WD * 2 + 16);
+    static bool attr_set = false;
+    auto kern = bottleneck_fused_kernel<WD>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long long tiles = (long long)a.N * ((a.H + TH - 1) / TH) * ((a.W + TW - 1) / TW);
+    const long long grid = ((tiles + 7) / 8) * 8;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, a);
+    return hipGetLastError();
+}
+
+// Host-side packing of a [Cout][K] bf16 weight matrix (K contiguous) into MFMA fragment order:
+// fragment (ct, ks) is 64 lanes x 8 elements, lane l holding W[32 ct + l % 32][16 ks + 8 (l / 32) .. + 7].
+void pack_mfma_fragments(const bf16_t* w, int Cout, int K, bf16_t* dst) {
+    const int KS = K / 16;
+    for (int ct = 0; ct < Cout / 32; ++ct)
+        for (int ks = 0; ks < KS; ++ks)
+            for (int l = 0; l < 64; ++l)
+                for (int e = 0; e < 8; ++e)
+                    dst[(((size_t)ct * KS + ks) * 64 + l) * 8 + e] = w[(size_t)(ct * 32 + l % 32) * K + ks * 16 + 8 * (l / 32) + e];
+}
+
+}  // namespace thia

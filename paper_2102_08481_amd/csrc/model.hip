@@ -29,6 +29,8 @@ struct Block {
     bool has_sc = false;
     int sc_ci = 0;     // input channels of the shortcut part
     int stride = 1;
+    // identity blocks the single-kernel bottleneck covers: the three weight matrices in MFMA fragment order
+    bf16_t *f1 = nullptr, *f2 = nullptr, *f3 = nullptr;
 };
 struct ExitUnit {
     Layer lateral, rpn_conv, rpn_head /* obj (A) ++ delta (4A) */, fc1, fc2, pred /* cls (Kc) ++ box (4Kc) */;
@@ -72,6 +74,7 @@ struct thia_model {
     char* warena = nullptr;
     hipStream_t stream = nullptr;
     int user_mb = 0;
+    bool fuse_blocks = true;  // identity bottlenecks as one kernel where a variant exists
     Workspace ws;
     bool debug = false;
     Tap taps[THIA_TAP_COUNT];
@@ -162,6 +165,17 @@ int upload_layer(thia_model* m, const HostLayer& a, const HostLayer* b2, Layer& 
     HIP_TRY(m, hipMemcpy(out.w, host.data(), host.size(), hipMemcpyHostToDevice));
     HIP_TRY(m, hipMalloc(reinterpret_cast<void**>(&out.b), bias.size() * 4));
     HIP_TRY(m, hipMemcpy(out.b, bias.data(), bias.size() * 4, hipMemcpyHostToDevice));
+    return THIA_OK;
+}
+// Upload one layer's weights in MFMA fragment order (bf16 models only).
+int upload_fragments(thia_model* m, const HostLayer& a, bf16_t** out) {
+    std::vector<unsigned char> host;
+    repack(a, 1, host);
+    const int K = a.ci * a.k * a.k;
+    std::vector<bf16_t> frag((size_t)a.co * K);
+    pack_mfma_fragments(reinterpret_cast<const bf16_t*>(host.data()), a.co, K, frag.data());
+    HIP_TRY(m, hipMalloc(reinterpret_cast<void**>(out), frag.size() * 2));
+    HIP_TRY(m, hipMemcpy(*out, frag.data(), frag.size() * 2, hipMemcpyHostToDevice));
     return THIA_OK;
 }
 void free_layer(Layer& L) {
@@ -364,6 +378,18 @@ int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int
     for (int s = 0; s < ep; ++s)
         for (const Block& B : m->stage[s]) {
             const int ho = conv_out(h, 3, B.stride, 1), wo = conv_out(w, 3, B.stride, 1);
+            if (B.f1 && m->fuse_blocks) {
+                FusedBlockArgs fa{};
+                fa.x = static_cast<const bf16_t*>(x); fa.y = static_cast<bf16_t*>(y);
+                fa.w1f = B.f1; fa.w2f = B.f2; fa.w3f = B.f3; fa.b1 = B.c1.b; fa.b2 = B.c2.b; fa.b3 = B.c3.b;
+                fa.N = nb; fa.H = h; fa.W = w;
+                if (fused_block_supported(fa, B.c1.co)) {
+                    Scope sc(m, THIA_K_CONV);
+                    HIP_TRY(m, launch_fused_block(fa, B.c1.co, m->stream));
+                    std::swap(x, y);
+                    continue;
+                }
+            }
             TRY(run_conv(m, THIA_K_CONV, B.c1, x, nb, h, w, 1, 0, nullptr, true, false, ws.act[2]));
             TRY(run_conv(m, THIA_K_CONV, B.c2, ws.act[2], nb, h, w, B.stride, 1, nullptr, true, false, ws.act[3]));
             if (B.has_sc) {
@@ -577,6 +603,11 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
                 if (!rc) rc = upload_layer(m, cat, nullptr, B.c3);
             } else {
                 if (!rc) rc = upload_layer(m, c3, nullptr, B.c3);
+                if (m->precision == 1 && w == 64) {   // widths the single-kernel bottleneck is written for
+                    if (!rc) rc = upload_fragments(m, c1, &B.f1);
+                    if (!rc) rc = upload_fragments(m, c2, &B.f2);
+                    if (!rc) rc = upload_fragments(m, c3, &B.f3);
+                }
             }
             if (rc) return bad(rc);
             cin = 4 * w;
@@ -623,7 +654,13 @@ void thia_free_model(thia_model* m) {
     if (m->stem_wk) (void)hipFree(m->stem_wk);
     if (m->stem_b) (void)hipFree(m->stem_b);
     for (int s = 0; s < 4; ++s)
-        for (Block& B : m->stage[s]) { free_layer(B.c1); free_layer(B.c2); free_layer(B.c3); }
+        for (Block& B : m->stage[s]) {
+            free_layer(B.c1); free_layer(B.c2); free_layer(B.c3);
+            if (B.f1) (void)hipFree(B.f1);
+            if (B.f2) (void)hipFree(B.f2);
+            if (B.f3) (void)hipFree(B.f3);
+            B.f1 = B.f2 = B.f3 = nullptr;
+        }
     for (int e = 0; e < 4; ++e) {
         ExitUnit& E = m->ex[e];
         free_layer(E.lateral); free_layer(E.rpn_conv); free_layer(E.rpn_head); free_layer(E.fc1); free_layer(E.fc2); free_layer(E.pred);
@@ -818,6 +855,55 @@ int thia_op_conv(thia_model* m, const void* in, int n, int H, int W, int Cin, co
     free_layer(L);
     if (rc != THIA_OK) return rc;
     if (e2 != hipSuccess) return fail_hip(m, e2, "conv sync");
+    return THIA_OK;
+}
+
+int thia_set_fusion(thia_model* m, int on) {
+    if (!m) return THIA_E_BADARG;
+    m->fuse_blocks = on != 0;
+    return THIA_OK;
+}
+
+int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int width, const float* w1, const float* b1, const float* w2,
+                       const float* b2, const float* w3, const float* b3, void* out) {
+    if (!m || !in || !out || !w1 || !b1 || !w2 || !b2 || !w3 || !b3 || n <= 0 || H <= 0 || W <= 0 || in == out)
+        return fail(m, THIA_E_BADARG, "bad arguments");
+    if (m->precision != 1) return fail(m, THIA_E_SHAPE, "the single-kernel bottleneck exists for bf16 models only");
+    HostLayer l1, l2, l3;
+    l1.w = w1; l1.b = b1; l1.co = width; l1.ci = 4 * width; l1.k = 1;
+    l2.w = w2; l2.b = b2; l2.co = width; l2.ci = width; l2.k = 3;
+    l3.w = w3; l3.b = b3; l3.co = 4 * width; l3.ci = width; l3.k = 1;
+    FusedBlockArgs fa{};
+    fa.x = static_cast<const bf16_t*>(in); fa.y = static_cast<bf16_t*>(out);
+    fa.N = n; fa.H = H; fa.W = W;
+    bf16_t* f[3] = {nullptr, nullptr, nullptr};
+    float* bias = nullptr;
+    int rc = THIA_OK;
+    auto cleanup = [&]() {
+        for (bf16_t* q : f) if (q) (void)hipFree(q);
+        if (bias) (void)hipFree(bias);
+    };
+    if (width != 64) return fail(m, THIA_E_SHAPE, "unsupported bottleneck width");
+    rc = upload_fragments(m, l1, &f[0]);
+    if (!rc) rc = upload_fragments(m, l2, &f[1]);
+    if (!rc) rc = upload_fragments(m, l3, &f[2]);
+    if (!rc && hipMalloc(reinterpret_cast<void**>(&bias), (size_t)6 * width * 4) != hipSuccess) rc = fail(m, THIA_E_NOMEM, "bias allocation failed");
+    if (!rc) {
+        std::vector<float> hb((size_t)6 * width);
+        std::memcpy(hb.data(), b1, sizeof(float) * width);
+        std::memcpy(hb.data() + width, b2, sizeof(float) * width);
+        std::memcpy(hb.data() + 2 * width, b3, sizeof(float) * 4 * width);
+        if (hipMemcpy(bias, hb.data(), hb.size() * 4, hipMemcpyHostToDevice) != hipSuccess) rc = fail(m, THIA_E_HIP, "bias upload failed");
+    }
+    if (rc) { cleanup(); return rc; }
+    fa.w1f = f[0]; fa.w2f = f[1]; fa.w3f = f[2];
+    fa.b1 = bias; fa.b2 = bias + width; fa.b3 = bias + 2 * width;
+    hipError_t e = fused_block_supported(fa, width) ? launch_fused_block(fa, width, m->stream) : hipErrorInvalidValue;
+    hipError_t e2 = hipStreamSynchronize(m->stream);
+    cleanup();
+    if (e == hipErrorInvalidValue) return fail(m, THIA_E_SHAPE, "shape not covered by the single-kernel bottleneck");
+    if (e != hipSuccess) return fail_hip(m, e, "launch_fused_block");
+    if (e2 != hipSuccess) return fail_hip(m, e2, "bottleneck sync");
     return THIA_OK;
 }
 

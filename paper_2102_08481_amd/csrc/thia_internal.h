@@ -49,6 +49,23 @@ hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream
 // Shapes the kernel accepts.
 bool conv_supported(const ConvArgs& a, int precision);
 
+// ---------------------------------------------------------------- fused identity bottleneck (bf16)
+// y = relu(W3 relu(W2 * relu(W1 x + b1) + b2) + b3 + x), stride 1, x and y [N][H][W][4*width] NHWC bf16 (distinct
+// buffers).  w1f / w2f / w3f are the three weight matrices ([width][4 width], [width][3][3][width],
+// [4 width][width], K contiguous) in MFMA fragment order (pack_mfma_fragments).
+struct FusedBlockArgs {
+    const bf16_t* x;
+    bf16_t* y;
+    const bf16_t *w1f, *w2f, *w3f;
+    const float *b1, *b2, *b3;
+    int N, H, W;
+};
+bool fused_block_supported(const FusedBlockArgs& a, int width);
+hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s);
+// w [Cout][K] (Cout % 32 == 0, K % 16 == 0) -> dst, Cout*K elements: fragment (ct, ks) = 64 lanes x 8 elements,
+// lane l holds w[32 ct + l % 32][16 ks + 8 (l / 32) .. + 7].
+void pack_mfma_fragments(const bf16_t* w, int Cout, int K, bf16_t* dst);
+
 // ---------------------------------------------------------------- stem + pool
 // frames u8 [n,3,H,W]; out T [n,Hs,Ws,64] NHWC with ReLU applied.  x = (u8 - mean) / stdv, zero padding
 // after normalisation.  precision 0 uses w: fp32 [(c*7+ky)*7+kx][64]; precision 1 uses wk: bf16

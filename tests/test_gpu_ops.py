@@ -68,6 +68,47 @@ def test_conv_op_matches_oracle(precision, case):
         assert relerr(got, ref) <= tol, (case, use_res, relu, out_f32, relerr(got, ref))
 
 
+@pytest.mark.parametrize("shape", [(2, 21, 37), (1, 5, 7), (3, 41, 50), (1, 8, 16)])
+def test_bottleneck_op_matches_oracle(shape):
+    """Single-kernel identity bottleneck against the oracle's three convolutions (bf16 storage mode).
+    Three roundings are chained, so besides the one-ulp flip of the output (2^-7, see above) a flipped
+    intermediate element can move an output by a fraction of an ulp more: the bound is 2^-6, and the
+    share of elements that differ at all is reported by the assertion message."""
+    m, _ = _model(1)
+    n, H, W = shape
+    wd = 64
+    rs = np.random.RandomState(H * 131 + W)
+    x = _bf16(np.abs(rs.randn(n, 4 * wd, H, W)).astype(np.float32))
+    w1 = (rs.randn(wd, 4 * wd, 1, 1) * np.sqrt(2.0 / (4 * wd))).astype(np.float32)
+    w2 = (rs.randn(wd, wd, 3, 3) * np.sqrt(2.0 / (9 * wd))).astype(np.float32)
+    w3 = (rs.randn(4 * wd, wd, 1, 1) * np.sqrt(2.0 / wd)).astype(np.float32)
+    b1, b2, b3 = [(rs.randn(c) * 0.1).astype(np.float32) for c in (wd, wd, 4 * wd)]
+    t1 = oracle.conv2d(x, w1, b1, relu=True, bf16_weights=1, round_out=1)
+    t2 = oracle.conv2d(t1, w2, b2, pad=1, relu=True, bf16_weights=1, round_out=1)
+    ref = oracle.conv2d(t2, w3, b3, residual=x, relu=True, bf16_weights=1, round_out=1)
+    got = m.op_bottleneck(to_dev(nchw_to_nhwc(x), m.elem), w1, b1, w2, b2, w3, b3)
+    torch.cuda.synchronize()
+    got = nhwc_to_nchw(got.float().cpu().numpy())
+    assert got.shape == ref.shape
+    differ = float(np.mean(got != ref))
+    assert relerr(got, ref) <= 2.0 ** -6, (shape, relerr(got, ref), differ)
+    assert differ <= 0.02, (shape, differ)
+
+
+def test_bottleneck_op_rejects_unsupported():
+    from paper_2102_08481_amd import ThiaError
+    m, _ = _model(1)
+    x = torch.zeros((1, 8, 8, 128), dtype=torch.bfloat16, device="cuda")
+    z = lambda *s: np.zeros(s, np.float32)
+    with pytest.raises(ThiaError) as e:
+        m.op_bottleneck(x, z(32, 128, 1, 1), z(32), z(32, 32, 3, 3), z(32), z(128, 32, 1, 1), z(128))
+    assert e.value.code == -3
+    m32, _ = _model(0)
+    with pytest.raises(ThiaError):
+        m32.op_bottleneck(torch.zeros((1, 8, 8, 256), dtype=torch.float32, device="cuda"), z(64, 256, 1, 1), z(64), z(64, 64, 3, 3), z(64),
+                          z(256, 64, 1, 1), z(256))
+
+
 @pytest.mark.parametrize("precision", [0, 1])
 def test_stem_op_matches_oracle(precision):
     m, blob = _model(precision)
