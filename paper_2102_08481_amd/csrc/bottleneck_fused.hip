@@ -33,7 +33,7 @@ namespace {
 __device__ inline void mma(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b) {
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), acc, 0, 0, 0);
 }
-__device__ inline uint32_t pack2(float lo, float hi) { return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16); }
+__device__ inline uint32_t pack2(float lo, float hi) { return pack_bf16x2(lo, hi); }
 
 template <int I, int N, typename F>
 __device__ inline void static_for(F&& f) {
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
     constexpr int KT1 = C4 / BK;           // phase-1 K steps
     constexpr int KS1 = C4 / 16, KS2 = 9 * WD / 16, KS3 = WD / 16;  // 16-wide MFMA k-steps per phase
     constexpr int EPITCH = 64 * 4 + 16;    // fp32 epilogue row: 64 channels + pad (bytes)
-    constexpr int RING = 8;                // weight fragments in flight in phase 2
+    constexpr int RING = 16;               // weight fragments in flight in phase 2
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* T1 = smem;                        // [NHP][TP]
@@ -101,15 +101,17 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
     const u32x4_t* __restrict__ w2f = reinterpret_cast<const u32x4_t*>(a.w2f) + (size_t)cw * KS2 * 64 + lane;
     const u32x4_t* __restrict__ w3f = reinterpret_cast<const u32x4_t*>(a.w3f) + (size_t)(2 * wv) * KS3 * 64 + lane;
 
-    u32x4_t xs[6];
-    auto load_x = [&](int kt) {
-#pragma unroll
-        for (int p = 0; p < 6; ++p) xs[p] = *reinterpret_cast<const u32x4_t*>(xin + xoff[p] + kt * BK);
-    };
-    load_x(0);
+    // the whole halo tile of x (4 K steps x 6 chunks per thread) is requested up front: one exposed
+    // memory latency per tile instead of one per K step
+    u32x4_t xs[KT1][6];
     u32x4_t wa[KS1];
+    static_for<0, KT1>([&](auto ktc) {   // issue order = use order (loads retire in order)
+        constexpr int kt = decltype(ktc)::value;
 #pragma unroll
-    for (int s = 0; s < KS1; ++s) wa[s] = w1f[s * 64];
+        for (int p = 0; p < 6; ++p) xs[kt][p] = *reinterpret_cast<const u32x4_t*>(xin + xoff[p] + kt * BK);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) wa[kt * (BK / 16) + kk] = w1f[(kt * (BK / 16) + kk) * 64];
+    });
 
     f32x16_t acc1[3];
 #pragma unroll
@@ -121,8 +123,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
         constexpr int kt = decltype(ktc)::value;
         if (kt > 0) __syncthreads();   // every wavefront is done with the previous staging tile
 #pragma unroll
-        for (int p = 0; p < 6; ++p) *reinterpret_cast<u32x4_t*>(XS + (lr + 32 * p) * XP + lc * 16) = xs[p];
-        if (kt + 1 < KT1) load_x(kt + 1);
+        for (int p = 0; p < 6; ++p) *reinterpret_cast<u32x4_t*>(XS + (lr + 32 * p) * XP + lc * 16) = xs[kt][p];
         __syncthreads();
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {

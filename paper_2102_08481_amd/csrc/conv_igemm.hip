@@ -48,7 +48,7 @@ __device__ inline void mma_step<float>(f32x16_t& acc, const u32x4_t& a, const u3
 __device__ inline float load_elem(const float* p) { return *p; }
 __device__ inline float load_elem(const bf16_t* p) { return bf16_to_f32(*p); }
 __device__ inline void store_elem(float* p, float v) { *p = v; }
-__device__ inline void store_elem(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+__device__ inline void store_elem(bf16_t* p, float v) { *p = (bf16_t)pack_bf16x2(v, 0.f); }
 
 __device__ inline void load4(const float* p, float r[4]) {
     const f32x4_t v = *reinterpret_cast<const f32x4_t*>(p);
@@ -65,8 +65,8 @@ __device__ inline void store4(float* p, const float r[4]) {
 }
 __device__ inline void store4(bf16_t* p, const float r[4]) {
     u32x2_t v;
-    v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
-    v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+    v.x = pack_bf16x2(r[0], r[1]);
+    v.y = pack_bf16x2(r[2], r[3]);
     *reinterpret_cast<u32x2_t*>(p) = v;
 }
 
@@ -84,10 +84,10 @@ __device__ inline void unpack8(const Vec8<float>& x, float r[8]) {
 }
 __device__ inline void store8(bf16_t* p, const float r[8]) {
     u32x4_t v;
-    v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
-    v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
-    v.z = (uint32_t)f32_to_bf16(r[4]) | ((uint32_t)f32_to_bf16(r[5]) << 16);
-    v.w = (uint32_t)f32_to_bf16(r[6]) | ((uint32_t)f32_to_bf16(r[7]) << 16);
+    v.x = pack_bf16x2(r[0], r[1]);
+    v.y = pack_bf16x2(r[2], r[3]);
+    v.z = pack_bf16x2(r[4], r[5]);
+    v.w = pack_bf16x2(r[6], r[7]);
     *reinterpret_cast<u32x4_t*>(p) = v;
 }
 __device__ inline void store8(float* p, const float r[8]) {

@@ -79,10 +79,8 @@ __global__ __launch_bounds__(256) void roialign_kernel(const T* __restrict__ fea
         }
         uint4 pk;
         if constexpr (sizeof(T) == 2) {
-            uint32_t h[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) h[e] = f32_to_bf16(sum[e] * 0.25f);
-            pk = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            pk = make_uint4(pack_bf16x2(sum[0] * 0.25f, sum[1] * 0.25f), pack_bf16x2(sum[2] * 0.25f, sum[3] * 0.25f),
+                            pack_bf16x2(sum[4] * 0.25f, sum[5] * 0.25f), pack_bf16x2(sum[6] * 0.25f, sum[7] * 0.25f));
         } else {
             pk = make_uint4(__float_as_uint(sum[0] * 0.25f), __float_as_uint(sum[1] * 0.25f), __float_as_uint(sum[2] * 0.25f),
                             __float_as_uint(sum[3] * 0.25f));

@@ -60,10 +60,10 @@ __global__ __launch_bounds__(256) void stem_kernel(const uint8_t* __restrict__ f
 #pragma unroll
         for (int ch = 0; ch < SC; ch += 8) {
             u32x4_t v;
-            uint32_t h[8];
+            float h[8];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) h[q] = f32_to_bf16(fmaxf(acc[ch + q] + bias[ch + q], 0.f));
-            v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16); v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
+            for (int q = 0; q < 8; ++q) h[q] = fmaxf(acc[ch + q] + bias[ch + q], 0.f);
+            v.x = pack_bf16x2(h[0], h[1]); v.y = pack_bf16x2(h[2], h[3]); v.z = pack_bf16x2(h[4], h[5]); v.w = pack_bf16x2(h[6], h[7]);
             *reinterpret_cast<u32x4_t*>(out + ch) = v;
         }
     } else {
@@ -200,11 +200,9 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(const uint8_t* __restric
             for (int v = 0; v < 4; ++v) {
                 const int ch = i * 32 + 8 * v + 4 * g;
                 const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(bias + ch);
-                const uint32_t h0 = f32_to_bf16(fmaxf(acc[r][i][4 * v] + bv.x, 0.f)), h1 = f32_to_bf16(fmaxf(acc[r][i][4 * v + 1] + bv.y, 0.f));
-                const uint32_t h2 = f32_to_bf16(fmaxf(acc[r][i][4 * v + 2] + bv.z, 0.f)), h3 = f32_to_bf16(fmaxf(acc[r][i][4 * v + 3] + bv.w, 0.f));
                 uint32_t* d = reinterpret_cast<uint32_t*>(ep + pxl * ME_PITCH + ch * 2);
-                d[0] = h0 | (h1 << 16);
-                d[1] = h2 | (h3 << 16);
+                d[0] = pack_bf16x2(fmaxf(acc[r][i][4 * v] + bv.x, 0.f), fmaxf(acc[r][i][4 * v + 1] + bv.y, 0.f));
+                d[1] = pack_bf16x2(fmaxf(acc[r][i][4 * v + 2] + bv.z, 0.f), fmaxf(acc[r][i][4 * v + 3] + bv.w, 0.f));
             }
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the tile is private to this wavefront
         __builtin_amdgcn_wave_barrier();

@@ -18,6 +18,13 @@ __host__ __device__ inline bf16_t f32_to_bf16(float x) {
     u += 0x7fffu + ((u >> 16) & 1u);                                           // round to nearest even
     return (bf16_t)(u >> 16);
 }
+// Two floats -> packed bf16 pair (lo in bits 0..15) with the hardware conversion (round to nearest even).
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2_v;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_v;
+    const f32x2_v v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_v));
+}
 __host__ __device__ inline float bf16_to_f32(bf16_t h) {
     union { float f; uint32_t u; } v;
     v.u = ((uint32_t)h) << 16;

@@ -68,6 +68,26 @@ def test_conv_op_matches_oracle(precision, case):
         assert relerr(got, ref) <= tol, (case, use_res, relu, out_f32, relerr(got, ref))
 
 
+def test_bf16_output_rounding_is_nearest_even_bit_exact():
+    """The kernels round fp32 results to bf16 with the hardware conversion; the oracle with integer
+    arithmetic.  A convolution with zero weights returns round(bias): ties both ways, values next to
+    ties, bf16 and fp32 subnormals, the largest finite values and signed zeros must agree bit for bit."""
+    m, _ = _model(1)
+    bits = [0x3F808000, 0x3F818000, 0x3F808001, 0x3F807FFF, 0x3F817FFF, 0x3F818001, 0x00000001, 0x00008000, 0x00018000, 0x007FFFFF,
+            0x00800000, 0x7F7F0000, 0x7F7F7FFF, 0x7F7E8000, 0x80000000, 0x00000000, 0xBF808000, 0xBF818000, 0x80008001, 0xC2F6E979]
+    rs = np.random.RandomState(7)
+    bits = np.array(bits + list(rs.randint(0, 2 ** 32, 64 - len(bits), dtype=np.uint64)), dtype=np.uint32)
+    bits = np.where((bits & 0x7F800000) == 0x7F800000, bits & 0x3FFFFFFF, bits).astype(np.uint32)   # no inf / nan
+    b = bits.view(np.float32)
+    x = np.zeros((1, 64, 3, 5), np.float32)
+    w = np.zeros((64, 64, 1, 1), np.float32)
+    ref = oracle.conv2d(x, w, b, bf16_weights=1, round_out=1)
+    got = m.op_conv(to_dev(nchw_to_nhwc(x), m.elem), w, b)
+    torch.cuda.synchronize()
+    got = nhwc_to_nchw(got.float().cpu().numpy())
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), np.flatnonzero(got.view(np.uint32) != ref.view(np.uint32))[:8]
+
+
 @pytest.mark.parametrize("shape", [(2, 21, 37), (1, 5, 7), (3, 41, 50), (1, 8, 16)])
 def test_bottleneck_op_matches_oracle(shape):
     """Single-kernel identity bottleneck against the oracle's three convolutions (bf16 storage mode).
