@@ -35,6 +35,10 @@ __device__ inline void mma(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b) {
 }
 __device__ inline uint32_t pack2(float lo, float hi) { return pack_bf16x2(lo, hi); }
 
+// Scheduling fence for global memory instructions only: the compiler otherwise sinks prefetch loads
+// down to their first use to save registers, which exposes the L2 latency once per fragment.
+__device__ inline void pin_vmem() { __builtin_amdgcn_sched_barrier(0x78f); }
+
 template <int I, int N, typename F>
 __device__ inline void static_for(F&& f) {
     if constexpr (I < N) {
@@ -60,8 +64,9 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
     constexpr int TP = WD * 2 + 16;        // LDS row pitch of t1 / t2 (bytes)
     constexpr int KT1 = C4 / BK;           // phase-1 K steps
     constexpr int KS1 = C4 / 16, KS2 = 9 * WD / 16, KS3 = WD / 16;  // 16-wide MFMA k-steps per phase
-    constexpr int EPITCH = 64 * 4 + 16;    // fp32 epilogue row: 64 channels + pad (bytes)
+    constexpr int EPITCH = 64 * 2 + 16;    // bf16 epilogue row: 64 channels + pad (bytes)
     constexpr int RING = 16;               // weight fragments in flight in phase 2
+    static_assert(KT1 == 4, "one phase-1 K step per wavefront (residual hand-over)");
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* T1 = smem;                        // [NHP][TP]
@@ -104,34 +109,66 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
     // the whole halo tile of x (4 K steps x 6 chunks per thread) is requested up front: one exposed
     // memory latency per tile instead of one per K step
     u32x4_t xs[KT1][6];
-    u32x4_t wa[KS1];
-    static_for<0, KT1>([&](auto ktc) {   // issue order = use order (loads retire in order)
-        constexpr int kt = decltype(ktc)::value;
+    u32x4_t wa[2][BK / 16];   // W1 fragments of the current and the next K step
+#pragma unroll
+    for (int p = 0; p < 6; ++p) xs[0][p] = *reinterpret_cast<const u32x4_t*>(xin + xoff[p]);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) wa[0][kk] = w1f[kk * 64];
+#pragma unroll
+    for (int kt = 1; kt < KT1; ++kt)
 #pragma unroll
         for (int p = 0; p < 6; ++p) xs[kt][p] = *reinterpret_cast<const u32x4_t*>(xin + xoff[p] + kt * BK);
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) wa[kt * (BK / 16) + kk] = w1f[(kt * (BK / 16) + kk) * 64];
-    });
 
+    // Accumulators start from the bias (element e of a lane is channel 8 (e / 4) + 4 (lane / 32) + e % 4 of the
+    // 32-channel tile), so no epilogue waits for a bias load.
+    auto bias_tile = [&](const float* b) {
+        f32x16_t r;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const f32x4_t q = *reinterpret_cast<const f32x4_t*>(b + 8 * v + 4 * lh);
+            r[4 * v] = q.x; r[4 * v + 1] = q.y; r[4 * v + 2] = q.z; r[4 * v + 3] = q.w;
+        }
+        return r;
+    };
     f32x16_t acc1[3];
-#pragma unroll
-    for (int j = 0; j < 3; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc1[j][e] = 0.f;
+    acc1[0] = bias_tile(a.b1 + cw * 32);
+    acc1[1] = acc1[0];
+    acc1[2] = acc1[0];
+
+    // Residual of phase 3: this wavefront's 64 output channels are K step wv of phase 1, so its share of
+    // the centre pixels is copied out of the staging tile while that step is resident (no second read of x).
+    u32x2_t rres[4][2][4];   // [pixel sub-tile][channel tile][accumulator quad], in accumulator layout
 
     static_for<0, KT1>([&](auto ktc) {
         constexpr int kt = decltype(ktc)::value;
         if (kt > 0) __syncthreads();   // every wavefront is done with the previous staging tile
 #pragma unroll
         for (int p = 0; p < 6; ++p) *reinterpret_cast<u32x4_t*>(XS + (lr + 32 * p) * XP + lc * 16) = xs[kt][p];
+        if (kt + 1 < KT1) {
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) wa[(kt + 1) & 1][kk] = w1f[((kt + 1) * (BK / 16) + kk) * 64];
+            pin_vmem();
+        }
         __syncthreads();
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
 #pragma unroll
             for (int j = 0; j < 3; ++j) {
                 const u32x4_t b = *reinterpret_cast<const u32x4_t*>(XS + ((pw + 2 * j) * 32 + l32) * XP + kk * 32 + lh * 16);
-                mma(acc1[j], wa[kt * (BK / 16) + kk], b);
+                mma(acc1[j], wa[kt & 1][kk], b);
             }
+        }
+        if (wv == kt) {
+#pragma unroll
+            for (int pt = 0; pt < 4; ++pt)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int p = pt * 32 + l32;
+                        const int hrow = (p / TW + 1) * HALO_W + (p % TW) + 1;
+                        rres[pt][i][v] = *reinterpret_cast<const u32x2_t*>(XS + hrow * XP + (i * 32 + 8 * v + 4 * lh) * 2);
+                    }
         }
     });
 
@@ -139,6 +176,10 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
     u32x4_t ring[RING];
 #pragma unroll
     for (int s = 0; s < RING; ++s) ring[s] = w2f[s * 64];
+    f32x16_t acc2[2];
+    acc2[0] = bias_tile(a.b2 + cw * 32);
+    acc2[1] = acc2[0];
+    pin_vmem();
 
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
@@ -149,9 +190,8 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int ch = cw * 32 + 8 * v + 4 * lh;
-            const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(a.b1 + ch);
-            const float r0 = ok ? fmaxf(acc1[j][4 * v] + bv.x, 0.f) : 0.f, r1 = ok ? fmaxf(acc1[j][4 * v + 1] + bv.y, 0.f) : 0.f;
-            const float r2 = ok ? fmaxf(acc1[j][4 * v + 2] + bv.z, 0.f) : 0.f, r3 = ok ? fmaxf(acc1[j][4 * v + 3] + bv.w, 0.f) : 0.f;
+            const float r0 = ok ? fmaxf(acc1[j][4 * v], 0.f) : 0.f, r1 = ok ? fmaxf(acc1[j][4 * v + 1], 0.f) : 0.f;
+            const float r2 = ok ? fmaxf(acc1[j][4 * v + 2], 0.f) : 0.f, r3 = ok ? fmaxf(acc1[j][4 * v + 3], 0.f) : 0.f;
             u32x2_t o = {pack2(r0, r1), pack2(r2, r3)};
             *reinterpret_cast<u32x2_t*>(T1 + r * TP + ch * 2) = o;
         }
@@ -159,37 +199,45 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
     __syncthreads();
 
     // ------------------------------------------------------------------ phase 2: t2 = relu(W2 * t1 + b2)
-    f32x16_t acc2[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc2[j][e] = 0.f;
     int hb[2];   // halo row of the tap (0, 0) input of this lane's pixel
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int p = (pw + 2 * j) * 32 + l32;
         hb[j] = (p / TW) * HALO_W + (p % TW);
     }
+    // Software pipeline, pinned step by step (the scheduler would otherwise run the first RING steps before
+    // issuing any refill): step s issues the weight fragment of step s + RING and the t1 operands of step
+    // s + 1, then multiplies the operands fetched one step earlier.
+    auto t1_frag = [&](int s, int j) {
+        const int tap = s / (WD / 16), kk = s % (WD / 16);
+        return *reinterpret_cast<const u32x4_t*>(T1 + (hb[j] + (tap / 3) * HALO_W + (tap % 3)) * TP + kk * 32 + lh * 16);
+    };
+    u32x4_t bq[2][2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) bq[0][j] = t1_frag(0, j);
     static_for<0, KS2>([&](auto sc) {
         constexpr int s = decltype(sc)::value;
-        constexpr int tap = s / (WD / 16), kk = s % (WD / 16);
-        constexpr int ky = tap / 3, kx = tap % 3;
         const u32x4_t wfrag = ring[s % RING];
         if (s + RING < KS2) ring[s % RING] = w2f[(s + RING) * 64];
+        if (s + 1 < KS2) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const u32x4_t b = *reinterpret_cast<const u32x4_t*>(T1 + (hb[j] + ky * HALO_W + kx) * TP + kk * 32 + lh * 16);
-            mma(acc2[j], wfrag, b);
+            for (int j = 0; j < 2; ++j) bq[(s + 1) & 1][j] = t1_frag(s + 1, j);
         }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) mma(acc2[j], wfrag, bq[s & 1][j]);
+        __builtin_amdgcn_sched_barrier(0);
     });
 
-    // residual tile and last-layer weights: requested now, used after the barrier
+    // last-layer weights: requested now, used after the barrier
     u32x4_t w3[2][KS3];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int kk = 0; kk < KS3; ++kk) w3[i][kk] = w3f[(i * KS3 + kk) * 64];
-    u32x4_t rres[4][4];
+    f32x16_t b3t[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) b3t[i] = bias_tile(a.b3 + wv * 64 + i * 32);
+    pin_vmem();
     uint32_t ooff[4][4];   // element offset of the lane's 8 output channels; ~0u = outside the frame
 #pragma unroll
     for (int pt = 0; pt < 4; ++pt)
@@ -198,10 +246,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
             const int item = lane + 64 * it;
             const int p = pt * 32 + (item >> 3), chunk = item & 7;
             const int oy = y0 + p / TW, ox = x0 + p % TW;
-            const bool ok = oy < a.H && ox < a.W;
-            const uint32_t off = (uint32_t)((min(oy, a.H - 1) * a.W + min(ox, a.W - 1)) * C4 + wv * 64 + chunk * 8);
-            rres[pt][it] = *reinterpret_cast<const u32x4_t*>(xin + off);
-            ooff[pt][it] = ok ? off : ~0u;
+            ooff[pt][it] = (oy < a.H && ox < a.W) ? (uint32_t)((oy * a.W + ox) * C4 + wv * 64 + chunk * 8) : ~0u;
         }
 
 #pragma unroll
@@ -210,9 +255,8 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int ch = cw * 32 + 8 * v + 4 * lh;
-            const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(a.b2 + ch);
-            u32x2_t o = {pack2(fmaxf(acc2[j][4 * v] + bv.x, 0.f), fmaxf(acc2[j][4 * v + 1] + bv.y, 0.f)),
-                         pack2(fmaxf(acc2[j][4 * v + 2] + bv.z, 0.f), fmaxf(acc2[j][4 * v + 3] + bv.w, 0.f))};
+            u32x2_t o = {pack2(fmaxf(acc2[j][4 * v], 0.f), fmaxf(acc2[j][4 * v + 1], 0.f)),
+                         pack2(fmaxf(acc2[j][4 * v + 2], 0.f), fmaxf(acc2[j][4 * v + 3], 0.f))};
             *reinterpret_cast<u32x2_t*>(T2 + p * TP + ch * 2) = o;
         }
     }
@@ -220,14 +264,12 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
 
     // ------------------------------------------------------------------ phase 3: y = relu(W3 t2 + b3 + x)
     // this wavefront: output channels 64 wv .. 64 wv + 63 of all 128 pixels, one 32-pixel sub-tile at a time
+    // The residual is added in accumulator layout (fp32), the sum is rounded once, and only the bf16 tile goes
+    // through the wavefront's LDS region to be re-read as 16-byte runs of 8 channels per lane.
     unsigned char* ep = smem + wv * (32 * EPITCH);
     static_for<0, 4>([&](auto ptc) {
         constexpr int pt = decltype(ptc)::value;
-        f32x16_t acc3[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc3[i][e] = 0.f;
+        f32x16_t acc3[2] = {b3t[0], b3t[1]};
 #pragma unroll
         for (int kk = 0; kk < KS3; ++kk) {
             const u32x4_t b = *reinterpret_cast<const u32x4_t*>(T2 + (pt * 32 + l32) * TP + kk * 32 + lh * 16);
@@ -238,30 +280,20 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int chl = i * 32 + 8 * v + 4 * lh;
-                const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(a.b3 + wv * 64 + chl);
-                f32x4_t r = {acc3[i][4 * v] + bv.x, acc3[i][4 * v + 1] + bv.y, acc3[i][4 * v + 2] + bv.z, acc3[i][4 * v + 3] + bv.w};
-                *reinterpret_cast<f32x4_t*>(ep + l32 * EPITCH + chl * 4) = r;
+                const u32x2_t q = rres[pt][i][v];
+                const float r0 = fmaxf(acc3[i][4 * v] + __uint_as_float(q.x << 16), 0.f);
+                const float r1 = fmaxf(acc3[i][4 * v + 1] + __uint_as_float(q.x & 0xffff0000u), 0.f);
+                const float r2 = fmaxf(acc3[i][4 * v + 2] + __uint_as_float(q.y << 16), 0.f);
+                const float r3 = fmaxf(acc3[i][4 * v + 3] + __uint_as_float(q.y & 0xffff0000u), 0.f);
+                u32x2_t o = {pack2(r0, r1), pack2(r2, r3)};
+                *reinterpret_cast<u32x2_t*>(ep + l32 * EPITCH + (i * 32 + 8 * v + 4 * lh) * 2) = o;
             }
         __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the region is private to this wavefront
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int item = lane + 64 * it;
-            const int pxl = item >> 3, chunk = item & 7;
-            const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(ep + pxl * EPITCH + chunk * 32);
-            const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(ep + pxl * EPITCH + chunk * 32 + 16);
-            const uint32_t q[4] = {rres[pt][it].x, rres[pt][it].y, rres[pt][it].z, rres[pt][it].w};
-            const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            u32x4_t o;
-            uint32_t ow[4];
-#pragma unroll
-            for (int h = 0; h < 4; ++h) {
-                const float v0 = fmaxf(f[2 * h] + __uint_as_float(q[h] << 16), 0.f);
-                const float v1 = fmaxf(f[2 * h + 1] + __uint_as_float(q[h] & 0xffff0000u), 0.f);
-                ow[h] = pack2(v0, v1);
-            }
-            o.x = ow[0]; o.y = ow[1]; o.z = ow[2]; o.w = ow[3];
+            const u32x4_t o = *reinterpret_cast<const u32x4_t*>(ep + (item >> 3) * EPITCH + (item & 7) * 16);
             if (ooff[pt][it] != ~0u) *reinterpret_cast<u32x4_t*>(yout + ooff[pt][it]) = o;
         }
         __builtin_amdgcn_s_waitcnt(0xc07f);
