@@ -203,16 +203,21 @@ int thia_op_select_detections(thia_model* m, const float* scores, const float* b
 int thia_op_conv(thia_model* m, const void* in, int n, int H, int W, int Cin, const float* weights, const float* bias,
                  int Cout, int k, int stride, int pad, const void* residual, int relu, int out_f32, void* out);
 
-/* One identity bottleneck block (Section 3 backbone; ResNet bottleneck: 1x1 reduce, 3x3,
- * 1x1 expand, + input, ReLU after each sum) as a single kernel, bf16 models only:
- * out = relu(W3 relu(W2 * relu(W1 in + b1) + b2) + b3 + in), stride 1, zero padding 1 on
- * the 3x3, both intermediates rounded to bf16 as in the layer-by-layer path.
- * in / out: device bf16 [n,H,W,4*width] NHWC, distinct buffers; weights host fp32
- * w1 [width,4*width,1,1], w2 [width,width,3,3], w3 [4*width,width,1,1] and biases
+/* One stride-1 bottleneck block (Section 3 backbone; ResNet bottleneck: 1x1 reduce, 3x3,
+ * 1x1 expand, + shortcut, ReLU after each layer and after the sum) as a single kernel,
+ * bf16 models only.  ws == NULL (identity shortcut):
+ *   out = relu(W3 relu(W2 * relu(W1 in + b1) + b2) + b3 + in),   in [n,H,W,4*width];
+ * ws != NULL (projection shortcut of a stage's first block):
+ *   out = relu(W3 relu(W2 * relu(W1 in + b1) + b2) + b3 + Ws in + bs),   in [n,H,W,width].
+ * Zero padding 1 on the 3x3; both intermediates are rounded to bf16 as in the
+ * layer-by-layer path; the projection is not rounded before the sum.  in / out: device
+ * bf16 NHWC, out [n,H,W,4*width], distinct buffers; weights host fp32 w1 [width,Cin,1,1],
+ * w2 [width,width,3,3], w3 [4*width,width,1,1], ws [4*width,width,1,1] and biases
  * (converted and uploaded by the call, which therefore blocks).  THIA_E_SHAPE for a
  * width without a fused variant (only 64 has one). */
 int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int width, const float* w1, const float* b1,
-                       const float* w2, const float* b2, const float* w3, const float* b3, void* out);
+                       const float* w2, const float* b2, const float* w3, const float* b3, const float* ws,
+                       const float* bs, void* out);
 
 /* Stem of the backbone on frames dev uint8 [n,3,H,W]: normalise, 7x7/2 conv + ReLU,
  * 3x3/2 max-pool; out T [n,Hp,Wp,stem_ch] NHWC. */

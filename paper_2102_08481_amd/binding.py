@@ -77,7 +77,7 @@ def lib():
     L.thia_op_select_detections.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp]
     L.thia_op_conv.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i32, i32, i32, vp, i32, i32, vp]
     L.thia_op_stem.argtypes = [vp, vp, i32, i32, i32, vp]
-    L.thia_op_bottleneck.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.thia_op_bottleneck.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.thia_set_fusion.argtypes = [vp, i32]
     for name in EXPORTS:
         getattr(L, name)
@@ -251,13 +251,15 @@ class Model:
     def set_fusion(self, on):
         self._check(lib().thia_set_fusion(self._h, int(bool(on))))
 
-    def op_bottleneck(self, x, w1, b1, w2, b2, w3, b3):
-        """x: cuda bf16 [n,H,W,4*width]; weights numpy fp32 in [Cout,Cin,k,k] order."""
+    def op_bottleneck(self, x, w1, b1, w2, b2, w3, b3, ws=None, bs=None):
+        """x: cuda bf16 [n,H,W,Cin]; weights numpy fp32 in [Cout,Cin,k,k] order; ws/bs: projection shortcut."""
         _dev(x, self.elem)
-        n, H, W, C4 = x.shape
-        arrs = [np.ascontiguousarray(v, dtype=np.float32) for v in (w1, b1, w2, b2, w3, b3)]
-        out = torch.empty_like(x)
-        self._check(lib().thia_op_bottleneck(self._h, _ptr(x), n, H, W, C4 // 4, *[v.ctypes.data for v in arrs], _ptr(out)))
+        n, H, W, _ = x.shape
+        width = np.asarray(w2).shape[0]
+        arrs = [None if v is None else np.ascontiguousarray(v, dtype=np.float32) for v in (w1, b1, w2, b2, w3, b3, ws, bs)]
+        out = torch.empty((n, H, W, 4 * width), dtype=self.elem, device=self.device)
+        self._check(lib().thia_op_bottleneck(self._h, _ptr(x), n, H, W, width, *[None if v is None else v.ctypes.data for v in arrs],
+                                             _ptr(out)))
         return out
 
     def op_stem(self, frames):

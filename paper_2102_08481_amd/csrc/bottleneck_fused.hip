@@ -55,24 +55,29 @@ constexpr int NPX = TH * TW;            // 128
 
 }  // namespace
 
-template <int WD>
+// FIRST = false: identity block, x has 4 WD channels and is the residual.
+// FIRST = true:  a stage's first block at stride 1: x has WD channels and enters the output through the
+//                projection shortcut; w3f holds [W3 | Ws] along K (2 WD) and b3 the summed biases, so phase 3 is one
+//                contraction over (t2 channels, x channels) with the x operand read from the staging tile.
+template <int WD, bool FIRST>
 __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlockArgs a) {
     static_assert(WD == 64, "work split below is written for 64-channel intermediates");
     constexpr int C4 = 4 * WD;
+    constexpr int CIN = FIRST ? WD : C4;
     constexpr int BK = 64;                 // phase-1 K step (channels)
     constexpr int XP = BK * 2 + 16;        // LDS row pitch of the x staging tile (bytes)
     constexpr int TP = WD * 2 + 16;        // LDS row pitch of t1 / t2 (bytes)
-    constexpr int KT1 = C4 / BK;           // phase-1 K steps
-    constexpr int KS1 = C4 / 16, KS2 = 9 * WD / 16, KS3 = WD / 16;  // 16-wide MFMA k-steps per phase
+    constexpr int KT1 = CIN / BK;          // phase-1 K steps
+    constexpr int KS1 = CIN / 16, KS2 = 9 * WD / 16, KS3 = (FIRST ? 2 * WD : WD) / 16;  // 16-wide MFMA k-steps per phase
     constexpr int EPITCH = 64 * 2 + 16;    // bf16 epilogue row: 64 channels + pad (bytes)
     constexpr int RING = 16;               // weight fragments in flight in phase 2
-    static_assert(KT1 == 4, "one phase-1 K step per wavefront (residual hand-over)");
+    static_assert(FIRST ? (KT1 == 1 && BK == WD) : KT1 == 4, "identity: one phase-1 K step per wavefront (residual hand-over)");
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* T1 = smem;                        // [NHP][TP]
     unsigned char* XS = smem + NHP * TP;             // [NHP][XP]
     unsigned char* T2 = smem + NHP * (TP + XP);      // [NPX][TP]
-    static_assert(4 * 32 * EPITCH <= NHP * (TP + XP), "epilogue tiles reuse the t1 / staging area");
+    static_assert(4 * 32 * EPITCH <= NHP * TP, "epilogue tiles reuse the t1 area (the staging tile stays live for FIRST)");
 
     const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
@@ -85,7 +90,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
     const int img = tile / (tiles_y * tiles_x);
     const int trem = tile - img * (tiles_y * tiles_x);
     const int y0 = (trem / tiles_x) * TH, x0 = (trem % tiles_x) * TW;
-    const bf16_t* __restrict__ xin = a.x + (size_t)img * a.H * a.W * C4;
+    const bf16_t* __restrict__ xin = a.x + (size_t)img * a.H * a.W * CIN;
     bf16_t* __restrict__ yout = a.y + (size_t)img * a.H * a.W * C4;
 
     // ------------------------------------------------------------------ phase 1: t1 on the halo tile
@@ -98,7 +103,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
         const int r = lr + 32 * p;
         const int hy = r / HALO_W, hx = r - hy * HALO_W;
         const int iy = min(max(y0 - 1 + hy, 0), a.H - 1), ix = min(max(x0 - 1 + hx, 0), a.W - 1);
-        xoff[p] = (uint32_t)((iy * a.W + ix) * C4 + lc * 8);
+        xoff[p] = (uint32_t)((iy * a.W + ix) * CIN + lc * 8);
     }
     const int cw = wv & 1;        // 32-channel half of the WD intermediates owned in phases 1 and 2
     const int pw = wv >> 1;       // pixel sub-tiles pw, pw + 2, ...
@@ -158,7 +163,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
                 mma(acc1[j], wa[kt & 1][kk], b);
             }
         }
-        if (wv == kt) {
+        if (!FIRST && wv == kt) {
 #pragma unroll
             for (int pt = 0; pt < 4; ++pt)
 #pragma unroll
@@ -272,7 +277,14 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
         f32x16_t acc3[2] = {b3t[0], b3t[1]};
 #pragma unroll
         for (int kk = 0; kk < KS3; ++kk) {
-            const u32x4_t b = *reinterpret_cast<const u32x4_t*>(T2 + (pt * 32 + l32) * TP + kk * 32 + lh * 16);
+            u32x4_t b;
+            if (kk < WD / 16) {
+                b = *reinterpret_cast<const u32x4_t*>(T2 + (pt * 32 + l32) * TP + kk * 32 + lh * 16);
+            } else {   // FIRST: the centre pixels of x, still resident in the staging tile
+                const int p = pt * 32 + l32;
+                const int hrow = (p / TW + 1) * HALO_W + (p % TW) + 1;
+                b = *reinterpret_cast<const u32x4_t*>(XS + hrow * XP + (kk - WD / 16) * 32 + lh * 16);
+            }
 #pragma unroll
             for (int i = 0; i < 2; ++i) mma(acc3[i], w3[i][kk], b);
         }
@@ -280,7 +292,8 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const u32x2_t q = rres[pt][i][v];
+                u32x2_t q = {0u, 0u};
+                if (!FIRST) q = rres[pt][i][v];
                 const float r0 = fmaxf(acc3[i][4 * v] + __uint_as_float(q.x << 16), 0.f);
                 const float r1 = fmaxf(acc3[i][4 * v + 1] + __uint_as_float(q.x & 0xffff0000u), 0.f);
                 const float r2 = fmaxf(acc3[i][4 * v + 2] + __uint_as_float(q.y << 16), 0.f);
@@ -310,12 +323,11 @@ bool fused_block_supported(const FusedBlockArgs& a, int width) {
     return tiles < (1ll << 30);
 }
 
-hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s) {
-    if (!fused_block_supported(a, width)) return hipErrorInvalidValue;
-    constexpr int WD = 64;
+template <int WD, bool FIRST>
+static hipError_t launch_fused_cfg(const FusedBlockArgs& a, hipStream_t s) {
     constexpr size_t lds = (size_t)NHP * ((WD * 2 + 16) + (64 * 2 + 16)) + (size_t)NPX * (WD * 2 + 16);
     static bool attr_set = false;
-    auto kern = bottleneck_fused_kernel<WD>;
+    auto kern = bottleneck_fused_kernel<WD, FIRST>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -325,6 +337,11 @@ hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s)
     const long long grid = ((tiles + 7) / 8) * 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, a);
     return hipGetLastError();
+}
+
+hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s) {
+    if (!fused_block_supported(a, width)) return hipErrorInvalidValue;
+    return a.first ? launch_fused_cfg<64, true>(a, s) : launch_fused_cfg<64, false>(a, s);
 }
 
 // Host-side packing of a [Cout][K] bf16 weight matrix (K contiguous) into MFMA fragment order:

@@ -382,8 +382,8 @@ int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int
                 FusedBlockArgs fa{};
                 fa.x = static_cast<const bf16_t*>(x); fa.y = static_cast<bf16_t*>(y);
                 fa.w1f = B.f1; fa.w2f = B.f2; fa.w3f = B.f3; fa.b1 = B.c1.b; fa.b2 = B.c2.b; fa.b3 = B.c3.b;
-                fa.N = nb; fa.H = h; fa.W = w;
-                if (fused_block_supported(fa, B.c1.co)) {
+                fa.N = nb; fa.H = h; fa.W = w; fa.first = B.has_sc ? 1 : 0;
+                if (B.stride == 1 && fused_block_supported(fa, B.c1.co)) {
                     Scope sc(m, THIA_K_CONV);
                     HIP_TRY(m, launch_fused_block(fa, B.c1.co, m->stream));
                     std::swap(x, y);
@@ -601,6 +601,11 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
                 HostLayer cat;
                 cat.w = wcat.data(); cat.b = bcat.data(); cat.co = 4 * w; cat.ci = w + cin; cat.k = 1;
                 if (!rc) rc = upload_layer(m, cat, nullptr, B.c3);
+                if (m->precision == 1 && w == 64 && cin == 64 && B.stride == 1) {   // projection block of the 64-wide stage
+                    if (!rc) rc = upload_fragments(m, c1, &B.f1);
+                    if (!rc) rc = upload_fragments(m, c2, &B.f2);
+                    if (!rc) rc = upload_fragments(m, cat, &B.f3);
+                }
             } else {
                 if (!rc) rc = upload_layer(m, c3, nullptr, B.c3);
                 if (m->precision == 1 && w == 64) {   // widths the single-kernel bottleneck is written for
@@ -865,26 +870,37 @@ int thia_set_fusion(thia_model* m, int on) {
 }
 
 int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int width, const float* w1, const float* b1, const float* w2,
-                       const float* b2, const float* w3, const float* b3, void* out) {
-    if (!m || !in || !out || !w1 || !b1 || !w2 || !b2 || !w3 || !b3 || n <= 0 || H <= 0 || W <= 0 || in == out)
+                       const float* b2, const float* w3, const float* b3, const float* ws, const float* bs, void* out) {
+    if (!m || !in || !out || !w1 || !b1 || !w2 || !b2 || !w3 || !b3 || n <= 0 || H <= 0 || W <= 0 || in == out || (ws == nullptr) != (bs == nullptr))
         return fail(m, THIA_E_BADARG, "bad arguments");
     if (m->precision != 1) return fail(m, THIA_E_SHAPE, "the single-kernel bottleneck exists for bf16 models only");
+    if (width != 64) return fail(m, THIA_E_SHAPE, "unsupported bottleneck width");
+    const bool first = ws != nullptr;
+    const int cin = first ? width : 4 * width;
     HostLayer l1, l2, l3;
-    l1.w = w1; l1.b = b1; l1.co = width; l1.ci = 4 * width; l1.k = 1;
+    l1.w = w1; l1.b = b1; l1.co = width; l1.ci = cin; l1.k = 1;
     l2.w = w2; l2.b = b2; l2.co = width; l2.ci = width; l2.k = 3;
     l3.w = w3; l3.b = b3; l3.co = 4 * width; l3.ci = width; l3.k = 1;
+    std::vector<float> wcat, b3v(b3, b3 + 4 * width);
+    if (first) {   // [W3 | Ws] along K, summed biases
+        wcat.resize((size_t)4 * width * 2 * width);
+        for (int o = 0; o < 4 * width; ++o) {
+            std::memcpy(&wcat[(size_t)o * 2 * width], w3 + (size_t)o * width, sizeof(float) * width);
+            std::memcpy(&wcat[(size_t)o * 2 * width + width], ws + (size_t)o * width, sizeof(float) * width);
+            b3v[o] += bs[o];
+        }
+        l3.w = wcat.data(); l3.ci = 2 * width;
+    }
     FusedBlockArgs fa{};
     fa.x = static_cast<const bf16_t*>(in); fa.y = static_cast<bf16_t*>(out);
-    fa.N = n; fa.H = H; fa.W = W;
+    fa.N = n; fa.H = H; fa.W = W; fa.first = first ? 1 : 0;
     bf16_t* f[3] = {nullptr, nullptr, nullptr};
     float* bias = nullptr;
-    int rc = THIA_OK;
     auto cleanup = [&]() {
         for (bf16_t* q : f) if (q) (void)hipFree(q);
         if (bias) (void)hipFree(bias);
     };
-    if (width != 64) return fail(m, THIA_E_SHAPE, "unsupported bottleneck width");
-    rc = upload_fragments(m, l1, &f[0]);
+    int rc = upload_fragments(m, l1, &f[0]);
     if (!rc) rc = upload_fragments(m, l2, &f[1]);
     if (!rc) rc = upload_fragments(m, l3, &f[2]);
     if (!rc && hipMalloc(reinterpret_cast<void**>(&bias), (size_t)6 * width * 4) != hipSuccess) rc = fail(m, THIA_E_NOMEM, "bias allocation failed");
@@ -892,7 +908,7 @@ int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int w
         std::vector<float> hb((size_t)6 * width);
         std::memcpy(hb.data(), b1, sizeof(float) * width);
         std::memcpy(hb.data() + width, b2, sizeof(float) * width);
-        std::memcpy(hb.data() + 2 * width, b3, sizeof(float) * 4 * width);
+        std::memcpy(hb.data() + 2 * width, b3v.data(), sizeof(float) * 4 * width);
         if (hipMemcpy(bias, hb.data(), hb.size() * 4, hipMemcpyHostToDevice) != hipSuccess) rc = fail(m, THIA_E_HIP, "bias upload failed");
     }
     if (rc) { cleanup(); return rc; }

@@ -56,16 +56,19 @@ hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream
 // Shapes the kernel accepts.
 bool conv_supported(const ConvArgs& a, int precision);
 
-// ---------------------------------------------------------------- fused identity bottleneck (bf16)
-// y = relu(W3 relu(W2 * relu(W1 x + b1) + b2) + b3 + x), stride 1, x and y [N][H][W][4*width] NHWC bf16 (distinct
-// buffers).  w1f / w2f / w3f are the three weight matrices ([width][4 width], [width][3][3][width],
-// [4 width][width], K contiguous) in MFMA fragment order (pack_mfma_fragments).
+// ---------------------------------------------------------------- single-kernel bottleneck (bf16, stride 1)
+// first == 0 (identity block): y = relu(W3 relu(W2 * relu(W1 x + b1) + b2) + b3 + x), x [N][H][W][4*width].
+// first != 0 (projection block): y = relu(W3 relu(W2 * relu(W1 x + b1) + b2) + Ws x + b3), x [N][H][W][width]; w3f is
+//   [W3 | Ws] concatenated along K ([4 width][2 width]) and b3 the sum of the two biases.
+// y [N][H][W][4*width]; NHWC bf16, distinct buffers.  w1f / w2f / w3f: weight matrices ([width][Cin],
+// [width][3][3][width], [4 width][K3], K contiguous) in MFMA fragment order (pack_mfma_fragments).
 struct FusedBlockArgs {
     const bf16_t* x;
     bf16_t* y;
     const bf16_t *w1f, *w2f, *w3f;
     const float *b1, *b2, *b3;
     int N, H, W;
+    int first;
 };
 bool fused_block_supported(const FusedBlockArgs& a, int width);
 hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s);

@@ -88,25 +88,33 @@ def test_bf16_output_rounding_is_nearest_even_bit_exact():
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), np.flatnonzero(got.view(np.uint32) != ref.view(np.uint32))[:8]
 
 
+@pytest.mark.parametrize("first", [False, True])
 @pytest.mark.parametrize("shape", [(2, 21, 37), (1, 5, 7), (3, 41, 50), (1, 8, 16)])
-def test_bottleneck_op_matches_oracle(shape):
-    """Single-kernel identity bottleneck against the oracle's three convolutions (bf16 storage mode).
-    Three roundings are chained, so besides the one-ulp flip of the output (2^-7, see above) a flipped
-    intermediate element can move an output by a fraction of an ulp more: the bound is 2^-6, and the
-    share of elements that differ at all is reported by the assertion message."""
+def test_bottleneck_op_matches_oracle(shape, first):
+    """Single-kernel bottleneck (identity and projection shortcut) against the oracle's convolutions in
+    bf16 storage mode.  Three roundings are chained, so besides the one-ulp flip of the output (2^-7, see
+    above) a flipped intermediate element can move an output by a fraction of an ulp more: the bound is
+    2^-6, and the share of elements that differ at all is bounded too."""
     m, _ = _model(1)
     n, H, W = shape
     wd = 64
-    rs = np.random.RandomState(H * 131 + W)
-    x = _bf16(np.abs(rs.randn(n, 4 * wd, H, W)).astype(np.float32))
-    w1 = (rs.randn(wd, 4 * wd, 1, 1) * np.sqrt(2.0 / (4 * wd))).astype(np.float32)
+    cin = wd if first else 4 * wd
+    rs = np.random.RandomState(H * 131 + W + int(first))
+    x = _bf16(np.abs(rs.randn(n, cin, H, W)).astype(np.float32))
+    w1 = (rs.randn(wd, cin, 1, 1) * np.sqrt(2.0 / cin)).astype(np.float32)
     w2 = (rs.randn(wd, wd, 3, 3) * np.sqrt(2.0 / (9 * wd))).astype(np.float32)
     w3 = (rs.randn(4 * wd, wd, 1, 1) * np.sqrt(2.0 / wd)).astype(np.float32)
-    b1, b2, b3 = [(rs.randn(c) * 0.1).astype(np.float32) for c in (wd, wd, 4 * wd)]
+    ws = (rs.randn(4 * wd, cin, 1, 1) * np.sqrt(1.0 / cin)).astype(np.float32)
+    b1, b2, b3, bs = [(rs.randn(c) * 0.1).astype(np.float32) for c in (wd, wd, 4 * wd, 4 * wd)]
     t1 = oracle.conv2d(x, w1, b1, relu=True, bf16_weights=1, round_out=1)
     t2 = oracle.conv2d(t1, w2, b2, pad=1, relu=True, bf16_weights=1, round_out=1)
-    ref = oracle.conv2d(t2, w3, b3, residual=x, relu=True, bf16_weights=1, round_out=1)
-    got = m.op_bottleneck(to_dev(nchw_to_nhwc(x), m.elem), w1, b1, w2, b2, w3, b3)
+    if first:
+        sc = oracle.conv2d(x, ws, bs, bf16_weights=1, round_out=0)      # the projection is not rounded before the sum
+        ref = oracle.conv2d(t2, w3, b3, residual=sc, relu=True, bf16_weights=1, round_out=1)
+        got = m.op_bottleneck(to_dev(nchw_to_nhwc(x), m.elem), w1, b1, w2, b2, w3, b3, ws, bs)
+    else:
+        ref = oracle.conv2d(t2, w3, b3, residual=x, relu=True, bf16_weights=1, round_out=1)
+        got = m.op_bottleneck(to_dev(nchw_to_nhwc(x), m.elem), w1, b1, w2, b2, w3, b3)
     torch.cuda.synchronize()
     got = nhwc_to_nchw(got.float().cpu().numpy())
     assert got.shape == ref.shape
