@@ -365,12 +365,15 @@ int tap_copy(thia_model* m, int which, int f0, int nb, const void* src) {
 int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int ep, const void** feat) {
     Workspace& ws = m->ws;
     const int Hs = conv_out(H, 7, 2, 3), Ws = conv_out(W, 7, 2, 3);
-    {
-        Scope sc(m, THIA_K_STEM);
-        HIP_TRY(m, launch_stem(frames, nb, H, W, m->stem_w, m->stem_wk, m->stem_b, m->mean, m->stdv, m->precision, ws.act[2], m->stream));
-    }
     int h = conv_out(Hs, 3, 2, 1), w = conv_out(Ws, 3, 2, 1);
-    {
+    if (m->precision == 1) {
+        Scope sc(m, THIA_K_STEM);
+        HIP_TRY(m, launch_stem_pool(frames, nb, H, W, m->stem_wk, m->stem_b, m->mean, m->stdv, ws.act[0], m->stream));
+    } else {
+        {
+            Scope sc(m, THIA_K_STEM);
+            HIP_TRY(m, launch_stem(frames, nb, H, W, m->stem_w, m->stem_wk, m->stem_b, m->mean, m->stdv, m->precision, ws.act[2], m->stream));
+        }
         Scope sc(m, THIA_K_POOL);
         HIP_TRY(m, launch_maxpool(ws.act[2], nb, Hs, Ws, m->stem_ch, m->precision, ws.act[0], m->stream));
     }
@@ -928,11 +931,16 @@ int thia_op_stem(thia_model* m, const uint8_t* frames, int n, int H, int W, void
     if (H < 32 || W < 32) return fail(m, THIA_E_SHAPE, "frame too small");
     const int Hs = conv_out(H, 7, 2, 3), Ws = conv_out(W, 7, 2, 3);
     void* tmp = nullptr;
-    if (hipMalloc(&tmp, (size_t)n * Hs * Ws * 64 * m->esz) != hipSuccess) return fail(m, THIA_E_NOMEM, "stem scratch allocation failed");
-    hipError_t e = launch_stem(frames, n, H, W, m->stem_w, m->stem_wk, m->stem_b, m->mean, m->stdv, m->precision, tmp, m->stream);
-    if (e == hipSuccess) e = launch_maxpool(tmp, n, Hs, Ws, 64, m->precision, out, m->stream);
+    hipError_t e;
+    if (m->precision == 1) {
+        e = launch_stem_pool(frames, n, H, W, m->stem_wk, m->stem_b, m->mean, m->stdv, out, m->stream);
+    } else {
+        if (hipMalloc(&tmp, (size_t)n * Hs * Ws * 64 * m->esz) != hipSuccess) return fail(m, THIA_E_NOMEM, "stem scratch allocation failed");
+        e = launch_stem(frames, n, H, W, m->stem_w, m->stem_wk, m->stem_b, m->mean, m->stdv, m->precision, tmp, m->stream);
+        if (e == hipSuccess) e = launch_maxpool(tmp, n, Hs, Ws, 64, m->precision, out, m->stream);
+    }
     hipError_t e2 = hipStreamSynchronize(m->stream);
-    (void)hipFree(tmp);
+    if (tmp) (void)hipFree(tmp);
     if (e != hipSuccess) return fail_hip(m, e, "stem launch");
     if (e2 != hipSuccess) return fail_hip(m, e2, "stem sync");
     return THIA_OK;

@@ -82,6 +82,9 @@ void pack_mfma_fragments(const bf16_t* w, int Cout, int K, bf16_t* dst);
 // [64][22][8] with wk[ch][c*7+ky][j] = weight(ch, c, ky, kx = j-1) for j = 1..7, zero for j = 0 and row 21.
 hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const bf16_t* wk, const float* bias,
                        float mean, float stdv, int precision, void* out, hipStream_t s);
+// bf16 models: stem and 3x3 / stride 2 / pad 1 max-pool in one kernel; out [n,Hp,Wp,64] NHWC bf16.
+hipError_t launch_stem_pool(const uint8_t* frames, int n, int H, int W, const bf16_t* wk, const float* bias, float mean, float stdv,
+                            void* out, hipStream_t s);
 hipError_t launch_maxpool(const void* in, int n, int H, int W, int C, int precision, void* out, hipStream_t s);
 
 // ---------------------------------------------------------------- RPN proposal path

@@ -138,12 +138,15 @@ def test_bottleneck_op_rejects_unsupported():
 
 
 @pytest.mark.parametrize("precision", [0, 1])
-def test_stem_op_matches_oracle(precision):
+@pytest.mark.parametrize("size", [(70, 93), (64, 128), (131, 252), (33, 37)])
+def test_stem_op_matches_oracle(precision, size):
+    """Normalisation + 7x7 stem + ReLU + 3x3 max-pool (one kernel for bf16 models): odd and even sizes,
+    widths that are and are not multiples of 4, several tiles with ragged right and bottom edges."""
     m, blob = _model(precision)
     spec = MINI_BF16 if precision else MINI_FP32
     from thia_synth import split_blob
     w = split_blob(spec, blob)
-    frames = make_frames(SceneSpec(70, 93, 3, 3, 6, 8, 40), 5)        # odd sizes: ragged 16x16 tiles
+    frames = make_frames(SceneSpec(size[0], size[1], 3, 3, 6, 8, 40), 5)
     x = oracle.normalize(frames, spec.mean, spec.std, bf16=precision)
     y = oracle.conv2d(x, w["stem.w"], w["stem.b"], stride=2, pad=3, relu=True, bf16_weights=precision, round_out=precision)
     ref = oracle.maxpool3x3s2(y)
