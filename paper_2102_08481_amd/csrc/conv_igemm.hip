@@ -441,6 +441,11 @@ hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream
         // flight, so they take the small-footprint 128 x 64 tile (4 blocks of 4 wavefronts per CU).
         if (K <= 128 && a.out1 == nullptr && a.in2 == nullptr) return launch_one<bf16_t, 128, 64, 64, 2, 2, bf16_t>(a, s);
         const long long tiles_l = ((M + 255) / 256) * ((a.Cout + 255) / 256);
+        // Very long K with a tile count that leaves CUs idle in a single round (the first FC layer: 152 tiles of
+        // 256 x 256 on 256 CUs): 192-pixel tiles give 200 tiles of 3/4 the work each.
+        const long long tiles_192 = ((M + 191) / 192) * ((a.Cout + 255) / 256);
+        if (a.Cout % 256 == 0 && K >= 8192 && tiles_l < 200 && tiles_192 <= 256 && tiles_192 > tiles_l && a.out1 == nullptr && a.in2 == nullptr)
+            return launch_one<bf16_t, 192, 256, 128, 2, 4, bf16_t>(a, s);
         if (a.Cout % 256 == 0 && K >= 64 && (tiles_l >= 200 || (tiles_l >= 150 && K >= 8192)) && a.out1 == nullptr) return launch_one<bf16_t, 256, 256, 128, 2, 4, bf16_t, true>(a, s);
     }
     return narrow ? launch_one<bf16_t, 128, 64, 64, 2, 2, bf16_t>(a, s) : launch_one<bf16_t, 128, 128, 128, 2, 4, bf16_t, true>(a, s);
