@@ -214,7 +214,7 @@ int thia_op_conv(thia_model* m, const void* in, int n, int H, int W, int Cin, co
  * bf16 NHWC, out [n,H,W,4*width], distinct buffers; weights host fp32 w1 [width,Cin,1,1],
  * w2 [width,width,3,3], w3 [4*width,width,1,1], ws [4*width,width,1,1] and biases
  * (converted and uploaded by the call, which therefore blocks).  THIA_E_SHAPE for a
- * width without a fused variant (only 64 has one). */
+ * width without a fused variant (64: both forms; 128: identity shortcut only). */
 int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int width, const float* w1, const float* b1,
                        const float* w2, const float* b2, const float* w3, const float* b3, const float* ws,
                        const float* bs, void* out);

@@ -314,8 +314,260 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
     });
 }
 
+// ---------------------------------------------------------------------------------------------------
+// 128-channel intermediates (identity blocks of the second stage): same tile and phases, other budgets.
+// t1 / t2 rows are 256 bytes and are stored unpadded with the 16-byte chunk index XOR-ed with the row
+// (t1 46 KB + t2 32 KB, the staging tile shares t2's space: two blocks per CU still fit).  Work split:
+//   phase 1  wavefront = 2 channel tiles x 3 pixel tiles (each staged operand feeds two MFMAs),
+//   phase 2  wavefront = 1 channel tile x 4 pixel tiles (each weight fragment is fetched by one wavefront only),
+//   phase 3  wavefront = 128 output channels as two 64-channel halves x 4 pixel tiles; the residual is
+//            re-read from global memory (L2) in 16-byte runs and added after an fp32 transpose through LDS.
+__device__ inline int swz256(int row, int byteoff) {   // physical offset in a 256-byte-row swizzled tile
+    return row * 256 + ((((byteoff >> 4) ^ row) & 15) << 4) + (byteoff & 15);
+}
+
+__global__ __launch_bounds__(256, 2) void bottleneck_fused128_kernel(const FusedBlockArgs a) {
+    constexpr int WD = 128, C4 = 512, BK = 64;
+    constexpr int XP = BK * 2 + 16;                  // staging tile row pitch (bytes)
+    constexpr int KT1 = C4 / BK;                     // 8 phase-1 K steps
+    constexpr int KS1 = C4 / 16, KS2 = 9 * WD / 16, KS3 = WD / 16;   // 32, 72, 8
+    constexpr int XRING = 2;                         // staged K steps in flight (a third spills registers)
+    constexpr int RING = 16;                         // phase-2 weight fragments in flight
+    constexpr int EPITCH = 64 * 4 + 16;              // fp32 epilogue row: 64 channels + pad
+    constexpr int T1_BYTES = NH * 256;               // 46080
+    constexpr int T2_BYTES = NPX * 256;              // 32768 (>= the staging tile)
+    static_assert(NHP * XP <= T2_BYTES, "the staging tile shares t2's space");
+    static_assert(4 * 32 * EPITCH <= T1_BYTES, "epilogue tiles reuse the t1 area");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* T1 = smem;
+    unsigned char* XS = smem + T1_BYTES;
+    unsigned char* T2 = smem + T1_BYTES;
+
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int tiles_x = (a.W + TW - 1) / TW, tiles_y = (a.H + TH - 1) / TH;
+    const int total = a.N * tiles_y * tiles_x;
+    const int per_xcd = (total + 7) >> 3;
+    const int tile = (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
+    if (tile >= total) return;
+    const int img = tile / (tiles_y * tiles_x);
+    const int trem = tile - img * (tiles_y * tiles_x);
+    const int y0 = (trem / tiles_x) * TH, x0 = (trem % tiles_x) * TW;
+    const bf16_t* __restrict__ xin = a.x + (size_t)img * a.H * a.W * C4;
+    bf16_t* __restrict__ yout = a.y + (size_t)img * a.H * a.W * C4;
+
+    auto bias_tile = [&](const float* b) {
+        f32x16_t r;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const f32x4_t q = *reinterpret_cast<const f32x4_t*>(b + 8 * v + 4 * lh);
+            r[4 * v] = q.x; r[4 * v + 1] = q.y; r[4 * v + 2] = q.z; r[4 * v + 3] = q.w;
+        }
+        return r;
+    };
+
+    // ------------------------------------------------------------------ phase 1
+    const int lc = t & 7, lr = t >> 3;
+    uint32_t xoff[6];
+#pragma unroll
+    for (int p = 0; p < 6; ++p) {
+        const int r = lr + 32 * p;
+        const int hy = r / HALO_W, hx = r - hy * HALO_W;
+        const int iy = min(max(y0 - 1 + hy, 0), a.H - 1), ix = min(max(x0 - 1 + hx, 0), a.W - 1);
+        xoff[p] = (uint32_t)((iy * a.W + ix) * C4 + lc * 8);
+    }
+    const int cp = wv & 1;        // phase 1: channel tiles 2 cp, 2 cp + 1
+    const int pw = wv >> 1;       // phase 1: pixel tiles pw, pw + 2, pw + 4
+    const u32x4_t* __restrict__ w1f = reinterpret_cast<const u32x4_t*>(a.w1f) + (size_t)(2 * cp) * KS1 * 64 + lane;
+    const u32x4_t* __restrict__ w2f = reinterpret_cast<const u32x4_t*>(a.w2f) + (size_t)wv * KS2 * 64 + lane;
+    const u32x4_t* __restrict__ w3f = reinterpret_cast<const u32x4_t*>(a.w3f) + (size_t)(4 * wv) * KS3 * 64 + lane;
+
+    u32x4_t xs[XRING][6];
+    u32x4_t wa[2][2][BK / 16];   // [buffer][channel tile][k-step of the K step]
+    auto load_x = [&](int kt, int slot) {
+#pragma unroll
+        for (int p = 0; p < 6; ++p) xs[slot][p] = *reinterpret_cast<const u32x4_t*>(xin + xoff[p] + kt * BK);
+    };
+    auto load_wa = [&](int kt, int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) wa[buf][i][kk] = w1f[(i * KS1 + kt * (BK / 16) + kk) * 64];
+    };
+    load_x(0, 0);
+    load_wa(0, 0);
+    load_x(1, 1);
+    static_assert(XRING == 2, "prologue issues two K steps");
+    f32x16_t acc1[2][3];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        acc1[i][0] = bias_tile(a.b1 + (2 * cp + i) * 32);
+        acc1[i][1] = acc1[i][0];
+        acc1[i][2] = acc1[i][0];
+    }
+    static_for<0, KT1>([&](auto ktc) {
+        constexpr int kt = decltype(ktc)::value;
+        if (kt > 0) __syncthreads();   // every wavefront is done with the previous staging tile
+#pragma unroll
+        for (int p = 0; p < 6; ++p) *reinterpret_cast<u32x4_t*>(XS + (lr + 32 * p) * XP + lc * 16) = xs[kt % XRING][p];
+        if (kt + XRING < KT1) load_x(kt + XRING, kt % XRING);
+        if (kt + 1 < KT1) load_wa(kt + 1, (kt + 1) & 1);
+        pin_vmem();
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const u32x4_t b = *reinterpret_cast<const u32x4_t*>(XS + ((pw + 2 * j) * 32 + l32) * XP + kk * 32 + lh * 16);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) mma(acc1[i][j], wa[kt & 1][i][kk], b);
+            }
+        }
+    });
+
+    // phase-2 prologue: first weight fragments and the bias tile
+    u32x4_t ring[RING];
+#pragma unroll
+    for (int s = 0; s < RING; ++s) ring[s] = w2f[s * 64];
+    f32x16_t acc2[4];
+    acc2[0] = bias_tile(a.b2 + wv * 32);
+    acc2[1] = acc2[0]; acc2[2] = acc2[0]; acc2[3] = acc2[0];
+    pin_vmem();
+
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        const int r = (pw + 2 * j) * 32 + l32;
+        const int hy = r / HALO_W, hx = r - hy * HALO_W;
+        const int iy = y0 - 1 + hy, ix = x0 - 1 + hx;
+        const bool ok = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+        if (r < NH) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int ch = (2 * cp + i) * 32 + 8 * v + 4 * lh;
+                    const float r0 = ok ? fmaxf(acc1[i][j][4 * v], 0.f) : 0.f, r1 = ok ? fmaxf(acc1[i][j][4 * v + 1], 0.f) : 0.f;
+                    const float r2 = ok ? fmaxf(acc1[i][j][4 * v + 2], 0.f) : 0.f, r3 = ok ? fmaxf(acc1[i][j][4 * v + 3], 0.f) : 0.f;
+                    u32x2_t o = {pack2(r0, r1), pack2(r2, r3)};
+                    *reinterpret_cast<u32x2_t*>(T1 + swz256(r, ch * 2)) = o;
+                }
+        }
+    }
+    __syncthreads();   // t1 complete; the staging tile is dead (t2 will take its place)
+
+    // ------------------------------------------------------------------ phase 2: channel tile wv, pixel tiles 0..3
+    int hb[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int p = j * 32 + l32;
+        hb[j] = (p / TW) * HALO_W + (p % TW);
+    }
+    auto t1_frag = [&](int s, int j) {
+        const int tap = s / (WD / 16), kk = s % (WD / 16);
+        return *reinterpret_cast<const u32x4_t*>(T1 + swz256(hb[j] + (tap / 3) * HALO_W + (tap % 3), kk * 32 + lh * 16));
+    };
+    u32x4_t bq[2][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bq[0][j] = t1_frag(0, j);
+    static_for<0, KS2>([&](auto sc) {
+        constexpr int s = decltype(sc)::value;
+        const u32x4_t wfrag = ring[s % RING];
+        if (s + RING < KS2) ring[s % RING] = w2f[(s + RING) * 64];
+        if (s + 1 < KS2) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bq[(s + 1) & 1][j] = t1_frag(s + 1, j);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) mma(acc2[j], wfrag, bq[s & 1][j]);
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    // (t2 takes the staging tile's place, which nobody has read since the barrier above; t1 is not touched)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int p = j * 32 + l32;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int ch = wv * 32 + 8 * v + 4 * lh;
+            u32x2_t o = {pack2(fmaxf(acc2[j][4 * v], 0.f), fmaxf(acc2[j][4 * v + 1], 0.f)),
+                         pack2(fmaxf(acc2[j][4 * v + 2], 0.f), fmaxf(acc2[j][4 * v + 3], 0.f))};
+            *reinterpret_cast<u32x2_t*>(T2 + swz256(p, ch * 2)) = o;
+        }
+    }
+    __syncthreads();   // t2 complete; t1 is dead from here on
+
+    // ------------------------------------------------------------------ phase 3: output channels 128 wv .. 128 wv + 127
+    unsigned char* ep = smem + wv * (32 * EPITCH);
+    auto out_off = [&](int pt, int it, int half) -> uint32_t {   // element offset of a lane's 8 channels; ~0u = outside the frame
+        const int item = lane + 64 * it;
+        const int p = pt * 32 + (item >> 3), chunk = item & 7;
+        const int oy = y0 + p / TW, ox = x0 + p % TW;
+        return (oy < a.H && ox < a.W) ? (uint32_t)((oy * a.W + ox) * C4 + wv * 128 + half * 64 + chunk * 8) : ~0u;
+    };
+    u32x4_t rq[2][4];   // residual of the current and the next (half, pixel tile) step
+    auto fetch_res = [&](int step, int slot) {
+        const int half = step >> 2, pt = step & 3;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const uint32_t off = out_off(pt, it, half);
+            rq[slot][it] = *reinterpret_cast<const u32x4_t*>(xin + (off == ~0u ? 0u : off));
+        }
+    };
+    fetch_res(0, 0);
+    static_for<0, 2>([&](auto hc) {
+        constexpr int half = decltype(hc)::value;
+        u32x4_t w3[2][KS3];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int kk = 0; kk < KS3; ++kk) w3[i][kk] = w3f[((2 * half + i) * KS3 + kk) * 64];
+        f32x16_t b3t[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) b3t[i] = bias_tile(a.b3 + wv * 128 + half * 64 + i * 32);
+        pin_vmem();
+        static_for<0, 4>([&](auto ptc) {
+            constexpr int pt = decltype(ptc)::value;
+            constexpr int step = half * 4 + pt;
+            if (step + 1 < 8) fetch_res(step + 1, (step + 1) & 1);
+            pin_vmem();
+            f32x16_t acc3[2] = {b3t[0], b3t[1]};
+#pragma unroll
+            for (int kk = 0; kk < KS3; ++kk) {
+                const u32x4_t b = *reinterpret_cast<const u32x4_t*>(T2 + swz256(pt * 32 + l32, kk * 32 + lh * 16));
+#pragma unroll
+                for (int i = 0; i < 2; ++i) mma(acc3[i], w3[i][kk], b);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    f32x4_t r = {acc3[i][4 * v], acc3[i][4 * v + 1], acc3[i][4 * v + 2], acc3[i][4 * v + 3]};
+                    *reinterpret_cast<f32x4_t*>(ep + l32 * EPITCH + (i * 32 + 8 * v + 4 * lh) * 4) = r;
+                }
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the region is private to this wavefront
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int item = lane + 64 * it;
+                const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(ep + (item >> 3) * EPITCH + (item & 7) * 32);
+                const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(ep + (item >> 3) * EPITCH + (item & 7) * 32 + 16);
+                const u32x4_t q = rq[step & 1][it];
+                u32x4_t o;
+                o.x = pack2(fmaxf(lo.x + __uint_as_float(q.x << 16), 0.f), fmaxf(lo.y + __uint_as_float(q.x & 0xffff0000u), 0.f));
+                o.y = pack2(fmaxf(lo.z + __uint_as_float(q.y << 16), 0.f), fmaxf(lo.w + __uint_as_float(q.y & 0xffff0000u), 0.f));
+                o.z = pack2(fmaxf(hi.x + __uint_as_float(q.z << 16), 0.f), fmaxf(hi.y + __uint_as_float(q.z & 0xffff0000u), 0.f));
+                o.w = pack2(fmaxf(hi.z + __uint_as_float(q.w << 16), 0.f), fmaxf(hi.w + __uint_as_float(q.w & 0xffff0000u), 0.f));
+                const uint32_t off = out_off(pt, it, half);
+                if (off != ~0u) *reinterpret_cast<u32x4_t*>(yout + off) = o;
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+        });
+    });
+}
+
 bool fused_block_supported(const FusedBlockArgs& a, int width) {
-    if (width != 64) return false;
+    if (width != 64 && !(width == 128 && !a.first)) return false;   // 128-wide: identity blocks only
     if (!a.x || !a.y || a.x == a.y || !a.w1f || !a.w2f || !a.w3f || !a.b1 || !a.b2 || !a.b3) return false;
     if (a.N <= 0 || a.H <= 0 || a.W <= 0) return false;
     if ((long long)a.H * a.W * 4 * width >= (1ll << 31)) return false;   // 32-bit element offsets within a frame
@@ -323,11 +575,8 @@ bool fused_block_supported(const FusedBlockArgs& a, int width) {
     return tiles < (1ll << 30);
 }
 
-template <int WD, bool FIRST>
-static hipError_t launch_fused_cfg(const FusedBlockArgs& a, hipStream_t s) {
-    constexpr size_t lds = (size_t)NHP * ((WD * 2 + 16) + (64 * 2 + 16)) + (size_t)NPX * (WD * 2 + 16);
-    static bool attr_set = false;
-    auto kern = bottleneck_fused_kernel<WD, FIRST>;
+template <typename Kern>
+static hipError_t launch_fused_kernel(Kern kern, size_t lds, bool& attr_set, const FusedBlockArgs& a, hipStream_t s) {
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -341,7 +590,12 @@ static hipError_t launch_fused_cfg(const FusedBlockArgs& a, hipStream_t s) {
 
 hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s) {
     if (!fused_block_supported(a, width)) return hipErrorInvalidValue;
-    return a.first ? launch_fused_cfg<64, true>(a, s) : launch_fused_cfg<64, false>(a, s);
+    constexpr size_t lds64 = (size_t)NHP * ((64 * 2 + 16) + (64 * 2 + 16)) + (size_t)NPX * (64 * 2 + 16);
+    constexpr size_t lds128 = (size_t)NH * 256 + (size_t)NPX * 256;
+    static bool set_first = false, set_ident = false, set_128 = false;
+    if (width == 128) return launch_fused_kernel(bottleneck_fused128_kernel, lds128, set_128, a, s);
+    if (a.first) return launch_fused_kernel(bottleneck_fused_kernel<64, true>, lds64, set_first, a, s);
+    return launch_fused_kernel(bottleneck_fused_kernel<64, false>, lds64, set_ident, a, s);
 }
 
 // Host-side packing of a [Cout][K] bf16 weight matrix (K contiguous) into MFMA fragment order:

@@ -611,7 +611,7 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
                 }
             } else {
                 if (!rc) rc = upload_layer(m, c3, nullptr, B.c3);
-                if (m->precision == 1 && w == 64) {   // widths the single-kernel bottleneck is written for
+                if (m->precision == 1 && (w == 64 || w == 128)) {   // widths the single-kernel bottleneck is written for
                     if (!rc) rc = upload_fragments(m, c1, &B.f1);
                     if (!rc) rc = upload_fragments(m, c2, &B.f2);
                     if (!rc) rc = upload_fragments(m, c3, &B.f3);
@@ -877,8 +877,8 @@ int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int w
     if (!m || !in || !out || !w1 || !b1 || !w2 || !b2 || !w3 || !b3 || n <= 0 || H <= 0 || W <= 0 || in == out || (ws == nullptr) != (bs == nullptr))
         return fail(m, THIA_E_BADARG, "bad arguments");
     if (m->precision != 1) return fail(m, THIA_E_SHAPE, "the single-kernel bottleneck exists for bf16 models only");
-    if (width != 64) return fail(m, THIA_E_SHAPE, "unsupported bottleneck width");
     const bool first = ws != nullptr;
+    if (width != 64 && !(width == 128 && !first)) return fail(m, THIA_E_SHAPE, "unsupported bottleneck width");
     const int cin = first ? width : 4 * width;
     HostLayer l1, l2, l3;
     l1.w = w1; l1.b = b1; l1.co = width; l1.ci = cin; l1.k = 1;

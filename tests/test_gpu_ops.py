@@ -89,18 +89,18 @@ def test_bf16_output_rounding_is_nearest_even_bit_exact():
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), np.flatnonzero(got.view(np.uint32) != ref.view(np.uint32))[:8]
 
 
-@pytest.mark.parametrize("first", [False, True])
+@pytest.mark.parametrize("variant", [(64, False), (64, True), (128, False)])
 @pytest.mark.parametrize("shape", [(2, 21, 37), (1, 5, 7), (3, 41, 50), (1, 8, 16)])
-def test_bottleneck_op_matches_oracle(shape, first):
+def test_bottleneck_op_matches_oracle(shape, variant):
     """Single-kernel bottleneck (identity and projection shortcut) against the oracle's convolutions in
     bf16 storage mode.  Three roundings are chained, so besides the one-ulp flip of the output (2^-7, see
     above) a flipped intermediate element can move an output by a fraction of an ulp more: the bound is
     2^-6, and the share of elements that differ at all is bounded too."""
     m, _ = _model(1)
     n, H, W = shape
-    wd = 64
+    wd, first = variant
     cin = wd if first else 4 * wd
-    rs = np.random.RandomState(H * 131 + W + int(first))
+    rs = np.random.RandomState(H * 131 + W + int(first) + wd)
     x = _bf16(np.abs(rs.randn(n, cin, H, W)).astype(np.float32))
     w1 = (rs.randn(wd, cin, 1, 1) * np.sqrt(2.0 / cin)).astype(np.float32)
     w2 = (rs.randn(wd, wd, 3, 3) * np.sqrt(2.0 / (9 * wd))).astype(np.float32)
@@ -131,6 +131,9 @@ def test_bottleneck_op_rejects_unsupported():
     z = lambda *s: np.zeros(s, np.float32)
     with pytest.raises(ThiaError) as e:
         m.op_bottleneck(x, z(32, 128, 1, 1), z(32), z(32, 32, 3, 3), z(32), z(128, 32, 1, 1), z(128))
+    assert e.value.code == -3
+    with pytest.raises(ThiaError) as e:       # the 128-wide variant has no projection form
+        m.op_bottleneck(x, z(128, 128, 1, 1), z(128), z(128, 128, 3, 3), z(128), z(512, 128, 1, 1), z(512), z(512, 128, 1, 1), z(512))
     assert e.value.code == -3
     m32, _ = _model(0)
     with pytest.raises(ThiaError):
