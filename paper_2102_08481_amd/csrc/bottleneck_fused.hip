@@ -498,19 +498,23 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused128_kernel(const Fused
 
     // ------------------------------------------------------------------ phase 3: output channels 128 wv .. 128 wv + 127
     unsigned char* ep = smem + wv * (32 * EPITCH);
-    auto out_off = [&](int pt, int it, int half) -> uint32_t {   // element offset of a lane's 8 channels; ~0u = outside the frame
-        const int item = lane + 64 * it;
-        const int p = pt * 32 + (item >> 3), chunk = item & 7;
-        const int oy = y0 + p / TW, ox = x0 + p % TW;
-        return (oy < a.H && ox < a.W) ? (uint32_t)((oy * a.W + ox) * C4 + wv * 128 + half * 64 + chunk * 8) : ~0u;
-    };
+    uint32_t ooff[4][4];   // element offset of the lane's 8 channels in the first 64-channel half; ~0u = outside the frame
+#pragma unroll
+    for (int pt = 0; pt < 4; ++pt)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int item = lane + 64 * it;
+            const int p = pt * 32 + (item >> 3), chunk = item & 7;
+            const int oy = y0 + p / TW, ox = x0 + p % TW;
+            ooff[pt][it] = (oy < a.H && ox < a.W) ? (uint32_t)((oy * a.W + ox) * C4 + wv * 128 + chunk * 8) : ~0u;
+        }
     u32x4_t rq[2][4];   // residual of the current and the next (half, pixel tile) step
     auto fetch_res = [&](int step, int slot) {
         const int half = step >> 2, pt = step & 3;
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            const uint32_t off = out_off(pt, it, half);
-            rq[slot][it] = *reinterpret_cast<const u32x4_t*>(xin + (off == ~0u ? 0u : off));
+            const uint32_t off = ooff[pt][it];
+            rq[slot][it] = *reinterpret_cast<const u32x4_t*>(xin + (off == ~0u ? 0u : off + half * 64));
         }
     };
     fetch_res(0, 0);
@@ -525,23 +529,30 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused128_kernel(const Fused
 #pragma unroll
         for (int i = 0; i < 2; ++i) b3t[i] = bias_tile(a.b3 + wv * 128 + half * 64 + i * 32);
         pin_vmem();
-        static_for<0, 4>([&](auto ptc) {
-            constexpr int pt = decltype(ptc)::value;
-            constexpr int step = half * 4 + pt;
-            if (step + 1 < 8) fetch_res(step + 1, (step + 1) & 1);
-            pin_vmem();
-            f32x16_t acc3[2] = {b3t[0], b3t[1]};
+        // the products of pixel tile pt + 1 are issued before the epilogue of pixel tile pt, so that the matrix
+        // pipe works while the vector ALUs and LDS transpose, add the residual and store
+        f32x16_t acc3[2][2];
+        auto products = [&](int pt, int slot) {
+            acc3[slot][0] = b3t[0];
+            acc3[slot][1] = b3t[1];
 #pragma unroll
             for (int kk = 0; kk < KS3; ++kk) {
                 const u32x4_t b = *reinterpret_cast<const u32x4_t*>(T2 + swz256(pt * 32 + l32, kk * 32 + lh * 16));
 #pragma unroll
-                for (int i = 0; i < 2; ++i) mma(acc3[i], w3[i][kk], b);
+                for (int i = 0; i < 2; ++i) mma(acc3[slot][i], w3[i][kk], b);
             }
+        };
+        products(0, 0);
+        static_for<0, 4>([&](auto ptc) {
+            constexpr int pt = decltype(ptc)::value;
+            constexpr int step = half * 4 + pt;
+            if (step + 1 < 8) fetch_res(step + 1, (step + 1) & 1);
+            if (pt + 1 < 4) products(pt + 1, (pt + 1) & 1);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    f32x4_t r = {acc3[i][4 * v], acc3[i][4 * v + 1], acc3[i][4 * v + 2], acc3[i][4 * v + 3]};
+                    f32x4_t r = {acc3[pt & 1][i][4 * v], acc3[pt & 1][i][4 * v + 1], acc3[pt & 1][i][4 * v + 2], acc3[pt & 1][i][4 * v + 3]};
                     *reinterpret_cast<f32x4_t*>(ep + l32 * EPITCH + (i * 32 + 8 * v + 4 * lh) * 4) = r;
                 }
             __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the region is private to this wavefront
@@ -557,8 +568,8 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused128_kernel(const Fused
                 o.y = pack2(fmaxf(lo.z + __uint_as_float(q.y << 16), 0.f), fmaxf(lo.w + __uint_as_float(q.y & 0xffff0000u), 0.f));
                 o.z = pack2(fmaxf(hi.x + __uint_as_float(q.z << 16), 0.f), fmaxf(hi.y + __uint_as_float(q.z & 0xffff0000u), 0.f));
                 o.w = pack2(fmaxf(hi.z + __uint_as_float(q.w << 16), 0.f), fmaxf(hi.w + __uint_as_float(q.w & 0xffff0000u), 0.f));
-                const uint32_t off = out_off(pt, it, half);
-                if (off != ~0u) *reinterpret_cast<u32x4_t*>(yout + off) = o;
+                const uint32_t off = ooff[pt][it];
+                if (off != ~0u) *reinterpret_cast<u32x4_t*>(yout + off + half * 64) = o;
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);
             __builtin_amdgcn_wave_barrier();
