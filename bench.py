@@ -15,7 +15,7 @@ sys.path.insert(0, ROOT)
 
 RES_GAIN, PRED_STD = 0.25, 0.01        # data-only gains of the synthetic weights
 PEAK_BF16_TFLOPS = 2500.0              # MI355X dense bf16 MFMA peak
-CONV_CLASSES = ("conv", "fc")          # launches of the implicit-GEMM MFMA kernel
+CONV_CLASSES = ("conv", "fc")          # launches of the implicit-GEMM MFMA kernels (layer-by-layer and fused blocks)
 
 
 def conv_out(n, k, s, p):
@@ -44,8 +44,9 @@ def layer_macs(spec, H, W, ep):
 
 
 def conv_layer_bytes(spec, H, W, ep, esz=2):
-    """Algorithmic HBM bytes per frame of the implicit-GEMM launches at exit ep, layer by layer and
-    unfused: input + output (+ residual) activations once each; weights are negligible and left out."""
+    """Algorithmic HBM bytes per frame of the convolution / FC layers at exit ep, layer by layer and
+    unfused: input + output (+ residual) activations once each; weights are negligible and left out.
+    (The single-kernel bottleneck blocks move less than this: their intermediates stay in LDS.)"""
     h, w = conv_out(conv_out(H, 7, 2, 3), 3, 2, 1), conv_out(conv_out(W, 7, 2, 3), 3, 2, 1)
     total, cin = 0, spec.stem_ch
     for s in range(ep):
@@ -71,7 +72,7 @@ def conv_layer_bytes(spec, H, W, ep, esz=2):
 
 def measured_traffic(workload_key):
     """HBM bytes per step of the dominant kernel from the committed rocprofv3 --pmc summary, if present."""
-    path = os.path.join(ROOT, "profiles", "conv_igemm_config3_sweep_pmc_fetch_write.txt")
+    path = os.path.join(ROOT, "profiles", "mfma_kernels_config3_sweep_pmc_fetch_write.txt")
     try:
         for line in open(path):
             if line.startswith("TRAFFIC_BYTES_PER_STEP " + workload_key):
@@ -167,7 +168,7 @@ def main():
     conv_launches = sum(prof[c][1] for c in CONV_CLASSES) / args.steps
     achieved = conv_flops_step / (conv_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "conv_igemm_kernel (all instantiations: backbone, lateral, RPN, FC)",
+        "kernel": "implicit-GEMM MFMA kernels: conv_igemm_kernel instantiations + bottleneck_fused kernels (backbone, lateral, RPN, FC)",
         "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
         "traffic": None,   # filled below: bytes per launch from the committed --pmc runs
         "flops_per_step": conv_flops_step, "launches_per_step": conv_launches, "avg_launch_us": 1e3 * conv_ms / max(conv_launches, 1),
@@ -176,7 +177,7 @@ def main():
     class_ms = {k: v[0] / args.steps for k, v in prof.items()}
     alg_bytes_step = float(B * sum(conv_layer_bytes(spec, H, W, ep) for ep in exits))
     roofline["algorithmic_bytes_per_step"] = alg_bytes_step
-    tr = measured_traffic("conv_igemm")
+    tr = measured_traffic("mfma_kernels")
     if tr is not None and not args.microbatch:
         roofline["traffic"] = tr / max(conv_launches, 1)          # per launch, like `achieved`
         roofline["traffic_bytes_per_step"] = tr

@@ -372,7 +372,7 @@ int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int
     } else {
         {
             Scope sc(m, THIA_K_STEM);
-            HIP_TRY(m, launch_stem(frames, nb, H, W, m->stem_w, m->stem_wk, m->stem_b, m->mean, m->stdv, m->precision, ws.act[2], m->stream));
+            HIP_TRY(m, launch_stem(frames, nb, H, W, m->stem_w, m->stem_b, m->mean, m->stdv, ws.act[2], m->stream));
         }
         Scope sc(m, THIA_K_POOL);
         HIP_TRY(m, launch_maxpool(ws.act[2], nb, Hs, Ws, m->stem_ch, m->precision, ws.act[0], m->stream));
@@ -936,7 +936,7 @@ int thia_op_stem(thia_model* m, const uint8_t* frames, int n, int H, int W, void
         e = launch_stem_pool(frames, n, H, W, m->stem_wk, m->stem_b, m->mean, m->stdv, out, m->stream);
     } else {
         if (hipMalloc(&tmp, (size_t)n * Hs * Ws * 64 * m->esz) != hipSuccess) return fail(m, THIA_E_NOMEM, "stem scratch allocation failed");
-        e = launch_stem(frames, n, H, W, m->stem_w, m->stem_wk, m->stem_b, m->mean, m->stdv, m->precision, tmp, m->stream);
+        e = launch_stem(frames, n, H, W, m->stem_w, m->stem_b, m->mean, m->stdv, tmp, m->stream);
         if (e == hipSuccess) e = launch_maxpool(tmp, n, Hs, Ws, 64, m->precision, out, m->stream);
     }
     hipError_t e2 = hipStreamSynchronize(m->stream);

@@ -2,11 +2,12 @@
 // (+ bias, ReLU), and the 3x3 stride-2 max-pool.  Input frames are planar uint8
 // [n,3,H,W]; outputs are NHWC.
 //
-// The stem contracts only K = 3*7*7 = 147 values per output, so it runs on the vector
-// ALUs: a 256-thread block owns a 16x16 tile of output pixels, stages the normalised
-// 37x37x3 input patch in LDS once, and every thread accumulates all 64 output channels of
-// its pixel in registers.  Weights are indexed uniformly across the wavefront, so they
-// are fetched through the scalar path rather than per lane.
+// bf16 models: one persistent matrix-core kernel does normalisation, stem, ReLU and pool
+// (stem_pool_mfma_kernel).  fp32 models: the stem contracts only K = 3*7*7 = 147 values per
+// output and runs on the vector ALUs (stem_kernel: a 256-thread block owns a 16x16 tile of
+// output pixels, stages the normalised 37x37x3 patch in LDS once, and every thread
+// accumulates all 64 output channels of its pixel; weights are wavefront-uniform), followed
+// by maxpool_kernel.
 #include <algorithm>
 #include <type_traits>
 
@@ -82,145 +83,17 @@ __global__ __launch_bounds__(256) void stem_kernel(const uint8_t* __restrict__ f
 
 // ---------------------------------------------------------------------------------
 // bf16 stem on the matrix cores.  The 7x7x3 window is laid out as K = 22 rows x 8 taps:
-// row r = c*7 + ky (row 21 is padding), tap j <-> input column 2*ox - 4 + j (j = 0 has a
-// zero weight, j = 1..7 are kx = 0..6).  With that layout the 8 consecutive K values a
-// lane feeds to one 32x32x16 MFMA are 8 consecutive pixels of one input row, i.e. four
-// aligned dwords of the normalised bf16 patch held in LDS: no im2col copy is ever built.
-// A 256-thread block owns 16 rows x 32 columns of stem outputs (wavefront w: rows 4w..4w+3,
-// each row one 32-pixel MFMA tile, both 32-channel tiles).  Results (+bias, ReLU, bf16)
-// go through a wavefront-private LDS tile so that the NHWC stores are 16 bytes per lane
-// and cover whole 128-byte pixel rows.
+// row r = c*7 + ky (row 21 is padding), tap j = kx + 1 (j = 0 has a zero weight).  With
+// that layout the 8 consecutive K values a lane feeds to one 32x32x16 MFMA are 8
+// consecutive pixels of one input row of the normalised bf16 patch held in LDS (four
+// dwords): no im2col copy is ever built.
 typedef __attribute__((ext_vector_type(8))) __bf16 sbf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float sf32x16_t;
 
-constexpr int MT_ROWS = 16, MT_COLS = 32;
-constexpr int MP_ROWS = 2 * MT_ROWS + 5;       // 37 patch rows
-constexpr int MP_W = 2 * MT_COLS + 8;          // 72 patch columns (70 used)
+constexpr int MP_W = 72;                       // patch columns (2 * 32 stem columns + taps)
 constexpr int MK_ROWS = 22;                    // 21 (c,ky) rows + 1 zero row
 constexpr int MW_PITCH = MK_ROWS * 16 + 16;    // bytes per channel row of the weight tile (padded)
 constexpr int ME_PITCH = 128 + 16;             // epilogue row pitch (64 bf16 + pad)
-
-__global__ __launch_bounds__(256) void stem_mfma_kernel(const uint8_t* __restrict__ frames, int H, int W, int Hs, int Ws,
-                                                        const bf16_t* __restrict__ wk /*[64][22*8]*/,
-                                                        const float* __restrict__ bias, float mean, float stdv,
-                                                        bf16_t* __restrict__ out) {
-    __shared__ __align__(16) bf16_t patch[3 * MP_ROWS * MP_W];
-    __shared__ __align__(16) unsigned char wt[64 * MW_PITCH];
-    __shared__ __align__(16) unsigned char etile[4 * 32 * ME_PITCH];
-    __shared__ bf16_t lut[256];
-    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
-    const int ox0 = blockIdx.x * MT_COLS, oy0 = blockIdx.y * MT_ROWS, img = blockIdx.z;
-    lut[t] = f32_to_bf16(((float)t - mean) / stdv);
-    for (int i = t; i < 64 * MK_ROWS; i += 256) {  // 16-byte chunks of the weight tile
-        const int ch = i / MK_ROWS, r = i - ch * MK_ROWS;
-        *reinterpret_cast<u32x4_t*>(wt + ch * MW_PITCH + r * 16) = *reinterpret_cast<const u32x4_t*>(wk + (size_t)ch * MK_ROWS * 8 + r * 8);
-    }
-    __syncthreads();
-    const int ix0 = 2 * ox0 - 4, iy0 = 2 * oy0 - 3;
-    const uint8_t* f = frames + (size_t)img * 3 * H * W;
-    // Patch fill: all global loads of a thread are issued before any of them is consumed.  When the
-    // frame width is a multiple of 4 every patch row starts on a 4-byte boundary (ix0 is a multiple of 4)
-    // and is fetched as dwords; out-of-image pixels become the bf16 zero of the normalised tensor.
-    constexpr int DW_ROW = MP_W / 4;                      // 18 dwords per patch row
-    constexpr int N_DW = 3 * MP_ROWS * DW_ROW;            // 1998 dwords per patch
-    constexpr int PER_T = (N_DW + 255) / 256;             // 8 per thread
-    if ((W & 3) == 0) {
-        uint32_t raw[PER_T];
-#pragma unroll
-        for (int q = 0; q < PER_T; ++q) {
-            const int i = q * 256 + t;
-            raw[q] = 0u;
-            if (i < N_DW) {
-                const int c = i / (MP_ROWS * DW_ROW), r = i - c * (MP_ROWS * DW_ROW), py = r / DW_ROW, pd = r - py * DW_ROW;
-                const int iy = iy0 + py, ix = ix0 + 4 * pd;
-                if ((unsigned)iy < (unsigned)H && ix >= 0 && ix + 3 < W)
-                    raw[q] = *reinterpret_cast<const uint32_t*>(f + ((size_t)c * H + iy) * W + ix);
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < PER_T; ++q) {
-            const int i = q * 256 + t;
-            if (i < N_DW) {
-                const int c = i / (MP_ROWS * DW_ROW), r = i - c * (MP_ROWS * DW_ROW), py = r / DW_ROW, pd = r - py * DW_ROW;
-                const int iy = iy0 + py, ix = ix0 + 4 * pd;
-                const bool in = (unsigned)iy < (unsigned)H && ix >= 0 && ix + 3 < W;
-                uint32_t lo = 0u, hi = 0u;
-                if (in) {
-                    lo = (uint32_t)lut[raw[q] & 0xffu] | ((uint32_t)lut[(raw[q] >> 8) & 0xffu] << 16);
-                    hi = (uint32_t)lut[(raw[q] >> 16) & 0xffu] | ((uint32_t)lut[raw[q] >> 24] << 16);
-                }
-                uint32_t* d = reinterpret_cast<uint32_t*>(patch + (c * MP_ROWS + py) * MP_W + 4 * pd);
-                d[0] = lo;
-                d[1] = hi;
-            }
-        }
-    } else {
-        for (int i = t; i < 3 * MP_ROWS * MP_W; i += 256) {
-            const int c = i / (MP_ROWS * MP_W), r = i - c * (MP_ROWS * MP_W), py = r / MP_W, px = r - py * MP_W;
-            const int iy = iy0 + py, ix = ix0 + px;
-            bf16_t v = 0;  // zero padding of the normalised tensor
-            if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) v = lut[f[((size_t)c * H + iy) * W + ix]];
-            patch[i] = v;
-        }
-    }
-    __syncthreads();
-
-    const int g = lane >> 5, pxl = lane & 31;
-    sf32x16_t acc[4][2];
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[r][i][e] = 0.f;
-#pragma unroll
-    for (int s = 0; s < MK_ROWS / 2; ++s) {
-        const int rr = 2 * s + g;                       // K row fed by this lane half
-        const int rq = rr < 21 ? rr : 0;                // padding row: weights are zero, any finite data will do
-        const int c = rq / 7, ky = rq - 7 * c;
-        u32x4_t fa[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const u32x4_t*>(wt + (i * 32 + pxl) * MW_PITCH + rr * 16);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = 2 * (4 * wv + r) + ky;      // patch row of this tap row
-            const uint32_t* src = reinterpret_cast<const uint32_t*>(patch + (c * MP_ROWS + row) * MP_W + 2 * pxl);
-            u32x4_t fb = {src[0], src[1], src[2], src[3]};
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-                acc[r][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(sbf16x8_t, fa[i]), __builtin_bit_cast(sbf16x8_t, fb),
-                                                                    acc[r][i], 0, 0, 0);
-        }
-    }
-
-    unsigned char* ep = etile + wv * 32 * ME_PITCH;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        // accumulator element e of lane l: channel 8*(e/4) + 4*(l/32) + e%4 (+32 i), pixel l%32
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int ch = i * 32 + 8 * v + 4 * g;
-                const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(bias + ch);
-                uint32_t* d = reinterpret_cast<uint32_t*>(ep + pxl * ME_PITCH + ch * 2);
-                d[0] = pack_bf16x2(fmaxf(acc[r][i][4 * v] + bv.x, 0.f), fmaxf(acc[r][i][4 * v + 1] + bv.y, 0.f));
-                d[1] = pack_bf16x2(fmaxf(acc[r][i][4 * v + 2] + bv.z, 0.f), fmaxf(acc[r][i][4 * v + 3] + bv.w, 0.f));
-            }
-        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the tile is private to this wavefront
-        __builtin_amdgcn_wave_barrier();
-        const int oy = oy0 + 4 * wv + r;
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int p = it * 8 + (lane >> 3), chunk = lane & 7;
-            const int ox = ox0 + p;
-            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(ep + p * ME_PITCH + chunk * 16);
-            if (oy < Hs && ox < Ws) *reinterpret_cast<u32x4_t*>(out + (((size_t)img * Hs + oy) * Ws + ox) * SC + chunk * 8) = v;
-        }
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_wave_barrier();
-    }
-}
 
 // Stem and max-pool in one kernel (bf16 models): the stem tensor is four times the size of the pooled one
 // and is otherwise written and read back once.  A block owns 8 x 15 pooled pixels = stem rows 2 py0 - 1 ..
@@ -436,16 +309,12 @@ hipError_t launch_stem_pool(const uint8_t* frames, int n, int H, int W, const bf
     return hipGetLastError();
 }
 
-hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const bf16_t* wk, const float* bias, float mean,
-                       float stdv, int precision, void* out, hipStream_t s) {
+hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const float* bias, float mean, float stdv, void* out,
+                       hipStream_t s) {
     const int Hs = (H + 6 - 7) / 2 + 1, Ws = (W + 6 - 7) / 2 + 1;
     dim3 grid((Ws + ST - 1) / ST, (Hs + ST - 1) / ST, n);
     if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
-    if (precision) {
-        dim3 g2((Ws + MT_COLS - 1) / MT_COLS, (Hs + MT_ROWS - 1) / MT_ROWS, n);
-        hipLaunchKernelGGL(stem_mfma_kernel, g2, dim3(256), 0, s, frames, H, W, Hs, Ws, wk, bias, mean, stdv, static_cast<bf16_t*>(out));
-    } else
-        hipLaunchKernelGGL(stem_kernel<false>, grid, dim3(256), 0, s, frames, H, W, Hs, Ws, w, bias, mean, stdv, out);
+    hipLaunchKernelGGL(stem_kernel<false>, grid, dim3(256), 0, s, frames, H, W, Hs, Ws, w, bias, mean, stdv, out);
     return hipGetLastError();
 }
 

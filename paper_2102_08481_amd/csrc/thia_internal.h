@@ -77,11 +77,12 @@ hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s)
 void pack_mfma_fragments(const bf16_t* w, int Cout, int K, bf16_t* dst);
 
 // ---------------------------------------------------------------- stem + pool
-// frames u8 [n,3,H,W]; out T [n,Hs,Ws,64] NHWC with ReLU applied.  x = (u8 - mean) / stdv, zero padding
-// after normalisation.  precision 0 uses w: fp32 [(c*7+ky)*7+kx][64]; precision 1 uses wk: bf16
-// [64][22][8] with wk[ch][c*7+ky][j] = weight(ch, c, ky, kx = j-1) for j = 1..7, zero for j = 0 and row 21.
-hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const bf16_t* wk, const float* bias,
-                       float mean, float stdv, int precision, void* out, hipStream_t s);
+// frames u8 [n,3,H,W].  x = (u8 - mean) / stdv, zero padding after normalisation.
+// fp32 models: launch_stem (out float [n,Hs,Ws,64] NHWC with ReLU applied; w: fp32 [(c*7+ky)*7+kx][64]) followed by
+// launch_maxpool.
+hipError_t launch_stem(const uint8_t* frames, int n, int H, int W, const float* w, const float* bias, float mean, float stdv, void* out,
+                       hipStream_t s);
+// wk: bf16 [64][22][8] with wk[ch][c*7+ky][j] = weight(ch, c, ky, kx = j-1) for j = 1..7, zero for j = 0 and row 21.
 // bf16 models: stem and 3x3 / stride 2 / pad 1 max-pool in one kernel; out [n,Hp,Wp,64] NHWC bf16.
 hipError_t launch_stem_pool(const uint8_t* frames, int n, int H, int W, const bf16_t* wk, const float* bias, float mean, float stdv,
                             void* out, hipStream_t s);
