@@ -286,6 +286,84 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
         __syncthreads();
     }
 
+    // ---- fused RPN predictors (large bf16 tile only): the block's ReLU'd 256 x 256 tile, rounded to bf16 as the
+    // stored tensor would be, stays in LDS and is contracted with the 1x1 predictor weights right away.
+    if constexpr (std::is_same<T, bf16_t>::value && std::is_same<OutT, bf16_t>::value && BM == 256 && BN == 256 && WAVES_M == 2 &&
+                  WAVES_N == 4 && MODE == 0) {
+        if (a.head_w != nullptr) {
+            constexpr int YP = BN * 2 + 16;            // LDS row pitch of the bf16 tile
+            constexpr int HKS = BN / 16;               // k-steps of the predictor contraction (16)
+            constexpr int HP = 96 * 4 + 16;            // fp32 row pitch of the per-wavefront output tile
+            static_assert(BM * YP <= 2 * (BN + BM) * LDS_ROW && 32 * HP <= 32 * YP, "tile and output staging fit");
+            const u32x4_t* __restrict__ hwf = reinterpret_cast<const u32x4_t*>(a.head_w) + lane;
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+#pragma unroll
+                for (int i = 0; i < TN; ++i)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int ch = wn * WN + i * 32 + 8 * v + 4 * (lane >> 5);
+                        const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(a.bias + n0 + ch);
+                        u32x2_t o = {pack_bf16x2(fmaxf(acc[i][j][4 * v] + bv.x, 0.f), fmaxf(acc[i][j][4 * v + 1] + bv.y, 0.f)),
+                                     pack_bf16x2(fmaxf(acc[i][j][4 * v + 2] + bv.z, 0.f), fmaxf(acc[i][j][4 * v + 3] + bv.w, 0.f))};
+                        *reinterpret_cast<u32x2_t*>(smem + (size_t)(wm * WM + j * 32 + frag_row) * YP + ch * 2) = o;
+                    }
+            // predictor weight fragments (3 channel tiles per k-step) run HRING k-steps ahead of their use; the first
+            // ones and the bias tile are requested once the accumulators are parked, in flight across the barrier
+            constexpr int HRING = 4;
+            __builtin_amdgcn_sched_barrier(0);   // (hoisted above the parking loop they would spill)
+            u32x4_t hw[HRING * 3];
+#pragma unroll
+            for (int ks = 0; ks < HRING; ++ks)
+#pragma unroll
+                for (int i = 0; i < 3; ++i) hw[ks * 3 + i] = hwf[(i * HKS + ks) * 64];
+            f32x16_t hacc[3];
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const f32x4_t q = *reinterpret_cast<const f32x4_t*>(a.head_b + i * 32 + 8 * v + 4 * (lane >> 5));
+                    hacc[i][4 * v] = q.x; hacc[i][4 * v + 1] = q.y; hacc[i][4 * v + 2] = q.z; hacc[i][4 * v + 3] = q.w;
+                }
+            __syncthreads();
+            // wavefront wv: pixels 32 wv .. 32 wv + 31 of the tile against all 96 (padded) predictor rows
+            const unsigned char* yrow = smem + (size_t)(wv * 32 + frag_row) * YP + frag_off;
+            static_for<0, HKS>([&](auto kc) {
+                constexpr int ks = decltype(kc)::value;
+                const u32x4_t b = *reinterpret_cast<const u32x4_t*>(yrow + ks * 32);
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    mma_step<T>(hacc[i], hw[(ks % HRING) * 3 + i], b);
+                    if (ks + HRING < HKS) hw[(ks % HRING) * 3 + i] = hwf[(i * HKS + ks + HRING) * 64];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            // the wavefront's own 32 rows of the tile are dead now: fp32 results go there, then out in dense rows
+            unsigned char* hp = smem + (size_t)(wv * 32) * YP;
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    f32x4_t r = {hacc[i][4 * v], hacc[i][4 * v + 1], hacc[i][4 * v + 2], hacc[i][4 * v + 3]};
+                    *reinterpret_cast<f32x4_t*>(hp + (size_t)frag_row * HP + (i * 32 + 8 * v + 4 * (lane >> 5)) * 4) = r;
+                }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+            const int A = a.head_a;
+            const int mbase = m0 + wv * 32;
+            for (int e = lane; e < 32 * A; e += 64) {
+                const int px = e / A, q = e - px * A;
+                if (mbase + px >= M) continue;
+                const f32x4_t d = *reinterpret_cast<const f32x4_t*>(hp + (size_t)px * HP + q * 16);
+                *reinterpret_cast<f32x4_t*>(a.head_deltas + ((size_t)(mbase + px) * A + q) * 4) = d;
+                a.head_logits[(size_t)(mbase + px) * A + q] = *reinterpret_cast<const float*>(hp + (size_t)px * HP + (4 * A + q) * 4);
+            }
+            return;
+        }
+    }
+
     // ---- epilogue.  Accumulator element e of lane l: channel 8*(e/4) + 4*(l/32) + e%4, pixel l%32.
     OutT* __restrict__ out0 = static_cast<OutT*>(a.out0);
     OutT* __restrict__ out1 = static_cast<OutT*>(a.out1);
@@ -382,6 +460,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     }
 }
 
+// Whether launch_conv picks the 256 x 256 bf16 tile for this layer (the only variant with the fused predictors).
+static bool takes_large_tile(const ConvArgs& a) {
+    const long long M = (long long)a.N * a.Ho * a.Wo;
+    const long long K = (long long)a.kh * a.kw * a.Cin + (a.in2 ? a.Cin2 : 0);
+    const long long tiles_l = ((M + 255) / 256) * ((a.Cout + 255) / 256);
+    return a.Cout % 256 == 0 && K >= 512 && (tiles_l >= 200 || (tiles_l >= 150 && K >= 8192)) && a.out1 == nullptr;
+}
+
+bool conv_heads_supported(const ConvArgs& a, int precision) {
+    if (precision != 1 || a.head_w == nullptr || a.head_b == nullptr || a.head_logits == nullptr || a.head_deltas == nullptr) return false;
+    if (a.Cout != 256 || a.in2 != nullptr || a.res != nullptr || !a.relu || a.head_a < 1 || 5 * a.head_a > 96) return false;
+    if (a.kh == 1 && a.kw == 1 && a.pad == 0) return false;   // only the general-filter instantiation carries the predictor path
+    return conv_supported(a, precision) && takes_large_tile(a);
+}
+
 bool conv_supported(const ConvArgs& a, int precision) {
     const int bk = precision ? 64 : 32;
     if (a.Cin <= 0 || a.Cin % bk) return false;
@@ -426,6 +519,10 @@ static hipError_t launch_one(const ConvArgs& a, hipStream_t s) {
 
 hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream_t s) {
     if (!conv_supported(a, precision)) return hipErrorInvalidValue;
+    if (a.head_w != nullptr) {   // fused predictors exist in one kernel variant only
+        if (out_f32 || !conv_heads_supported(a, precision)) return hipErrorInvalidValue;
+        return launch_one<bf16_t, 256, 256, 128, 2, 4, bf16_t, true>(a, s);
+    }
     const bool narrow = a.Cout <= 64;
     if (precision == 0) {
         return narrow ? launch_one<float, 128, 64, 128, 2, 2, float>(a, s) : launch_one<float, 128, 128, 128, 2, 2, float, true>(a, s);

@@ -34,6 +34,10 @@ struct Block {
 };
 struct ExitUnit {
     Layer lateral, rpn_conv, rpn_head /* obj (A) ++ delta (4A) */, fc1, fc2, pred /* cls (Kc) ++ box (4Kc) */;
+    // RPN predictors for the convolution kernel's fused path: 96 rows (4A delta rows, A logit rows, zero rows) x 256
+    // in MFMA fragment order, and the matching fp32 bias; null when the exit has no fused variant
+    bf16_t* head_f = nullptr;
+    float* head_fb = nullptr;
 };
 
 struct Tap {
@@ -318,20 +322,33 @@ struct Second {  // second source of a dual 1x1 convolution
     const void* in = nullptr;
     int Cin = 0, H = 0, W = 0, stride = 1;
 };
+struct Heads {  // RPN predictors fused into the convolution (ConvArgs::head_*)
+    const bf16_t* w = nullptr;
+    const float* b = nullptr;
+    float *logits = nullptr, *deltas = nullptr;
+    int A = 0;
+};
 
-int run_conv(thia_model* m, int cls, const Layer& L, const void* in, int n, int H, int W, int stride, int pad, const void* res,
-             bool relu, bool out_f32, void* out0, void* out1 = nullptr, int n_split = -1, const Second* second = nullptr) {
-    ConvArgs a{};
+void fill_conv_args(const thia_model* m, ConvArgs& a, const Layer& L, const void* in, int n, int H, int W, int stride, int pad,
+                    const void* res, bool relu, void* out0, void* out1, int n_split, const Second* second) {
+    a = ConvArgs{};
     a.in = in; a.w = L.w; a.bias = L.b; a.res = res; a.out0 = out0; a.out1 = out1; a.zeros = m->zeros;
     a.N = n; a.H = H; a.W = W; a.Cin = L.ci; a.Cout = L.co;
     if (second) {
         a.in2 = second->in; a.Cin2 = second->Cin; a.H2 = second->H; a.W2 = second->W; a.stride2 = second->stride;
         a.Cin = L.ci - second->Cin;
-    } a.kh = L.k; a.kw = L.k; a.stride = stride; a.pad = pad;
+    }
+    a.kh = L.k; a.kw = L.k; a.stride = stride; a.pad = pad;
     a.Ho = conv_out(H, L.k, stride, pad); a.Wo = conv_out(W, L.k, stride, pad);
     a.relu = relu ? 1 : 0;
     if (out1) { a.n_split = n_split; a.ld0 = n_split; a.ld1 = L.co - n_split; }
     else { a.n_split = L.co; a.ld0 = L.co; a.ld1 = 0; }
+}
+
+int run_conv(thia_model* m, int cls, const Layer& L, const void* in, int n, int H, int W, int stride, int pad, const void* res,
+             bool relu, bool out_f32, void* out0, void* out1 = nullptr, int n_split = -1, const Second* second = nullptr) {
+    ConvArgs a;
+    fill_conv_args(m, a, L, in, n, H, W, stride, pad, res, relu, out0, out1, n_split, second);
     Scope sc(m, cls);
     HIP_TRY(m, launch_conv(a, m->precision, out_f32, m->stream));
     return THIA_OK;
@@ -423,8 +440,22 @@ int run_heads(thia_model* m, const void* feat, int f0, int nb, int H, int W, int
         TRY(run_conv(m, THIA_K_CONV, E.lateral, feat, nb, g.Hk, g.Wk, 1, 0, nullptr, false, false, ws.hf));
         hf = ws.hf;
     }
-    TRY(run_conv(m, THIA_K_CONV, E.rpn_conv, hf, nb, g.Hk, g.Wk, 1, 1, nullptr, true, false, ws.rpn_t));
-    TRY(run_conv(m, THIA_K_CONV, E.rpn_head, ws.rpn_t, nb, g.Hk, g.Wk, 1, 0, nullptr, false, true, ws.logits, ws.deltas, A));
+    bool fused_heads = false;
+    if (E.head_f && m->fuse_blocks) {
+        // 3x3 + ReLU and both 1x1 predictors in one launch: the 256-channel tensor between them never leaves LDS
+        ConvArgs a;
+        fill_conv_args(m, a, E.rpn_conv, hf, nb, g.Hk, g.Wk, 1, 1, nullptr, true, ws.rpn_t, nullptr, -1, nullptr);
+        a.head_w = E.head_f; a.head_b = E.head_fb; a.head_logits = ws.logits; a.head_deltas = ws.deltas; a.head_a = A;
+        if (conv_heads_supported(a, m->precision)) {
+            Scope sc(m, THIA_K_CONV);
+            HIP_TRY(m, launch_conv(a, m->precision, false, m->stream));
+            fused_heads = true;
+        }
+    }
+    if (!fused_heads) {
+        TRY(run_conv(m, THIA_K_CONV, E.rpn_conv, hf, nb, g.Hk, g.Wk, 1, 1, nullptr, true, false, ws.rpn_t));
+        TRY(run_conv(m, THIA_K_CONV, E.rpn_head, ws.rpn_t, nb, g.Hk, g.Wk, 1, 0, nullptr, false, true, ws.logits, ws.deltas, A));
+    }
     {
         Scope sc(m, THIA_K_TOPK);
         HIP_TRY(m, launch_rpn_proposals(ws.logits, ws.deltas, nb, nA, m->pre, g.Wk, g.stride, (float)W, (float)H, m->anc, ws.topk,
@@ -638,6 +669,20 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
             return bad(THIA_E_BLOB);
         if (!rc) rc = upload_layer(m, rc3, nullptr, E.rpn_conv);
         if (!rc) rc = upload_layer(m, obj, &dl, E.rpn_head);
+        if (!rc && m->precision == 1 && hc == 256 && 5 * A <= 96) {
+            std::vector<float> wcat((size_t)96 * hc, 0.f), bcat(96, 0.f);
+            std::memcpy(wcat.data(), dl.w, sizeof(float) * 4 * A * hc);
+            std::memcpy(wcat.data() + (size_t)4 * A * hc, obj.w, sizeof(float) * A * hc);
+            std::memcpy(bcat.data(), dl.b, sizeof(float) * 4 * A);
+            std::memcpy(bcat.data() + 4 * A, obj.b, sizeof(float) * A);
+            HostLayer cat;
+            cat.w = wcat.data(); cat.b = bcat.data(); cat.co = 96; cat.ci = hc; cat.k = 1;
+            rc = upload_fragments(m, cat, &E.head_f);
+            if (!rc) {
+                HIP_TRY(m, hipMalloc(reinterpret_cast<void**>(&E.head_fb), 96 * 4));
+                HIP_TRY(m, hipMemcpy(E.head_fb, bcat.data(), 96 * 4, hipMemcpyHostToDevice));
+            }
+        }
         // FC1 reads ROI features laid out [(ph*P+pw)][c]: the same O,(kh,kw),I repack as a PxP convolution,
         // after which it is a plain matrix product over K = P*P*hc
         if (!rc) rc = upload_layer(m, fc1, nullptr, E.fc1);
@@ -672,6 +717,9 @@ void thia_free_model(thia_model* m) {
     for (int e = 0; e < 4; ++e) {
         ExitUnit& E = m->ex[e];
         free_layer(E.lateral); free_layer(E.rpn_conv); free_layer(E.rpn_head); free_layer(E.fc1); free_layer(E.fc2); free_layer(E.pred);
+        if (E.head_f) (void)hipFree(E.head_f);
+        if (E.head_fb) (void)hipFree(E.head_fb);
+        E.head_f = nullptr; E.head_fb = nullptr;
     }
     delete m;
 }

@@ -49,12 +49,24 @@ struct ConvArgs {
     // Used to sum a bottleneck's last 1x1 convolution and its projection shortcut in one accumulator.
     const void* in2;  // null = single source
     int Cin2, H2, W2, stride2;
+    // Optional fused RPN predictors (bf16, Cout == 256, ReLU, large-tile kernel only; conv_heads_supported): instead of
+    // storing the convolution's output t, the block rounds its 256-pixel x 256-channel tile to bf16 in LDS and
+    // multiplies it by the 1x1 predictor weights: logits[m, a] = bl[a] + sum_c Wl[a, c] t[m, c] (a < head_a) and
+    // deltas[m, j] = bd[j] + sum_c Wd[j, c] t[m, c] (j < 4 head_a), both fp32 and dense.  head_w: bf16 [96][256] rows
+    // ordered (4 head_a delta rows, head_a logit rows, zero rows) in MFMA fragment order; head_b: fp32 [96] likewise.
+    const void* head_w;  // null = plain convolution
+    const float* head_b;
+    float* head_logits;
+    float* head_deltas;
+    int head_a;
 };
 // precision 0: float tensors, fp32 MFMA; 1: bf16 tensors, bf16 MFMA with fp32 accumulation.
 // out_f32: store float outputs even when tensors are bf16.  Returns hipSuccess or the launch error.
 hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream_t s);
 // Shapes the kernel accepts.
 bool conv_supported(const ConvArgs& a, int precision);
+// True if launch_conv would run `a` (bf16, with head_* set) on the kernel variant that has the fused predictors.
+bool conv_heads_supported(const ConvArgs& a, int precision);
 
 // ---------------------------------------------------------------- single-kernel bottleneck (bf16, stride 1)
 // first == 0 (identity block): y = relu(W3 relu(W2 * relu(W1 x + b1) + b2) + b3 + x), x [N][H][W][4*width].

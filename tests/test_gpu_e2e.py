@@ -132,6 +132,30 @@ def test_fused_blocks_match_layer_by_layer_path():
             assert torch.equal(a, b)
 
 
+def test_fused_rpn_predictors_match_separate_launches():
+    """At sizes where the RPN 3x3 runs on the large tile, its ReLU'd output stays in LDS and both 1x1
+    predictors are applied in the same kernel.  Same bf16 rounding of the intermediate and same K order as
+    the two-launch path: logits and deltas agree to fp32 rounding (equality reported), detections follow."""
+    cfg = CONFIGS[3]
+    m, _ = gpu_model(cfg.model, cfg.weight_seed)
+    frames = to_dev(make_frames(SceneSpec(540, 960, 3, 6, 12, 16, 120), 45))
+    res = []
+    m.set_debug(True)
+    for on in (True, False):
+        m.set_fusion(on)
+        o = m.detect_chunk(frames, 1)
+        torch.cuda.synchronize()
+        res.append(([t.clone() for t in o], m.tap("rpn_logits").copy(), m.tap("rpn_deltas").copy()))
+    m.set_fusion(True)
+    m.set_debug(False)
+    assert np.isfinite(res[0][1]).all() and np.isfinite(res[0][2]).all()
+    assert relerr(res[0][1], res[1][1]) <= 1e-5, relerr(res[0][1], res[1][1])
+    assert relerr(res[0][2], res[1][2]) <= 1e-5, relerr(res[0][2], res[1][2])
+    if np.array_equal(res[0][1], res[1][1]) and np.array_equal(res[0][2], res[1][2]):
+        for a, b in zip(res[0][0], res[1][0]):
+            assert torch.equal(a, b)
+
+
 def test_plan_is_bit_identical_to_per_chunk_calls_and_skip_is_empty():
     m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
     plan = [1, 4, 0, 2, 3, 1]
