@@ -277,12 +277,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     // with the two wavefronts of a SIMD taking turns.)
     load_tiles(0, st0);
     store_tiles(0, st0);
+    if (KT > 1) load_tiles(1, st0);
     __syncthreads();
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < KT) load_tiles(kt + 1, st0);
         compute(buf);
         if (kt + 1 < KT) store_tiles(buf ^ 1, st0);
+        // the requests for tile kt + 2 go out at the END of the step, into the registers the LDS write has just
+        // freed: a wavefront that finishes early queues its loads at the CU's address unit while the others
+        // still multiply (issued right after the barrier, all wavefronts queue there at once and the matrix
+        // pipe idles), and the data has the whole next step to arrive
+        if (kt + 2 < KT) load_tiles(kt + 2, st0);
         __syncthreads();
     }
 
