@@ -279,15 +279,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     store_tiles(0, st0);
     if (KT > 1) load_tiles(1, st0);
     __syncthreads();
+    // The requests for tile kt + 2 go out right after the LDS write of tile kt + 1 has freed the staging
+    // registers, so the data has a whole step to arrive.  With 8 wavefronts the two that share a SIMD (w and
+    // w + 4) do this staging at opposite ends of the step - one before its MFMAs, one after - so that one of them
+    // multiplies while the other writes LDS and queues at the CU's address unit (issued by all wavefronts at
+    // once right after the barrier, the loads cost ~1300 of ~4100 cycles per step with the matrix pipe idle).
+    const bool stage_first = NT == 512 && (wv >> 2) == 1;
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
+        if (stage_first) {
+            if (kt + 1 < KT) store_tiles(buf ^ 1, st0);
+            if (kt + 2 < KT) load_tiles(kt + 2, st0);
+        }
         compute(buf);
-        if (kt + 1 < KT) store_tiles(buf ^ 1, st0);
-        // the requests for tile kt + 2 go out at the END of the step, into the registers the LDS write has just
-        // freed: a wavefront that finishes early queues its loads at the CU's address unit while the others
-        // still multiply (issued right after the barrier, all wavefronts queue there at once and the matrix
-        // pipe idles), and the data has the whole next step to arrive
-        if (kt + 2 < KT) load_tiles(kt + 2, st0);
+        if (!stage_first) {
+            if (kt + 1 < KT) store_tiles(buf ^ 1, st0);
+            if (kt + 2 < KT) load_tiles(kt + 2, st0);
+        }
         __syncthreads();
     }
 
