@@ -154,7 +154,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     size_t b_base[PB];
     size_t b_base2[DUAL ? PB : 1];
     const T* __restrict__ in2 = static_cast<const T*>(a.in2);
-    int b_iy0[PB], b_ix0[PB];
+    // general filters: signed element offset of the (tap 0, channel 0) input of the row's pixel and, per filter tap, one
+    // bit "tap lies inside the image" (kh * kw <= 32)
+    long long b_off0[ONE ? 1 : PB];
+    uint32_t b_taps[ONE ? 1 : PB];
     bool b_ok[PB];
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
@@ -163,11 +166,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
         const int mm = b_ok[p] ? m : 0;
         const int img = mm / HoWo, rem = mm - img * HoWo;
         const int oy = rem / a.Wo, ox = rem - oy * a.Wo;
-        b_iy0[p] = oy * a.stride - a.pad;
-        b_ix0[p] = ox * a.stride - a.pad;
+        const int iy0 = oy * a.stride - a.pad, ix0 = ox * a.stride - a.pad;
         b_base[p] = (size_t)img * a.H * a.W * a.Cin + (size_t)lchunk * EPC;
         // 1x1, unpadded: the row's input pixel is fixed for the whole K loop
-        if constexpr (ONE) b_base[p] += ((size_t)b_iy0[p] * a.W + b_ix0[p]) * a.Cin;
+        if constexpr (ONE) {
+            b_base[p] += ((size_t)iy0 * a.W + ix0) * a.Cin;
+        } else {
+            b_off0[p] = (long long)b_base[p] + ((long long)iy0 * a.W + ix0) * a.Cin;
+            uint32_t bits = 0;
+            for (int ky = 0; ky < a.kh; ++ky)
+                for (int kx = 0; kx < a.kw; ++kx)
+                    if ((unsigned)(iy0 + ky) < (unsigned)a.H && (unsigned)(ix0 + kx) < (unsigned)a.W) bits |= 1u << (ky * a.kw + kx);
+            b_taps[p] = bits;
+        }
         if constexpr (DUAL)
             b_base2[p] = (((size_t)img * a.H2 + (size_t)oy * a.stride2) * a.W2 + (size_t)ox * a.stride2) * a.Cin2 + (size_t)lchunk * EPC;
     }
@@ -182,12 +193,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     const int cin_tiles = a.Cin / BK;
     const int KT = K / BK;
 
-    struct Stage { u32x4_t a[PA]; u32x4_t b[PB]; };
+    // zmask: bit p set = activation chunk p is a padded tap and is written to LDS as zeros.  (The select is applied at
+    // the LDS write, one step after the load: applied right after the load it would make every step wait for its data.)
+    struct Stage { u32x4_t a[PA]; u32x4_t b[PB]; uint32_t zmask; };
     Stage st0;
     auto load_tiles = [&](int kt, Stage& st) {
-        // All loads are unconditional so that a K step is one basic block the scheduler can interleave
-        // with the MFMAs: rows beyond M / Cout are clamped to row 0 (they only feed outputs that are never
-        // stored), padded filter taps are fetched from a clamped in-image address and zeroed by a select.
+        // All loads are unconditional: rows beyond M / Cout are clamped to row 0 (they only feed outputs that are
+        // never stored), padded filter taps are fetched from a valid in-image address and zeroed at the LDS write.
+        st.zmask = 0;
         if constexpr (ONE) {
             const int kt1 = a.Cin / BK;  // K tiles of the first source
             if (!DUAL || kt < kt1) {
@@ -205,15 +218,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
         const int tap = kt / cin_tiles;
         const int c0 = (kt - tap * cin_tiles) * BK;
         const int ky = tap / a.kw, kx = tap - ky * a.kw;
+        const long long tap_off = ((long long)ky * a.W + kx) * a.Cin + c0;   // uniform over the block
+        uint32_t zm = 0;
 #pragma unroll
         for (int p = 0; p < PB; ++p) {
-            const int iy = b_iy0[p] + ky, ix = b_ix0[p] + kx;
-            const bool ok = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
-            const int iyc = min(max(iy, 0), a.H - 1), ixc = min(max(ix, 0), a.W - 1);
-            u32x4_t v = *reinterpret_cast<const u32x4_t*>(in + b_base[p] + ((size_t)iyc * a.W + ixc) * a.Cin + c0);
-            const u32x4_t z = {0u, 0u, 0u, 0u};
-            st.b[p] = ok ? v : z;
+            const bool ok = (b_taps[ONE ? 0 : p] >> tap) & 1u;
+            // a padded tap reads the row's (always valid) image base instead and is replaced by zeros at the LDS write
+            const long long off = ok ? b_off0[ONE ? 0 : p] + tap_off : (long long)b_base[p];
+            st.b[p] = *reinterpret_cast<const u32x4_t*>(in + off);
+            zm |= ok ? 0u : (1u << p);
         }
+        st.zmask = zm;
 #pragma unroll
         for (int p = 0; p < PA; ++p) st.a[p] = *reinterpret_cast<const u32x4_t*>(wgt + a_base[p] + (size_t)kt * BK);
     };
@@ -222,8 +237,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
         for (int p = 0; p < PA; ++p)
             *reinterpret_cast<u32x4_t*>(sA + (size_t)(buf * BN + lrow + RPP * p) * LDS_ROW + lchunk * 16) = st.a[p];
 #pragma unroll
-        for (int p = 0; p < PB; ++p)
-            *reinterpret_cast<u32x4_t*>(sB + (size_t)(buf * BM + lrow + RPP * p) * LDS_ROW + lchunk * 16) = st.b[p];
+        for (int p = 0; p < PB; ++p) {
+            const u32x4_t z = {0u, 0u, 0u, 0u};
+            const u32x4_t v = (!ONE && ((st.zmask >> p) & 1u)) ? z : st.b[p];
+            *reinterpret_cast<u32x4_t*>(sB + (size_t)(buf * BM + lrow + RPP * p) * LDS_ROW + lchunk * 16) = v;
+        }
     };
 
     f32x16_t acc[TN][TM];
@@ -491,6 +509,7 @@ bool conv_heads_supported(const ConvArgs& a, int precision) {
 bool conv_supported(const ConvArgs& a, int precision) {
     const int bk = precision ? 64 : 32;
     if (a.Cin <= 0 || a.Cin % bk) return false;
+    if (a.kh < 1 || a.kw < 1 || a.kh * a.kw > 32) return false;   // one validity bit per filter tap
     if (a.N <= 0 || a.Cout <= 0 || a.Ho <= 0 || a.Wo <= 0 || a.zeros == nullptr) return false;
     if (a.in2 != nullptr) {
         if (a.kh != 1 || a.kw != 1 || a.pad != 0 || a.Cin2 <= 0 || a.Cin2 % bk || a.stride2 < 1) return false;
