@@ -264,39 +264,48 @@ __global__ __launch_bounds__(256) void nms_reduce_kernel(const uint64_t* __restr
             if (e < 64 * words) tile[e] = stage[q];
         }
     };
-    if (t == 0) s_nk = 0;
+    if (t == 0) s_nk = -1;    // becomes the final count as soon as max_keep boxes are kept (early exit for all wavefronts)
     uint64_t removed = 0ull;  // wavefront 0: lane w holds word w
     int nk = 0;
     if (wc > 0) fetch(0);
+    __syncthreads();
     for (int c = 0; c < wc; ++c) {
         stash();
         __syncthreads();
         if (c + 1 < wc) fetch(c + 1);
-        if (wv == 0 && nk < max_keep) {
+        if (wv == 0) {
             const int rows = (cnt - 64 * c) < 64 ? (cnt - 64 * c) : 64;
             const uint64_t diag = lane < rows ? tile[(size_t)lane * words + c] : 0ull;
             const uint32_t dlo = (uint32_t)diag, dhi = (uint32_t)(diag >> 32);
             const uint32_t rlo = (uint32_t)removed, rhi = (uint32_t)(removed >> 32);
             uint64_t cur = (uint64_t)(uint32_t)__builtin_amdgcn_readlane(rlo, c) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(rhi, c) << 32);
+            // serial greedy chain over the tile's rows, registers and scalars only
             uint64_t kept = 0ull;
-            for (int b = 0; b < rows; ++b) {
+            int room = max_keep - nk;
+            for (int b = 0; b < rows && room > 0; ++b) {
                 if ((cur >> b) & 1ull) continue;
                 kept |= 1ull << b;
-                if (lane == 0) keep[nk] = 64 * c + b;
-                ++nk;
-                if (nk == max_keep) break;
+                --room;
                 cur |= (uint64_t)(uint32_t)__builtin_amdgcn_readlane(dlo, b) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(dhi, b) << 32);
             }
-            if (lane < words) {
+            // kept rows -> keep list (lane b writes its own slot) and OR of their mask rows into the removed set
+            if ((kept >> lane) & 1ull) keep[nk + __popcll(kept & ((1ull << lane) - 1ull))] = 64 * c + lane;
+            nk += __popcll(kept);
+            if (nk < max_keep && lane < words) {
                 uint64_t acc = 0ull;
-                for (int b = 0; b < rows; ++b)
-                    if ((kept >> b) & 1ull) acc |= tile[(size_t)b * words + lane];
+#pragma unroll 8
+                for (int b = 0; b < 64; ++b) {
+                    const uint64_t row = tile[(size_t)b * words + lane];
+                    acc |= ((kept >> b) & 1ull) ? row : 0ull;
+                }
                 removed |= acc;
             }
+            if (nk == max_keep && lane == 0) s_nk = nk;
         }
         __syncthreads();
+        if (s_nk >= 0) break;   // uniform: written before the barrier
     }
-    if (t == 0) s_nk = nk;
+    if (t == 0 && s_nk < 0) s_nk = nk;
     __syncthreads();
     nk = s_nk;
     const float* bf = boxes + (size_t)f * cap * 4;
