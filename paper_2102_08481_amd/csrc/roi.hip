@@ -240,10 +240,189 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
     if (t == 0 && out_n) out_n[f] = nk;
 }
 
+// Same selection with one wavefront per foreground class (post <= 512, Kc - 1 <= 16, D <= 128).  Same-class NMS
+// never looks across classes and the global walk stops after D kept boxes, so the result equals: per class, greedy
+// NMS over that class's candidates in key order, cut after its first D kept; then the D largest keys among all
+// kept.  Every wavefront gathers and sorts its class's candidates in LDS (wave-level barriers only), resolves 64
+// candidates at a time (overlap bits against the earlier candidates of the group, then a register-only greedy
+// chain), and the block finally ranks the <= (Kc - 1) * D kept keys by counting.
+constexpr int SELC_MAX_POST = 512, SELC_MAX_CLASSES = 16, SELC_MAX_D = 128;
+
+// n2 = 64 * 2^k <= 512 keys in LDS, sorted descending by one wavefront.  Every lane owns n2 / 128 compare-exchange
+// pairs per pass; all of a pass's keys are read before any is written back, so the LDS latency is paid once per pass.
+__device__ inline void wave_bitonic_sort_desc(uint64_t* keys, int n2, int lane) {
+    const int pairs = n2 >> 7;   // per lane: 1, 2 or 4 (n2 / 2 pairs over 64 lanes); n2 = 64 handled as one half-filled pass
+    for (int k = 2; k <= n2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            uint64_t a[4], b[4];
+            int ia[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int q = lane + 64 * r;                       // pair index
+                ia[r] = ((q & ~(j - 1)) << 1) | (q & (j - 1));      // lower element of the pair; its partner is ia | j
+                if (r < pairs || (pairs == 0 && r == 0 && q < (n2 >> 1))) { a[r] = keys[ia[r]]; b[r] = keys[ia[r] | j]; }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int q = lane + 64 * r;
+                if (r < pairs || (pairs == 0 && r == 0 && q < (n2 >> 1))) {
+                    const bool desc = (ia[r] & k) == 0;
+                    if (desc ? (a[r] < b[r]) : (a[r] > b[r])) { keys[ia[r]] = b[r]; keys[ia[r] | j] = a[r]; }
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0); the array is private to this wavefront
+            __builtin_amdgcn_wave_barrier();
+        }
+}
+
+__global__ __launch_bounds__(1024) void select_classes_kernel(const float* __restrict__ scores, const float* __restrict__ boxes,
+                                                              const int32_t* __restrict__ roi_n, int post, int Kc,
+                                                              float score_thr, float nms_thr, int D,
+                                                              float* __restrict__ out_boxes, float* __restrict__ out_scores,
+                                                              int32_t* __restrict__ out_labels, int32_t* __restrict__ out_n) {
+    extern __shared__ __align__(16) unsigned char sel_smem[];
+    const int NC = Kc - 1;
+    uint64_t* keys = reinterpret_cast<uint64_t*>(sel_smem);              // [NC][SELC_MAX_POST]
+    uint64_t* kkey = keys + (size_t)NC * SELC_MAX_POST;                  // [NC][D]
+    Box* kbox = reinterpret_cast<Box*>(kkey + (size_t)NC * D);           // [NC][D]
+    int* kcount = reinterpret_cast<int*>(kbox + (size_t)NC * D);         // [NC]
+    const int f = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    int nr = roi_n[f];
+    nr = nr < post ? nr : post;
+    const float* sc = scores + (size_t)f * post * Kc;
+    const float* bx = boxes + (size_t)f * post * Kc * 4;
+
+    if (wv < NC) {
+        const int c = wv;                       // label c + 1
+        uint64_t* ck = keys + (size_t)c * SELC_MAX_POST;
+        int n2 = 64;
+        while (n2 < nr) n2 <<= 1;
+        int nc = 0;
+        for (int r0 = 0; r0 < n2; r0 += 64) {
+            const int roi = r0 + lane;
+            uint64_t key = 0ull;
+            if (roi < nr) {
+                const int j = roi * Kc + c + 1;
+                const float s = sc[j];
+                if (s > score_thr) {
+                    const float4 b = *reinterpret_cast<const float4*>(bx + 4 * (size_t)j);
+                    if ((b.z - b.x >= 1e-3f) && (b.w - b.y >= 1e-3f)) key = ((uint64_t)score_key(s) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)j);
+                }
+            }
+            ck[roi] = key;
+            nc += __popcll(__ballot(key != 0ull));
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_wave_barrier();
+        wave_bitonic_sort_desc(ck, n2, lane);   // valid keys are non-zero and sort before the zero padding
+        int nk = 0;
+        for (int s0 = 0; s0 < nc && nk < D; s0 += 64) {
+            const int i = s0 + lane;
+            bool alive = i < nc;
+            Box me = {0.f, 0.f, 0.f, 0.f};
+            uint64_t key = 0ull;
+            if (alive) {
+                key = ck[i];
+                const uint32_t j = 0xFFFFFFFFu - (uint32_t)(key & 0xFFFFFFFFull);
+                const float4 b = *reinterpret_cast<const float4*>(bx + 4 * (size_t)j);
+                me = {b.x, b.y, b.z, b.w};
+            }
+            {   // against the boxes this class has kept so far: four at a time, no early exit (the loads pipeline)
+                bool hit = false;
+                const Box* kb = kbox + (size_t)c * D;
+                int q = 0;
+                for (; q + 4 <= nk; q += 4) {
+                    const Box b0 = kb[q], b1 = kb[q + 1], b2 = kb[q + 2], b3 = kb[q + 3];
+                    const int h = (int)iou_over(b0, me, nms_thr) | (int)iou_over(b1, me, nms_thr) | (int)iou_over(b2, me, nms_thr) | (int)iou_over(b3, me, nms_thr);
+                    hit = hit || h != 0;
+                }
+                for (; q < nk; ++q) hit = hit || iou_over(kb[q], me, nms_thr);
+                alive = alive && !hit;
+            }
+            // column b of the group's overlap matrix (which later candidates candidate b suppresses), held by lane b
+            uint64_t col = 0ull;
+            const int live = (nc - s0) < 64 ? (nc - s0) : 64;   // candidates in this group
+            for (int b = 0; b < live; ++b) {   // b is wavefront-uniform: the box is broadcast through scalar registers
+                const Box kb = {__uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(me.x1), b)),
+                                __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(me.y1), b)),
+                                __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(me.x2), b)),
+                                __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(me.y2), b))};
+                const uint64_t m = __ballot(lane > b && i < nc && iou_over(kb, me, nms_thr));
+                if (lane == b) col = m;
+            }
+            uint64_t dead = ~__ballot(alive);
+            uint64_t kept = 0ull;
+            const uint32_t clo = (uint32_t)col, chi = (uint32_t)(col >> 32);
+            for (int b = 0; b < 64; ++b) {
+                if ((dead >> b) & 1ull) continue;
+                kept |= 1ull << b;
+                dead |= (uint64_t)(uint32_t)__builtin_amdgcn_readlane(clo, b) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(chi, b) << 32);
+            }
+            if ((kept >> lane) & 1ull) {
+                const int pos = nk + __popcll(kept & ((1ull << lane) - 1ull));
+                if (pos < D) { kbox[(size_t)c * D + pos] = me; kkey[(size_t)c * D + pos] = key; }
+            }
+            nk += __popcll(kept);
+            nk = nk < D ? nk : D;
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (lane == 0) kcount[c] = nk;
+    }
+    __syncthreads();
+    // rank of every kept key among all kept keys (each class list is sorted descending: binary search per class)
+    int total = 0;
+    for (int c = 0; c < NC; ++c) total += kcount[c];
+    const int nk_out = total < D ? total : D;
+    for (int e = t; e < NC * D; e += 1024) {
+        const int c = e / D, q = e - c * D;
+        if (q >= kcount[c]) continue;
+        const uint64_t key = kkey[(size_t)c * D + q];
+        int rank = 0;
+        for (int c2 = 0; c2 < NC; ++c2) {
+            const uint64_t* l = kkey + (size_t)c2 * D;
+            int lo = 0, hi = kcount[c2];          // first position whose key is <= key
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (l[mid] > key) lo = mid + 1; else hi = mid;
+            }
+            rank += lo;
+        }
+        if (rank < D) {
+            const Box b = kbox[(size_t)c * D + q];
+            *reinterpret_cast<float4*>(out_boxes + ((size_t)f * D + rank) * 4) = make_float4(b.x1, b.y1, b.x2, b.y2);
+            out_scores[(size_t)f * D + rank] = key_score((uint32_t)(key >> 32));
+            out_labels[(size_t)f * D + rank] = c + 1;
+        }
+    }
+    for (int d = nk_out + t; d < D; d += 1024) {
+        *reinterpret_cast<float4*>(out_boxes + ((size_t)f * D + d) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+        out_scores[(size_t)f * D + d] = 0.f;
+        out_labels[(size_t)f * D + d] = -1;
+    }
+    if (t == 0 && out_n) out_n[f] = nk_out;
+}
+
 hipError_t launch_select(const float* scores, const float* boxes, const int32_t* roi_n, int n, int post, int Kc,
                          float score_thr, float nms_thr, int D, uint64_t* keys, int key_cap, float* out_boxes,
                          float* out_scores, int32_t* out_labels, int32_t* out_n, hipStream_t s) {
     if (n <= 0 || D <= 0 || D > SEL_MAX_D || key_cap < post * Kc) return hipErrorInvalidValue;
+    if (post <= SELC_MAX_POST && Kc >= 2 && Kc - 1 <= SELC_MAX_CLASSES && D <= SELC_MAX_D) {
+        const int NC = Kc - 1;
+        const size_t lds = (size_t)NC * SELC_MAX_POST * 8 + (size_t)NC * D * (8 + sizeof(Box)) + (size_t)NC * 4;
+        static bool attr_set = false;
+        if (!attr_set) {
+            const size_t lds_max = (size_t)SELC_MAX_CLASSES * SELC_MAX_POST * 8 + (size_t)SELC_MAX_CLASSES * SELC_MAX_D * (8 + sizeof(Box)) +
+                                   (size_t)SELC_MAX_CLASSES * 4;
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_classes_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(select_classes_kernel, dim3(n), dim3(1024), lds, s, scores, boxes, roi_n, post, Kc, score_thr, nms_thr, D,
+                           out_boxes, out_scores, out_labels, out_n);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(select_kernel, dim3(n), dim3(1024), 0, s, scores, boxes, roi_n, post, Kc, score_thr, nms_thr, D, keys,
                        key_cap, out_boxes, out_scores, out_labels, out_n);
     return hipGetLastError();
