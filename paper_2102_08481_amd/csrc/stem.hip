@@ -116,7 +116,9 @@ __global__ __launch_bounds__(256, 2) void stem_pool_mfma_kernel(const uint8_t* _
     __shared__ __align__(16) unsigned char wt[64 * MW_PITCH];
     __shared__ __align__(16) unsigned char etile[4 * 32 * ME_PITCH];
     __shared__ bf16_t lut[256];
+    __shared__ __align__(16) float sbias[64];
     const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    if (t < 64) sbias[t] = bias[t];
     // Persistent blocks: weights and the normalisation table are staged once, and the raw pixels of the next
     // tile are requested (9 dwords per thread, held in registers) before the current tile is multiplied.
     lut[t] = f32_to_bf16(((float)t - mean) / stdv);
@@ -211,7 +213,7 @@ __global__ __launch_bounds__(256, 2) void stem_pool_mfma_kernel(const uint8_t* _
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const f32x4_t q = *reinterpret_cast<const f32x4_t*>(bias + i * 32 + 8 * v + 4 * g);
+                const f32x4_t q = *reinterpret_cast<const f32x4_t*>(sbias + i * 32 + 8 * v + 4 * g);   // LDS copy: no per-tile global wait
                 bias_t[i][4 * v] = q.x; bias_t[i][4 * v + 1] = q.y; bias_t[i][4 * v + 2] = q.z; bias_t[i][4 * v + 3] = q.w;
             }
         const int sx0 = 2 * cur.px0 - 1, sy0 = 2 * cur.py0 - 1;
