@@ -510,7 +510,7 @@ bool conv_supported(const ConvArgs& a, int precision) {
     const int bk = precision ? 64 : 32;
     if (a.Cin <= 0 || a.Cin % bk) return false;
     if (a.kh < 1 || a.kw < 1 || a.kh * a.kw > 32) return false;   // one validity bit per filter tap
-    if (a.N <= 0 || a.Cout <= 0 || a.Ho <= 0 || a.Wo <= 0 || a.zeros == nullptr) return false;
+    if (a.N <= 0 || a.Cout <= 0 || a.Ho <= 0 || a.Wo <= 0) return false;
     if (a.in2 != nullptr) {
         if (a.kh != 1 || a.kw != 1 || a.pad != 0 || a.Cin2 <= 0 || a.Cin2 % bk || a.stride2 < 1) return false;
         if ((a.Ho - 1) * a.stride2 >= a.H2 || (a.Wo - 1) * a.stride2 >= a.W2) return false;

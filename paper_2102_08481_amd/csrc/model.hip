@@ -72,7 +72,6 @@ struct thia_model {
     float* stem_w = nullptr;  // device fp32 [147][64] (fp32 path)
     bf16_t* stem_wk = nullptr;  // device bf16 [64][22][8] (matrix-core path)
     float* stem_b = nullptr;
-    void* zeros = nullptr;  // 256 zero bytes (padding source of the convolution loads)
     std::vector<Block> stage[4];
     ExitUnit ex[4];
     char* warena = nullptr;
@@ -332,7 +331,7 @@ struct Heads {  // RPN predictors fused into the convolution (ConvArgs::head_*)
 void fill_conv_args(const thia_model* m, ConvArgs& a, const Layer& L, const void* in, int n, int H, int W, int stride, int pad,
                     const void* res, bool relu, void* out0, void* out1, int n_split, const Second* second) {
     a = ConvArgs{};
-    a.in = in; a.w = L.w; a.bias = L.b; a.res = res; a.out0 = out0; a.out1 = out1; a.zeros = m->zeros;
+    a.in = in; a.w = L.w; a.bias = L.b; a.res = res; a.out0 = out0; a.out1 = out1;
     a.N = n; a.H = H; a.W = W; a.Cin = L.ci; a.Cout = L.co;
     if (second) {
         a.in2 = second->in; a.Cin2 = second->Cin; a.H2 = second->H; a.W2 = second->W; a.stride2 = second->stride;
@@ -584,8 +583,6 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
     for (int i = 0; i < 8; ++i) m->anc.sizes[i] = hf[13 + i];
     for (int i = 0; i < 4; ++i) m->anc.sqrt_ratios[i] = i < m->anc.n_ratios ? sqrtf(hf[21 + i]) : 1.f;
 
-    if (hipMalloc(&m->zeros, 256) != hipSuccess) return bad(THIA_E_NOMEM);
-    if (hipMemset(m->zeros, 0, 256) != hipSuccess) return bad(THIA_E_HIP);
     BlobReader r{reinterpret_cast<const float*>(static_cast<const char*>(weights) + kHeaderBytes),
                  reinterpret_cast<const float*>(static_cast<const char*>(weights) + nbytes)};
     HostLayer stem;
@@ -702,7 +699,6 @@ void thia_free_model(thia_model* m) {
     free_workspace(m);
     for (auto& t : m->taps) if (t.buf) (void)hipFree(t.buf);
     for (auto e : m->ev_pool) (void)hipEventDestroy(e);
-    if (m->zeros) (void)hipFree(m->zeros);
     if (m->stem_w) (void)hipFree(m->stem_w);
     if (m->stem_wk) (void)hipFree(m->stem_wk);
     if (m->stem_b) (void)hipFree(m->stem_b);

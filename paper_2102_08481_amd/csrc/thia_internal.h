@@ -42,7 +42,6 @@ struct ConvArgs {
     const void* res;  // may be null
     void* out0;
     void* out1;       // == nullptr unless the output is split
-    const void* zeros;  // >= 16 zero bytes on the device: source of padded / out-of-range tile chunks
     int N, H, W, Cin, Ho, Wo, Cout, kh, kw, stride, pad;
     int relu, n_split, ld0, ld1;
     // Optional second source of a 1x1 convolution: out += W[:, Cin:Cin+Cin2] * in2[pixel (oy*stride2, ox*stride2)].

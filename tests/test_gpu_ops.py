@@ -38,6 +38,8 @@ def _bf16(x):
     dict(n=1, H=9, W=11, Cin=256, Cout=75, k=1, stride=1, pad=0),        # Cout not a multiple of 4 (scalar epilogue)
     dict(n=300, H=1, W=1, Cin=1024, Cout=40, k=1, stride=1, pad=0),      # FC-shaped, narrow
     dict(n=1, H=1, W=1, Cin=64, Cout=64, k=1, stride=1, pad=0),          # single row
+    dict(n=2, H=11, W=9, Cin=128, Cout=128, k=1, stride=1, pad=0),       # two K steps
+    dict(n=2, H=11, W=9, Cin=192, Cout=256, k=1, stride=1, pad=0),       # three K steps (odd count)
     dict(n=2, H=161, W=159, Cin=64, Cout=256, k=3, stride=1, pad=1),     # 256x256 tile kernel, ragged M, 3x3 borders
     dict(n=2, H=161, W=160, Cin=512, Cout=512, k=1, stride=1, pad=0),    # 256x256 tile kernel, two N tiles
     dict(n=400, H=1, W=1, Cin=8192, Cout=256, k=1, stride=1, pad=0),     # very long K, few tiles: 192-pixel tile kernel, ragged M
