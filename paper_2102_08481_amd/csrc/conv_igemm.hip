@@ -341,7 +341,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
                     }
             // predictor weight fragments (3 channel tiles per k-step) run HRING k-steps ahead of their use; the first
             // ones and the bias tile are requested once the accumulators are parked, in flight across the barrier
-            constexpr int HRING = 4;
+            constexpr int HRING = 4;   // (8 spills and is slower)
             __builtin_amdgcn_sched_barrier(0);   // (hoisted above the parking loop they would spill)
             u32x4_t hw[HRING * 3];
 #pragma unroll
