@@ -2,7 +2,8 @@
 32-frame batch of synthetic 540x960 traffic frames, swept over exits EP1..EP4.
 
 One "step" = thia_detect_chunk on the resident batch at EP1, EP2, EP3 and EP4 (the whole
-hot path at every exit; 4 x 32 frame inferences).  Prints ONE JSON line.
+hot path at every exit; 4 x 32 frame inferences).  Prints ONE JSON line with the metric, the
+roofline of the dominant kernel class and the CPU oracle's rate on a bounded sample.
 """
 import argparse
 import json
@@ -92,7 +93,7 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true", help="append one 256 MiB device copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (frames are independent; see DESIGN.md for sharding); use --gpus 1",
+        print("bench.py: this build measures one GPU only (frames are independent, so more GPUs would each take a share of the chunk); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 
