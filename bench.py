@@ -88,6 +88,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--skip-all-exits", action="store_true", help="leave out the all-exits-in-one-pass timing (for profiler runs)")
     ap.add_argument("--skip-cpu-baseline", action="store_true", help="leave out the oracle timing (for profiler runs)")
     ap.add_argument("--microbatch", type=int, default=0)
     ap.add_argument("--pmc-calibration", action="store_true", help="append one 256 MiB device copy (counter calibration)")
@@ -148,6 +149,20 @@ def main():
     prof = model.profile_read()
     model.profile_end()
 
+    # ---- beside the metric: the same batch with every exit evaluated in ONE backbone pass (what the planner's
+    # exit selection needs on its sampled frames); the sweep above pays for the shared stages once per exit
+    all_exits_ms = None
+    if not args.skip_all_exits:
+        out_all = model.detect_all_exits(frames)
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        ea.record(stream)
+        for k in range(args.steps):
+            model.detect_all_exits(frames, out_all)
+        eb.record(stream)
+        torch.cuda.synchronize()
+        all_exits_ms = ea.elapsed_time(eb) / args.steps
+
     if args.pmc_calibration:
         # a plain copy of known size, so that a `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE` run of this command can
         # scale the counters: 256 MiB read + 256 MiB written by one elementwise kernel
@@ -197,6 +212,9 @@ def main():
         "roofline": roofline,
     }
 
+    if all_exits_ms is not None:
+        result["all_exits_one_pass"] = {"ms_per_batch": all_exits_ms, "frames_per_s": B / (all_exits_ms * 1e-3),
+                                        "vs_sweep": ms_per_step / all_exits_ms}
     if not args.skip_cpu_baseline:
         import oracle
         orc = oracle.Model(blob)

@@ -107,6 +107,21 @@ int thia_detect_chunk(thia_model* m, const uint8_t* frames, int n, int H, int W,
                       float* out_boxes, float* out_scores, int32_t* out_labels);
 
 /*
+ * Run every exit on the same frames in one pass (Sec. 5.2, evaluation-based exit
+ * selection: the planner scores all exits on each sampled frame against the reference
+ * exit; Sec. 6.9: exits share parameters and the features already computed).  The
+ * backbone runs once to the last stage and exit e's units read stage e's tensor on the
+ * way, so exit e's result is bit-identical to thia_detect_chunk(..., ep = e) while the
+ * earlier stages are evaluated once instead of once per exit.
+ * frames: dev uint8 [n,3,H,W].  Outputs: dev, exit-major: out_boxes float32
+ * [n_exits,n,D,4], out_scores float32 [n_exits,n,D], out_labels int32 [n_exits,n,D],
+ * each exit's block laid out as thia_detect_chunk's.  Debug taps are not recorded.
+ * Errors and workspace behaviour as for thia_detect_chunk.
+ */
+int thia_detect_all_exits(thia_model* m, const uint8_t* frames, int n, int H, int W,
+                          float* out_boxes, float* out_scores, int32_t* out_labels);
+
+/*
  * Run a fine-grained plan (Sec. 3; Algorithm 1's output): frames dev uint8
  * [n_chunks*chunk_len,3,H,W]; chunk c = frames [c*chunk_len, (c+1)*chunk_len) runs at
  * exit chunk_ep[c] (host int32 [n_chunks], 0 = skip).  Chunks are grouped by exit and

@@ -60,6 +60,8 @@ def lib():
         L.orc_detect.restype = C.c_int
         L.orc_detect.argtypes = [C.c_void_p, _u8p] + [C.c_int] * 4 + [_f32p, _f32p, _i32p, C.c_void_p]
         L.orc_run_plan.restype = C.c_int
+        L.orc_detect_all_exits.restype = C.c_int
+        L.orc_detect_all_exits.argtypes = [C.c_void_p, _u8p] + [C.c_int] * 3 + [_f32p, _f32p, _i32p]
         L.orc_run_plan.argtypes = [C.c_void_p, _u8p] + [C.c_int] * 4 + [_i32p, _f32p, _f32p, _i32p]
         L.orc_num_threads.restype = C.c_int
         L.free.argtypes = [C.c_void_p]
@@ -256,6 +258,17 @@ class Model:
             raise ValueError("oracle: bad arguments")
         bufs.update(boxes=boxes, scores=scores, labels=labels)
         return bufs
+
+    def detect_all_exits(self, frames):
+        f = _c(frames, np.uint8)
+        n, _, H, W = f.shape
+        E, D = self.n_exits, self.D
+        boxes, scores = np.zeros((E, n, D, 4), np.float32), np.zeros((E, n, D), np.float32)
+        labels = np.full((E, n, D), -1, np.int32)
+        rc = lib().orc_detect_all_exits(self._h, f, n, H, W, boxes, scores, labels)
+        if rc:
+            raise ValueError("oracle: bad arguments")
+        return dict(boxes=boxes, scores=scores, labels=labels)
 
     def run_plan(self, frames, chunk_len, chunk_ep):
         f = _c(frames, np.uint8)

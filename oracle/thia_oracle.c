@@ -673,6 +673,23 @@ int orc_detect(const orc_model *m, const uint8_t *frames, int n, int H, int W, i
 }
 
 /*
+ * Every exit on the same frames (Sec. 5.2, evaluation-based exit selection: all
+ * exits are evaluated on each sampled frame).  By definition this is one
+ * orc_detect per exit; outputs are exit-major, [n_exits][n][D]...
+ */
+int orc_detect_all_exits(const orc_model *m, const uint8_t *frames, int n, int H, int W, float *out_boxes,
+                         float *out_scores, int32_t *out_labels) {
+    if (!m || n < 0) return -1;
+    const size_t D = m->max_det;
+    for (int ep = 1; ep <= m->n_exits; ++ep) {
+        size_t o = (size_t)(ep - 1) * n;
+        int rc = orc_detect(m, frames, n, H, W, ep, out_boxes + o * D * 4, out_scores + o * D, out_labels + o * D, NULL);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+/*
  * Plan execution: frames [n_chunks*chunk_len,3,H,W]; chunk c runs at exit
  * chunk_ep[c] (0 = skip).  Each chunk is exactly one orc_detect call.
  */

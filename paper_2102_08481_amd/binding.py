@@ -23,7 +23,7 @@ _TAP_ELEM = {"feat": "T", "head_feat": "T", "roi_feat": "T", "topk_idx": "i", "p
 KERNEL_CLASSES = ["stem", "pool", "conv", "fc", "topk", "nms", "roialign", "post"]
 
 EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_microbatch", "thia_get_info",
-           "thia_detect_chunk", "thia_run_plan", "thia_last_error", "thia_set_debug", "thia_debug_tap",
+           "thia_detect_chunk", "thia_detect_all_exits", "thia_run_plan", "thia_last_error", "thia_set_debug", "thia_debug_tap",
            "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
            "thia_op_rpn_proposals", "thia_op_nms", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
            "thia_op_stem", "thia_op_bottleneck", "thia_set_fusion"]
@@ -61,6 +61,7 @@ def lib():
     L.thia_set_microbatch.argtypes = [vp, i32]
     L.thia_get_info.argtypes = [vp, C.POINTER(ThiaInfo)]
     L.thia_detect_chunk.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
+    L.thia_detect_all_exits.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
     L.thia_run_plan.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
     L.thia_last_error.argtypes = [vp]
     L.thia_last_error.restype = C.c_char_p
@@ -110,6 +111,7 @@ class Model:
         self.info = ThiaInfo()
         self._check(lib().thia_get_info(self._h, C.byref(self.info)))
         self.precision = self.info.precision
+        self.n_exits = self.info.n_exits
         self.elem = torch.bfloat16 if self.precision else torch.float32
         self.D = self.info.max_det
         self.set_stream(torch.cuda.current_stream(self.device))
@@ -154,6 +156,17 @@ class Model:
         assert c == 3
         out = out or self.alloc_outputs(n)
         self._check(lib().thia_detect_chunk(self._h, _ptr(frames), n, H, W, ep, _ptr(out[0]), _ptr(out[1]), _ptr(out[2])))
+        return out
+
+    def detect_all_exits(self, frames, out=None):
+        """frames: cuda uint8 [n,3,H,W]; returns (boxes [E,n,D,4], scores [E,n,D], labels [E,n,D]), E = n_exits."""
+        _dev(frames, torch.uint8)
+        n, c, H, W = frames.shape
+        assert c == 3
+        if out is None:
+            b, s, l = self.alloc_outputs(self.n_exits * n)
+            out = (b.view(self.n_exits, n, self.D, 4), s.view(self.n_exits, n, self.D), l.view(self.n_exits, n, self.D))
+        self._check(lib().thia_detect_all_exits(self._h, _ptr(frames), n, H, W, _ptr(out[0]), _ptr(out[1]), _ptr(out[2])))
         return out
 
     def run_plan(self, frames, chunk_len, chunk_ep, out=None):

@@ -377,11 +377,17 @@ int tap_copy(thia_model* m, int which, int f0, int nb, const void* src) {
         if (rc__ != THIA_OK) return rc__; \
     } while (0)
 
-// Backbone truncated at exit ep for nb frames; returns the exit-stage tensor (NHWC) in *feat.
-int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int ep, const void** feat) {
+// State of one backbone pass over nb frames: x holds the newest stage tensor (NHWC, h x w), y is the spare buffer.
+struct Trunk {
+    void *x = nullptr, *y = nullptr;
+    int h = 0, w = 0;
+};
+
+// Normalisation, stem and max-pool.
+int run_stem(thia_model* m, const uint8_t* frames, int nb, int H, int W, Trunk& t) {
     Workspace& ws = m->ws;
     const int Hs = conv_out(H, 7, 2, 3), Ws = conv_out(W, 7, 2, 3);
-    int h = conv_out(Hs, 3, 2, 1), w = conv_out(Ws, 3, 2, 1);
+    t.h = conv_out(Hs, 3, 2, 1); t.w = conv_out(Ws, 3, 2, 1);
     if (m->precision == 1) {
         Scope sc(m, THIA_K_STEM);
         HIP_TRY(m, launch_stem_pool(frames, nb, H, W, m->stem_wk, m->stem_b, m->mean, m->stdv, ws.act[0], m->stream));
@@ -393,36 +399,51 @@ int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int
         Scope sc(m, THIA_K_POOL);
         HIP_TRY(m, launch_maxpool(ws.act[2], nb, Hs, Ws, m->stem_ch, m->precision, ws.act[0], m->stream));
     }
-    void *x = ws.act[0], *y = ws.act[1];
-    for (int s = 0; s < ep; ++s)
-        for (const Block& B : m->stage[s]) {
-            const int ho = conv_out(h, 3, B.stride, 1), wo = conv_out(w, 3, B.stride, 1);
-            if (B.f1 && m->fuse_blocks) {
-                FusedBlockArgs fa{};
-                fa.x = static_cast<const bf16_t*>(x); fa.y = static_cast<bf16_t*>(y);
-                fa.w1f = B.f1; fa.w2f = B.f2; fa.w3f = B.f3; fa.b1 = B.c1.b; fa.b2 = B.c2.b; fa.b3 = B.c3.b;
-                fa.N = nb; fa.H = h; fa.W = w; fa.first = B.has_sc ? 1 : 0;
-                if (B.stride == 1 && fused_block_supported(fa, B.c1.co)) {
-                    Scope sc(m, THIA_K_CONV);
-                    HIP_TRY(m, launch_fused_block(fa, B.c1.co, m->stream));
-                    std::swap(x, y);
-                    continue;
-                }
+    t.x = ws.act[0]; t.y = ws.act[1];
+    return THIA_OK;
+}
+
+// Bottleneck stage s (0-based) applied to t.x; the stage's output becomes t.x.
+int run_stage(thia_model* m, int s, int nb, Trunk& t) {
+    Workspace& ws = m->ws;
+    void *&x = t.x, *&y = t.y;
+    int &h = t.h, &w = t.w;
+    for (const Block& B : m->stage[s]) {
+        const int ho = conv_out(h, 3, B.stride, 1), wo = conv_out(w, 3, B.stride, 1);
+        if (B.f1 && m->fuse_blocks) {
+            FusedBlockArgs fa{};
+            fa.x = static_cast<const bf16_t*>(x); fa.y = static_cast<bf16_t*>(y);
+            fa.w1f = B.f1; fa.w2f = B.f2; fa.w3f = B.f3; fa.b1 = B.c1.b; fa.b2 = B.c2.b; fa.b3 = B.c3.b;
+            fa.N = nb; fa.H = h; fa.W = w; fa.first = B.has_sc ? 1 : 0;
+            if (B.stride == 1 && fused_block_supported(fa, B.c1.co)) {
+                Scope sc(m, THIA_K_CONV);
+                HIP_TRY(m, launch_fused_block(fa, B.c1.co, m->stream));
+                std::swap(x, y);
+                continue;
             }
-            TRY(run_conv(m, THIA_K_CONV, B.c1, x, nb, h, w, 1, 0, nullptr, true, false, ws.act[2]));
-            TRY(run_conv(m, THIA_K_CONV, B.c2, ws.act[2], nb, h, w, B.stride, 1, nullptr, true, false, ws.act[3]));
-            if (B.has_sc) {
-                // last 1x1 and projection shortcut share one accumulator: y = relu(W3 t2 + Ws x(strided) + b3 + bs)
-                Second sec;
-                sec.in = x; sec.Cin = B.sc_ci; sec.H = h; sec.W = w; sec.stride = B.stride;
-                TRY(run_conv(m, THIA_K_CONV, B.c3, ws.act[3], nb, ho, wo, 1, 0, nullptr, true, false, y, nullptr, -1, &sec));
-            } else {
-                TRY(run_conv(m, THIA_K_CONV, B.c3, ws.act[3], nb, ho, wo, 1, 0, x, true, false, y));
-            }
-            std::swap(x, y);
-            h = ho; w = wo;
         }
-    *feat = x;
+        TRY(run_conv(m, THIA_K_CONV, B.c1, x, nb, h, w, 1, 0, nullptr, true, false, ws.act[2]));
+        TRY(run_conv(m, THIA_K_CONV, B.c2, ws.act[2], nb, h, w, B.stride, 1, nullptr, true, false, ws.act[3]));
+        if (B.has_sc) {
+            // last 1x1 and projection shortcut share one accumulator: y = relu(W3 t2 + Ws x(strided) + b3 + bs)
+            Second sec;
+            sec.in = x; sec.Cin = B.sc_ci; sec.H = h; sec.W = w; sec.stride = B.stride;
+            TRY(run_conv(m, THIA_K_CONV, B.c3, ws.act[3], nb, ho, wo, 1, 0, nullptr, true, false, y, nullptr, -1, &sec));
+        } else {
+            TRY(run_conv(m, THIA_K_CONV, B.c3, ws.act[3], nb, ho, wo, 1, 0, x, true, false, y));
+        }
+        std::swap(x, y);
+        h = ho; w = wo;
+    }
+    return THIA_OK;
+}
+
+// Backbone truncated at exit ep for nb frames; returns the exit-stage tensor (NHWC) in *feat.
+int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int ep, const void** feat) {
+    Trunk t;
+    TRY(run_stem(m, frames, nb, H, W, t));
+    for (int s = 0; s < ep; ++s) TRY(run_stage(m, s, nb, t));
+    *feat = t.x;
     return THIA_OK;
 }
 
@@ -545,6 +566,29 @@ int detect_frames(thia_model* m, const uint8_t* frames, int n, int H, int W, int
         TRY(run_heads(m, feat, f0, nb, H, W, ep, ob + (size_t)f0 * D * 4, os + (size_t)f0 * D, ol + (size_t)f0 * D));
     }
     return THIA_OK;
+}
+
+// n frames through the whole backbone once, every exit's heads applied to its own stage tensor on the way.
+// Outputs are exit-major: exit e (1-based) fills the block at (e - 1) * n frames.
+int detect_frames_all_exits(thia_model* m, const uint8_t* frames, int n, int H, int W, float* ob, float* os, int32_t* ol) {
+    TRY(ensure_workspace(m, H, W));
+    const int mb = m->ws.mb, D = m->D;
+    const bool debug = m->debug;
+    m->debug = false;  // the taps describe one exit; this call records none
+    int rc = THIA_OK;
+    for (int f0 = 0; f0 < n && rc == THIA_OK; f0 += mb) {
+        const int nb = std::min(mb, n - f0);
+        Trunk t;
+        rc = run_stem(m, frames + (size_t)f0 * 3 * H * W, nb, H, W, t);
+        for (int s = 0; s < m->n_exits && rc == THIA_OK; ++s) {
+            rc = run_stage(m, s, nb, t);
+            if (rc != THIA_OK) break;
+            const size_t o = (size_t)s * n + f0;
+            rc = run_heads(m, t.x, f0, nb, H, W, s + 1, ob + o * D * 4, os + o * D, ol + o * D);
+        }
+    }
+    m->debug = debug;
+    return rc;
 }
 
 }  // namespace
@@ -754,6 +798,14 @@ int thia_detect_chunk(thia_model* m, const uint8_t* frames, int n, int H, int W,
         return THIA_OK;
     }
     return detect_frames(m, frames, n, H, W, ep, out_boxes, out_scores, out_labels);
+}
+
+int thia_detect_all_exits(thia_model* m, const uint8_t* frames, int n, int H, int W, float* out_boxes, float* out_scores,
+                          int32_t* out_labels) {
+    int rc = check_frame_args(m, frames, n, H, W, out_boxes, out_scores, out_labels);
+    if (rc != THIA_OK) return rc;
+    if (n == 0) return THIA_OK;
+    return detect_frames_all_exits(m, frames, n, H, W, out_boxes, out_scores, out_labels);
 }
 
 int thia_run_plan(thia_model* m, const uint8_t* frames, int n_chunks, int chunk_len, int H, int W, const int32_t* chunk_ep,

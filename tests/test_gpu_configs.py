@@ -125,6 +125,19 @@ def test_config4_plan_256_frames_bit_identical_to_chunks():
     assert torch.equal(qb[:32], pb[:32]) and torch.equal(qb[64:], pb[64:])
 
 
+def test_config3_all_exits_in_one_pass_bit_identical_to_the_sweep():
+    cfg = CONFIGS[3]
+    m, _ = gpu_model(cfg.model, cfg.weight_seed)
+    fd = to_dev(_frames(cfg))
+    ab, as_, al = m.detect_all_exits(fd)
+    torch.cuda.synchronize()
+    for ep in range(1, 5):
+        b, s, l = m.detect_chunk(fd, ep)
+        torch.cuda.synchronize()
+        assert torch.equal(ab[ep - 1], b) and torch.equal(as_[ep - 1], s) and torch.equal(al[ep - 1], l), f"EP{ep}"
+        assert _properties(cfg, ab[ep - 1], as_[ep - 1], al[ep - 1], 540, 960) > 0
+
+
 @pytest.mark.parametrize("ep", [1, 2, 3, 4])
 def test_config5_r101_1080p_batch8(ep):
     cfg = CONFIGS[5]

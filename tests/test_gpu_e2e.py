@@ -171,6 +171,34 @@ def test_plan_is_bit_identical_to_per_chunk_calls_and_skip_is_empty():
     assert (pl[:L, 0] >= 1).all()
 
 
+def test_all_exits_in_one_pass_matches_each_exit_and_the_oracle():
+    """One backbone pass with every exit's units tapped on the way: each exit's block is bit-identical to a
+    call at that exit (also across micro-batch sizes), and it matches the oracle's all-exits result."""
+    m, blob = gpu_model(MINI_FP32, 0xBEEF + 50)
+    fh = make_frames(SceneSpec(200, 264, 5, 4, 10, 10, 90), 47)
+    fd = to_dev(fh)
+    ab, as_, al = m.detect_all_exits(fd)
+    torch.cuda.synchronize()
+    assert ab.shape == (4, 5, m.D, 4) and as_.shape == (4, 5, m.D) and al.shape == (4, 5, m.D)
+    for ep in range(1, 5):
+        b, s, l = m.detect_chunk(fd, ep)
+        torch.cuda.synchronize()
+        assert torch.equal(ab[ep - 1], b) and torch.equal(as_[ep - 1], s) and torch.equal(al[ep - 1], l), f"EP{ep}"
+    for mb in (1, 2):
+        m.set_microbatch(mb)
+        b2, s2, l2 = m.detect_all_exits(fd)
+        torch.cuda.synchronize()
+        assert torch.equal(ab, b2) and torch.equal(as_, s2) and torch.equal(al, l2)
+    m.set_microbatch(0)
+    ref = oracle.Model(blob).detect_all_exits(fh)
+    for ep in range(1, 5):
+        r = {k: v[ep - 1] for k, v in ref.items()}
+        _check_detections(ab[ep - 1].cpu().numpy(), as_[ep - 1].cpu().numpy(), al[ep - 1].cpu().numpy(), r)
+    # n = 0 is a no-op
+    e = m.detect_all_exits(fd[:0])
+    assert e[0].shape == (4, 0, m.D, 4)
+
+
 def test_argument_errors_return_codes():
     from paper_2102_08481_amd import lib, ThiaError, thia_load_model
     m, blob = gpu_model(MINI_BF16, 0xBEEF + 51)

@@ -165,6 +165,27 @@ def test_early_stop_never_touches_later_stages_or_other_exits(mini):
     assert (a["labels"] >= 0).any()
 
 
+def test_all_exits_result_is_each_exit_alone_in_exit_major_order(mini):
+    """Evaluation-based exit selection (Sec. 5.2) looks at every exit on the same sampled frames: block e
+    of the all-exits result is exit e's own result, and it survives poisoning everything exit e never reads."""
+    blob, frames = mini
+    allx = oracle.Model(blob).detect_all_exits(frames)
+    assert allx["labels"].shape[:2] == (4, frames.shape[0])
+    for ep in (1, 2, 3, 4):
+        one = oracle.Model(blob).detect(frames, ep)
+        for key in ("boxes", "scores", "labels"):
+            assert np.array_equal(allx[key][ep - 1], one[key])
+    b2 = blob.copy()
+    w2 = split_blob(MINI, b2)
+    for name in w2:
+        if name.startswith(("s4.", "e4.")):
+            w2[name][...] = np.nan
+    poisoned = oracle.Model(b2).detect_all_exits(frames)
+    for key in ("boxes", "scores", "labels"):
+        assert np.array_equal(poisoned[key][:3], allx[key][:3])
+    assert (allx["labels"][:, :, 0] >= 1).all()
+
+
 def test_plan_equals_per_chunk_calls_and_skip_is_empty(mini):
     """A plan is a list of chunks each with an exit or 'skip' (Sec. 3, execution engine)."""
     blob, _ = mini
