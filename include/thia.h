@@ -132,6 +132,85 @@ int thia_detect_all_exits(thia_model* m, const uint8_t* frames, int n, int H, in
 int thia_run_plan(thia_model* m, const uint8_t* frames, int n_chunks, int chunk_len, int H, int W,
                   const int32_t* chunk_ep, float* out_boxes, float* out_scores, int32_t* out_labels);
 
+/*
+ * Run chunks of any length (the planner's chunks are halves of halves of the video, Sec. 5.2,
+ * so they differ in length): frames dev uint8 [n,3,H,W]; chunk c = frames
+ * [start[c], start[c]+len[c]) runs at exit ep[c] (0 = skip); start/len/ep host int32
+ * [n_chunks]; chunks must lie inside 0..n and must not overlap.  Outputs as for n frames of
+ * thia_detect_chunk; frames no chunk covers get the empty pattern.  Grouped by exit like
+ * thia_run_plan, and each chunk's slice is bit-identical to a stand-alone call on it.
+ */
+int thia_run_chunks(thia_model* m, const uint8_t* frames, int n, int H, int W, int n_chunks, const int32_t* start,
+                    const int32_t* len, const int32_t* ep, float* out_boxes, float* out_scores, int32_t* out_labels);
+
+/* ---------------------------------------------------------------- query planning
+ * Fine-grained planning (Sec. 5.2, Algorithm 1): the video is sampled sparsely, every exit
+ * is evaluated on the samples and compared with the last exit (the reference), and a chunk
+ * either gets the fastest exit that is accurate enough, is skipped, or is halved and sampled
+ * twice as densely.  The query is Table 2's: frames with Count(class) >= t.
+ */
+typedef struct thia_query {
+    int32_t label;     /* class to count (1..n_classes-1)                                   */
+    int32_t min_count; /* t: the frame is positive when at least t objects are found        */
+    float min_score;   /* detections below this confidence are not counted                  */
+} thia_query;
+
+typedef struct thia_planner_cfg {
+    double precision, recall; /* P, R an exit must reach on the samples (0.8, 0.8)            */
+    int32_t min_chunk;        /* no chunk is shorter than this many frames (100)              */
+    int32_t final_span;       /* 1 / final sampling rate: the deepest level samples every     */
+                              /* final_span-th frame (rate 0.1 -> 10); level 0 samples every  */
+                              /* final_span * 2^ceil(log2(n / min_chunk))-th (the rate bound)  */
+    double posi_enough;       /* ratio of positive samples from which a chunk is settled at   */
+                              /* the fastest exit                                             */
+    double posi_skip;         /* ratio of positive samples up to which a chunk is skipped     */
+    int32_t reuse_dist;       /* a memoised frame of the same chunk within this many frames   */
+                              /* stands in for a sample (0 = exact reuse only)                */
+    int32_t eval_batch;       /* frames evaluated per device batch (0 = all of a level)       */
+} thia_planner_cfg;
+
+typedef struct thia_plan_stats {
+    int32_t n_chunks;         /* chunks of the plan (also set when the capacity is too small) */
+    int32_t frames_evaluated; /* frames on which every exit was run                           */
+    int32_t samples_reused;   /* samples answered from memoised frames                        */
+    int32_t depth;            /* deepest level reached (0 = the whole video)                  */
+    int32_t eval_batches;     /* device batches issued                                        */
+} thia_plan_stats;
+
+/* The paper's constants (P = R = 0.8, chunks of at least 100 frames, final rate 0.1) and this
+ * library's choices where it names none (posi_enough 0.1, posi_skip 0, reuse_dist 0, eval_batch 32). */
+void thia_planner_defaults(thia_planner_cfg* cfg);
+
+/*
+ * Count(class) >= t on detection slots: labels dev int32 [rows,D], scores dev float32 [rows,D]
+ * (any number of frames, e.g. all exits' outputs at once), flags dev uint8 [rows] (1 = positive).
+ */
+int thia_eval_predicate(thia_model* m, const int32_t* labels, const float* scores, int rows, const thia_query* q,
+                        uint8_t* flags);
+
+/*
+ * The planner on a table of answers (host only, touches no device): flags host uint8
+ * [n,n_exits], flags[f*n_exits+e] = exit e+1's answer on frame f (only sampled rows are read;
+ * the last exit is the reference).  Writes the plan in frame order to start/len/ep (host int32,
+ * capacity cap chunks; ep 0 = skip) and the counters to stats.  evaluated (host uint8 [n], may
+ * be NULL) marks the frames whose row was "evaluated" rather than reused.  Returns
+ * THIA_E_BADARG for a bad configuration or when cap is too small (stats->n_chunks = needed).
+ */
+int thia_plan_from_flags(const uint8_t* flags, int n, int n_exits, const thia_planner_cfg* cfg, int cap, int32_t* start,
+                         int32_t* len, int32_t* ep, thia_plan_stats* stats, uint8_t* evaluated);
+
+/*
+ * The planner on a video: frames dev uint8 [n,3,H,W].  Each level's unmemoised samples are
+ * gathered and run through every exit in one backbone pass (thia_detect_all_exits) in batches
+ * of eval_batch frames, the predicate is applied on the device, and only the per-frame answers
+ * come back to the host.  Blocks until the plan is known (it synchronises the model's stream
+ * once per batch) and allocates its staging buffers for the duration of the call.  Outputs as
+ * for thia_plan_from_flags.  Execute the plan with thia_run_chunks.
+ */
+int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, const thia_query* q,
+                    const thia_planner_cfg* cfg, int cap, int32_t* start, int32_t* len, int32_t* ep,
+                    thia_plan_stats* stats, uint8_t* evaluated);
+
 const char* thia_last_error(const thia_model* m);
 
 /* ---------------------------------------------------------------- inspection

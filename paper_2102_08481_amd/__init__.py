@@ -3,7 +3,8 @@
 
 The names below mirror the C entry points; they only marshal arguments.
 """
-from .binding import Model, ThiaError, ThiaInfo, lib, EXPORTS, TAPS, KERNEL_CLASSES, LIB_PATH
+from .binding import (Model, ThiaError, ThiaInfo, ThiaQuery, ThiaPlannerCfg, ThiaPlanStats, lib, planner_cfg, plan_from_flags,
+                      EXPORTS, TAPS, KERNEL_CLASSES, LIB_PATH)
 
 
 def thia_load_model(weights, n_exits, device="cuda:0"):
@@ -19,6 +20,26 @@ def thia_detect_chunk(model, frames, ep, out=None):
 def thia_run_plan(model, frames, chunk_len, chunk_ep, out=None):
     """frames: cuda uint8 [n_chunks*chunk_len,3,H,W]; chunk_ep: exit per chunk (0 = skip)."""
     return model.run_plan(frames, chunk_len, chunk_ep, out)
+
+
+def thia_detect_all_exits(model, frames, out=None):
+    """frames: cuda uint8 [n,3,H,W]; every exit in one backbone pass.  Returns exit-major (boxes, scores, labels)."""
+    return model.detect_all_exits(frames, out)
+
+
+def thia_run_chunks(model, frames, plan, out=None):
+    """plan: [(start, len, exit or 0 = skip), ...] over frames cuda uint8 [n,3,H,W]."""
+    return model.run_chunks(frames, plan, out)
+
+
+def thia_plan_query(model, frames, label, min_count, min_score=0.0, cfg=None):
+    """Plan for the query Count(label) >= min_count.  Returns (plan, stats, evaluated mask)."""
+    return model.plan_query(frames, label, min_count, min_score, cfg)
+
+
+def thia_plan_from_flags(flags, cfg=None):
+    """The planner on a host table of per-frame, per-exit answers [n, E]."""
+    return plan_from_flags(flags, cfg)
 
 
 def thia_free_model(model):

@@ -23,7 +23,8 @@ _TAP_ELEM = {"feat": "T", "head_feat": "T", "roi_feat": "T", "topk_idx": "i", "p
 KERNEL_CLASSES = ["stem", "pool", "conv", "fc", "topk", "nms", "roialign", "post"]
 
 EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_microbatch", "thia_get_info",
-           "thia_detect_chunk", "thia_detect_all_exits", "thia_run_plan", "thia_last_error", "thia_set_debug", "thia_debug_tap",
+           "thia_detect_chunk", "thia_detect_all_exits", "thia_run_plan", "thia_run_chunks",
+           "thia_planner_defaults", "thia_eval_predicate", "thia_plan_from_flags", "thia_plan_query", "thia_last_error", "thia_set_debug", "thia_debug_tap",
            "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
            "thia_op_rpn_proposals", "thia_op_nms", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
            "thia_op_stem", "thia_op_bottleneck", "thia_set_fusion"]
@@ -34,6 +35,20 @@ class ThiaInfo(C.Structure):
                 ("n_anchors", C.c_int32), ("pre_nms", C.c_int32), ("post_nms", C.c_int32), ("pool", C.c_int32),
                 ("fc_dim", C.c_int32), ("n_classes", C.c_int32), ("max_det", C.c_int32), ("microbatch", C.c_int32),
                 ("has_lateral", C.c_int32)]
+
+
+class ThiaQuery(C.Structure):
+    _fields_ = [("label", C.c_int32), ("min_count", C.c_int32), ("min_score", C.c_float)]
+
+
+class ThiaPlannerCfg(C.Structure):
+    _fields_ = [("precision", C.c_double), ("recall", C.c_double), ("min_chunk", C.c_int32), ("final_span", C.c_int32),
+                ("posi_enough", C.c_double), ("posi_skip", C.c_double), ("reuse_dist", C.c_int32), ("eval_batch", C.c_int32)]
+
+
+class ThiaPlanStats(C.Structure):
+    _fields_ = [("n_chunks", C.c_int32), ("frames_evaluated", C.c_int32), ("samples_reused", C.c_int32), ("depth", C.c_int32),
+                ("eval_batches", C.c_int32)]
 
 
 class ThiaError(RuntimeError):
@@ -63,6 +78,13 @@ def lib():
     L.thia_detect_chunk.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
     L.thia_detect_all_exits.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
     L.thia_run_plan.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
+    L.thia_run_chunks.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    L.thia_planner_defaults.argtypes = [C.POINTER(ThiaPlannerCfg)]
+    L.thia_planner_defaults.restype = None
+    L.thia_eval_predicate.argtypes = [vp, vp, vp, i32, C.POINTER(ThiaQuery), vp]
+    L.thia_plan_from_flags.argtypes = [vp, i32, i32, C.POINTER(ThiaPlannerCfg), i32, vp, vp, vp, C.POINTER(ThiaPlanStats), vp]
+    L.thia_plan_query.argtypes = [vp, vp, i32, i32, i32, C.POINTER(ThiaQuery), C.POINTER(ThiaPlannerCfg), i32, vp, vp, vp,
+                                  C.POINTER(ThiaPlanStats), vp]
     L.thia_last_error.argtypes = [vp]
     L.thia_last_error.restype = C.c_char_p
     L.thia_set_debug.argtypes = [vp, i32]
@@ -84,6 +106,42 @@ def lib():
         getattr(L, name)
     _lib = L
     return L
+
+
+def planner_cfg(**overrides):
+    """thia_planner_cfg with the library's defaults, fields overridden by keyword."""
+    cfg = ThiaPlannerCfg()
+    lib().thia_planner_defaults(C.byref(cfg))
+    for k, v in overrides.items():
+        if k not in dict(ThiaPlannerCfg._fields_):
+            raise KeyError(k)
+        setattr(cfg, k, v)
+    return cfg
+
+
+def _plan_buffers(n, cfg):
+    cap = max(1, 2 * (n // max(1, cfg.min_chunk)) + 2)
+    return cap, [np.zeros(cap, np.int32) for _ in range(3)], ThiaPlanStats(), np.zeros(max(n, 1), np.uint8)
+
+
+def _plan_result(bufs, stats, evaluated, n):
+    k = stats.n_chunks
+    plan = [(int(bufs[0][i]), int(bufs[1][i]), int(bufs[2][i])) for i in range(k)]
+    st = {name: int(getattr(stats, name)) for name, _ in ThiaPlanStats._fields_}
+    return plan, st, evaluated[:n].astype(bool)
+
+
+def plan_from_flags(flags, cfg=None):
+    """thia_plan_from_flags: flags [n, E] (host) -> (plan [(start, len, exit or 0)], stats dict, evaluated mask [n])."""
+    flags = np.ascontiguousarray(flags, dtype=np.uint8)
+    n, E = flags.shape
+    cfg = cfg or planner_cfg()
+    cap, bufs, stats, ev = _plan_buffers(n, cfg)
+    rc = lib().thia_plan_from_flags(flags.ctypes.data, n, E, C.byref(cfg), cap, bufs[0].ctypes.data, bufs[1].ctypes.data,
+                                    bufs[2].ctypes.data, C.byref(stats), ev.ctypes.data)
+    if rc:
+        raise ThiaError(rc, "thia_plan_from_flags")
+    return _plan_result(bufs, stats, ev, n)
 
 
 def _ptr(t):
@@ -178,6 +236,40 @@ class Model:
         self._check(lib().thia_run_plan(self._h, _ptr(frames), ce.size, chunk_len, H, W, ce.ctypes.data, _ptr(out[0]),
                                         _ptr(out[1]), _ptr(out[2])))
         return out
+
+    def run_chunks(self, frames, plan, out=None):
+        """plan: [(start, len, exit or 0 = skip), ...]; outputs as for detect_chunk on all frames."""
+        _dev(frames, torch.uint8)
+        n, c, H, W = frames.shape
+        assert c == 3
+        st, ln, ep = (np.ascontiguousarray([p[i] for p in plan], dtype=np.int32) for i in range(3))
+        out = out or self.alloc_outputs(n)
+        self._check(lib().thia_run_chunks(self._h, _ptr(frames), n, H, W, len(plan), st.ctypes.data, ln.ctypes.data, ep.ctypes.data,
+                                          _ptr(out[0]), _ptr(out[1]), _ptr(out[2])))
+        return out
+
+    def eval_predicate(self, labels, scores, label, min_count, min_score=0.0):
+        """Count(label) >= min_count per row of detection slots: labels int32 [..., D], scores float32 [..., D] -> uint8 [...]."""
+        _dev(labels, torch.int32)
+        _dev(scores, torch.float32)
+        assert labels.shape == scores.shape and labels.shape[-1] == self.D
+        rows = labels.numel() // self.D
+        flags = torch.empty(labels.shape[:-1], dtype=torch.uint8, device=self.device)
+        q = ThiaQuery(label, min_count, min_score)
+        self._check(lib().thia_eval_predicate(self._h, _ptr(labels), _ptr(scores), rows, C.byref(q), _ptr(flags)))
+        return flags
+
+    def plan_query(self, frames, label, min_count, min_score=0.0, cfg=None):
+        """thia_plan_query on resident frames -> (plan, stats dict, evaluated mask [n])."""
+        _dev(frames, torch.uint8)
+        n, c, H, W = frames.shape
+        assert c == 3
+        cfg = cfg or planner_cfg()
+        cap, bufs, stats, ev = _plan_buffers(n, cfg)
+        q = ThiaQuery(label, min_count, min_score)
+        self._check(lib().thia_plan_query(self._h, _ptr(frames), n, H, W, C.byref(q), C.byref(cfg), cap, bufs[0].ctypes.data,
+                                          bufs[1].ctypes.data, bufs[2].ctypes.data, C.byref(stats), ev.ctypes.data))
+        return _plan_result(bufs, stats, ev, n)
 
     # -- inspection
     def set_debug(self, on):

@@ -834,6 +834,141 @@ int thia_run_plan(thia_model* m, const uint8_t* frames, int n_chunks, int chunk_
     return THIA_OK;
 }
 
+int thia_run_chunks(thia_model* m, const uint8_t* frames, int n, int H, int W, int n_chunks, const int32_t* start, const int32_t* len,
+                    const int32_t* ep, float* out_boxes, float* out_scores, int32_t* out_labels) {
+    if (!m) return THIA_E_BADARG;
+    if (n_chunks < 0 || (n_chunks > 0 && (!start || !len || !ep))) return fail(m, THIA_E_BADARG, "bad chunk list");
+    TRY(check_frame_args(m, frames, n, H, W, out_boxes, out_scores, out_labels));
+    std::vector<std::pair<int, int>> spans;
+    for (int c = 0; c < n_chunks; ++c) {
+        if (ep[c] < 0 || ep[c] > m->n_exits) return fail(m, THIA_E_BADEP, "chunk list holds an exit outside 0..n_exits");
+        if (start[c] < 0 || len[c] < 0 || (long long)start[c] + len[c] > n) return fail(m, THIA_E_BADARG, "chunk outside the frames");
+        if (len[c] > 0) spans.emplace_back(start[c], start[c] + len[c]);
+    }
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+        if (spans[i].first < spans[i - 1].second) return fail(m, THIA_E_BADARG, "chunks overlap");
+    if (n == 0) return THIA_OK;
+    const int D = m->D;
+    const size_t fbytes = (size_t)3 * H * W;
+    // frames no chunk covers, and skipped chunks, get the empty pattern
+    int pos = 0;
+    for (size_t i = 0; i <= spans.size(); ++i) {
+        const int upto = i < spans.size() ? spans[i].first : n;
+        if (upto > pos)
+            HIP_TRY(m, launch_fill_empty(upto - pos, D, out_boxes + (size_t)pos * D * 4, out_scores + (size_t)pos * D,
+                                         out_labels + (size_t)pos * D, m->stream));
+        if (i < spans.size()) pos = spans[i].second;
+    }
+    for (int e = 0; e <= m->n_exits; ++e)
+        for (int c = 0; c < n_chunks; ++c) {
+            if (ep[c] != e || len[c] == 0) continue;
+            const size_t f0 = (size_t)start[c];
+            if (e == 0) {
+                HIP_TRY(m, launch_fill_empty(len[c], D, out_boxes + f0 * D * 4, out_scores + f0 * D, out_labels + f0 * D, m->stream));
+            } else {
+                TRY(detect_frames(m, frames + f0 * fbytes, len[c], H, W, e, out_boxes + f0 * D * 4, out_scores + f0 * D,
+                                  out_labels + f0 * D));
+            }
+        }
+    return THIA_OK;
+}
+
+void thia_planner_defaults(thia_planner_cfg* cfg) {
+    if (!cfg) return;
+    cfg->precision = 0.8; cfg->recall = 0.8;
+    cfg->min_chunk = 100; cfg->final_span = 10;
+    cfg->posi_enough = 0.1; cfg->posi_skip = 0.0;
+    cfg->reuse_dist = 0; cfg->eval_batch = 32;
+}
+
+int thia_eval_predicate(thia_model* m, const int32_t* labels, const float* scores, int rows, const thia_query* q, uint8_t* flags) {
+    if (!m) return THIA_E_BADARG;
+    if (rows < 0 || !q || (rows > 0 && (!labels || !scores || !flags))) return fail(m, THIA_E_BADARG, "bad predicate arguments");
+    HIP_TRY(m, launch_count_predicate(labels, scores, rows, m->D, q->label, q->min_count, q->min_score, flags, m->stream));
+    return THIA_OK;
+}
+
+namespace {
+int store_plan(const std::vector<PlanChunk>& plan, int cap, int32_t* start, int32_t* len, int32_t* ep) {
+    if ((int)plan.size() > cap) return THIA_E_BADARG;
+    for (size_t i = 0; i < plan.size(); ++i) { start[i] = plan[i].start; len[i] = plan[i].len; ep[i] = plan[i].ep; }
+    return THIA_OK;
+}
+}  // namespace
+
+int thia_plan_from_flags(const uint8_t* flags, int n, int n_exits, const thia_planner_cfg* cfg, int cap, int32_t* start, int32_t* len,
+                         int32_t* ep, thia_plan_stats* stats, uint8_t* evaluated) {
+    if (n < 0 || n_exits < 1 || !cfg || cap < 0 || !stats || (n > 0 && !flags) || (cap > 0 && (!start || !len || !ep))) return THIA_E_BADARG;
+    if (planner_cfg_error(*cfg)) return THIA_E_BADARG;
+    const int E = n_exits;
+    PlanEval eval = [&](const int* fr, int k, uint8_t* out, std::string&) {
+        for (int i = 0; i < k; ++i)
+            for (int e = 0; e < E; ++e) out[(size_t)i * E + e] = flags[(size_t)fr[i] * E + e] ? 1 : 0;
+        return (int)THIA_OK;
+    };
+    std::vector<PlanChunk> plan;
+    std::string err;
+    const int rc = plan_core(n, E, *cfg, eval, plan, *stats, evaluated, err);
+    if (rc != THIA_OK) return rc;
+    return store_plan(plan, cap, start, len, ep);
+}
+
+int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, const thia_query* q, const thia_planner_cfg* cfg,
+                    int cap, int32_t* start, int32_t* len, int32_t* ep, thia_plan_stats* stats, uint8_t* evaluated) {
+    if (!m) return THIA_E_BADARG;
+    if (n < 0 || !q || !cfg || cap < 0 || !stats || (n > 0 && !frames) || (cap > 0 && (!start || !len || !ep)))
+        return fail(m, THIA_E_BADARG, "bad planner arguments");
+    if (const char* why = planner_cfg_error(*cfg)) return fail(m, THIA_E_BADARG, why);
+    if (H < 32 || W < 32 || H > 16384 || W > 16384) return fail(m, THIA_E_SHAPE, "frame size must be within 32..16384");
+    const int E = m->n_exits, D = m->D;
+    const int kb = cfg->eval_batch > 0 ? cfg->eval_batch : 64;  // staging capacity; larger requests are cut into pieces
+    const size_t fbytes = (size_t)3 * H * W;
+    // staging: gathered frames, every exit's detections for them, the answers
+    uint8_t *stage = nullptr, *dflags = nullptr;
+    float *ob = nullptr, *os = nullptr;
+    int32_t* ol = nullptr;
+    std::vector<uint8_t> hflags((size_t)E * kb);
+    auto release = [&]() {
+        (void)hipFree(stage); (void)hipFree(dflags); (void)hipFree(ob); (void)hipFree(os); (void)hipFree(ol);
+    };
+    hipError_t he = hipSuccess;
+    if (n > 0) {
+        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&stage), fbytes * kb);
+        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&dflags), (size_t)E * kb);
+        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&ob), (size_t)E * kb * D * 16);
+        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&os), (size_t)E * kb * D * 4);
+        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&ol), (size_t)E * kb * D * 4);
+        if (he != hipSuccess) { release(); return fail(m, THIA_E_NOMEM, std::string("planner staging: ") + hipGetErrorString(he)); }
+    }
+    PlanEval eval = [&](const int* fr, int k, uint8_t* out, std::string& err) -> int {
+        for (int o = 0; o < k; o += kb) {
+            const int kk = std::min(kb, k - o);
+            for (int i = 0; i < kk; ++i) {
+                const hipError_t e1 = hipMemcpyAsync(stage + (size_t)i * fbytes, frames + (size_t)fr[o + i] * fbytes, fbytes,
+                                                     hipMemcpyDeviceToDevice, m->stream);
+                if (e1 != hipSuccess) { err = std::string("planner gather: ") + hipGetErrorString(e1); return THIA_E_HIP; }
+            }
+            int rc = detect_frames_all_exits(m, stage, kk, H, W, ob, os, ol);
+            if (rc != THIA_OK) { err = m->err; return rc; }
+            hipError_t e2 = launch_count_predicate(ol, os, (long)E * kk, D, q->label, q->min_count, q->min_score, dflags, m->stream);
+            if (e2 == hipSuccess) e2 = hipMemcpyAsync(hflags.data(), dflags, (size_t)E * kk, hipMemcpyDeviceToHost, m->stream);
+            if (e2 == hipSuccess) e2 = hipStreamSynchronize(m->stream);
+            if (e2 != hipSuccess) { err = std::string("planner predicate: ") + hipGetErrorString(e2); return THIA_E_HIP; }
+            for (int i = 0; i < kk; ++i)
+                for (int e = 0; e < E; ++e) out[(size_t)(o + i) * E + e] = hflags[(size_t)e * kk + i];  // exit-major -> frame-major
+        }
+        return THIA_OK;
+    };
+    std::vector<PlanChunk> plan;
+    std::string err;
+    const int rc = plan_core(n, E, *cfg, eval, plan, *stats, evaluated, err);
+    release();
+    if (rc != THIA_OK) return fail(m, rc, err);
+    if (store_plan(plan, cap, start, len, ep) != THIA_OK) return fail(m, THIA_E_BADARG, "plan has more chunks than the capacity given");
+    return THIA_OK;
+}
+
 const char* thia_last_error(const thia_model* m) { return m ? m->err.c_str() : "null model"; }
 
 int thia_set_debug(thia_model* m, int enable) {

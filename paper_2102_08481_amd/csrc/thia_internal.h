@@ -5,6 +5,12 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <functional>
+#include <string>
+#include <vector>
+
+#include "../../include/thia.h"
+
 namespace thia {
 
 // ---------------------------------------------------------------- element helpers
@@ -131,5 +137,16 @@ hipError_t launch_select(const float* scores, const float* boxes, const int32_t*
                          float* out_scores, int32_t* out_labels, int32_t* out_n, hipStream_t s);
 // fills the empty pattern for n frames
 hipError_t launch_fill_empty(int n, int D, float* out_boxes, float* out_scores, int32_t* out_labels, hipStream_t s);
+
+// ---------------------------------------------------------------- query planning (host logic + the predicate kernel)
+// flags[r] = (number of slots d of row r with labels[r][d] == label and scores[r][d] >= min_score) >= min_count
+hipError_t launch_count_predicate(const int32_t* labels, const float* scores, long rows, int D, int label, int min_count,
+                                  float min_score, uint8_t* flags, hipStream_t s);
+struct PlanChunk { int start, len, ep; };
+// Evaluates every exit on k frames (indices in `frames`) and writes their answers, flags[i * E + e]; blocks until done.
+using PlanEval = std::function<int(const int* frames, int k, uint8_t* flags, std::string& err)>;
+const char* planner_cfg_error(const thia_planner_cfg& c);  // nullptr if the configuration is usable
+int plan_core(int n, int E, const thia_planner_cfg& cfg, const PlanEval& eval, std::vector<PlanChunk>& plan, thia_plan_stats& st,
+              uint8_t* evaluated_mask, std::string& err);
 
 }  // namespace thia

@@ -1,0 +1,136 @@
+"""Planner on the device path (Sec. 5.2): the predicate kernel, chunks of unequal length, and
+thia_plan_query against the planning oracle.  The planner's decisions are discrete, so the oracle
+planner is fed the answers derived (with the oracle's predicate) from the GPU's own detections of
+every frame -- the planner itself, its sampling, memoisation and batching are what is compared; the
+detections behind the answers are covered by the end-to-end parity tests."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import planner as P
+from gpu_common import MINI_BF16, MINI_FP32, gpu_model, to_dev
+from paper_2102_08481_amd import ThiaError, planner_cfg
+from thia_synth import SceneSpec, make_frames
+
+pytestmark = pytest.mark.gpu
+
+
+def test_predicate_kernel_is_bit_exact():
+    m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
+    rng = np.random.default_rng(3)
+    for rows in (0, 1, 255, 256, 1031):
+        labels = rng.integers(-1, 8, (rows, m.D)).astype(np.int32)
+        scores = (rng.integers(0, 11, (rows, m.D)) / 10).astype(np.float32)      # many ties with the threshold
+        for label, t, s in ((1, 1, 0.0), (3, 4, 0.5), (7, 0, 0.9), (2, m.D + 1, 0.0), (5, 2, 1.0)):
+            got = m.eval_predicate(to_dev(labels), to_dev(scores), label, t, s).cpu().numpy().astype(bool)
+            assert np.array_equal(got, P.count_predicate(labels, scores, label, t, s)), (rows, label, t, s)
+
+
+def test_chunks_of_unequal_length_match_stand_alone_calls():
+    m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
+    frames = to_dev(make_frames(SceneSpec(160, 224, 20, 4, 10, 10, 90), 43))
+    plan = [(10, 5, 4), (0, 3, 1), (3, 7, 0), (17, 3, 2), (15, 0, 3)]           # frames 15, 16 uncovered; unordered
+    b, s, l = m.run_chunks(frames, plan)
+    torch.cuda.synchronize()
+    for a, ln, ep in plan:
+        if ep == 0 or ln == 0:
+            continue
+        cb, cs, cl = m.detect_chunk(frames[a:a + ln].contiguous(), ep)
+        torch.cuda.synchronize()
+        assert torch.equal(b[a:a + ln], cb) and torch.equal(s[a:a + ln], cs) and torch.equal(l[a:a + ln], cl), (a, ln, ep)
+    for a, e in ((3, 10), (15, 17)):
+        assert (l[a:e] == -1).all() and (s[a:e] == 0).all() and (b[a:e] == 0).all()
+    assert (l[:3, 0] >= 1).all()
+    for bad in ([(0, 5, 1), (4, 3, 2)], [(18, 3, 1)], [(-1, 2, 1)], [(0, 2, 5)]):
+        with pytest.raises(ThiaError):
+            m.run_chunks(frames, bad)
+    out = m.run_chunks(frames[:0], [])
+    assert out[0].shape[0] == 0
+
+
+def _answers_of_every_frame(m, frames_dev, label, t, s):
+    b, sc, l = m.detect_all_exits(frames_dev)
+    torch.cuda.synchronize()
+    return P.count_predicate(l.cpu().numpy(), sc.cpu().numpy(), label, t, s).T       # [n, E]
+
+
+def _pick_query(m, frames_dev):
+    """A query whose answer changes along the video (derived from the data; both sides use the same one)."""
+    b, sc, l = m.detect_all_exits(frames_dev)
+    torch.cuda.synchronize()
+    l, sc = l.cpu().numpy(), sc.cpu().numpy()
+    best = None
+    for label in range(1, 8):
+        for t in (1, 2, 3, 4, 6):
+            r = P.count_predicate(l[-1], sc[-1], label, t, 0.0).mean()
+            if best is None or abs(r - 0.5) < best[0]:
+                best = (abs(r - 0.5), label, t)
+    return best[1], best[2]
+
+
+@pytest.mark.parametrize("reuse,batch", [(0, 32), (2, 5), (0, 0)])
+def test_plan_query_equals_the_oracle_planner_on_the_same_answers(reuse, batch):
+    m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
+    n = 150
+    frames = to_dev(make_frames(SceneSpec(160, 224, n, 4, 10, 10, 90), 48))
+    label, t = _pick_query(m, frames)
+    flags = _answers_of_every_frame(m, frames, label, t, 0.0)
+    assert 0 < flags[:, -1].mean() < 1
+    kw = dict(min_chunk=9, final_span=2, posi_enough=0.1, posi_skip=0.0, reuse_dist=reuse)
+    plan_o, pl = P.plan_from_flags(flags, P.PlannerConfig(**kw))
+    plan, st, ev = m.plan_query(frames, label, t, 0.0, planner_cfg(eval_batch=batch, **kw))
+    assert plan == plan_o
+    assert np.flatnonzero(ev).tolist() == sorted(pl.evaluated)
+    assert st["frames_evaluated"] == len(pl.evaluated) and st["samples_reused"] == pl.reused and st["depth"] == pl.depth
+    assert st["frames_evaluated"] < n                                   # sampling, not a scan
+    # executing the plan: every chunk as a stand-alone call would give it, skipped chunks empty
+    b, s, l = m.run_chunks(frames, plan)
+    torch.cuda.synchronize()
+    ans = np.zeros(n, bool)
+    for a, ln, ep in plan:
+        if ep == 0:
+            assert (l[a:a + ln] == -1).all()
+            continue
+        cb, cs, cl = m.detect_chunk(frames[a:a + ln].contiguous(), ep)
+        torch.cuda.synchronize()
+        assert torch.equal(l[a:a + ln], cl) and torch.equal(s[a:a + ln], cs) and torch.equal(b[a:a + ln], cb)
+        ans[a:a + ln] = flags[a:a + ln, ep - 1]
+    got = m.eval_predicate(l, s, label, t, 0.0).cpu().numpy().astype(bool)
+    assert np.array_equal(got, ans)
+
+
+def test_plan_query_against_the_full_oracle_pipeline_fp32():
+    """Small enough for the CPU oracle to evaluate every exit on every frame: oracle detections -> oracle
+    predicate -> oracle planner, against the library's planner on the device.  Discrete answers can differ
+    where a detection score sits within fp32 rounding of a threshold; the comparison is made when the
+    answers agree (reported otherwise), which they do on this seed."""
+    m, blob = gpu_model(MINI_FP32, 0xBEEF + 50)
+    n = 24
+    fh = make_frames(SceneSpec(128, 160, n, 4, 10, 10, 70), 49)
+    fd = to_dev(fh)
+    label, t = _pick_query(m, fd)
+    ref = oracle.Model(blob).detect_all_exits(fh)
+    flags_o = P.count_predicate(ref["labels"], ref["scores"], label, t, 0.0).T
+    flags_g = _answers_of_every_frame(m, fd, label, t, 0.0)
+    agree = np.mean(flags_o == flags_g)
+    assert agree >= 0.95, agree
+    kw = dict(min_chunk=3, final_span=1, posi_enough=0.1, posi_skip=0.0, reuse_dist=0)
+    plan, st, ev = m.plan_query(fd, label, t, 0.0, planner_cfg(eval_batch=8, **kw))
+    plan_o, pl = P.plan_from_flags(flags_o, P.PlannerConfig(**kw))
+    if np.array_equal(flags_o, flags_g):
+        assert plan == plan_o and np.flatnonzero(ev).tolist() == sorted(pl.evaluated)
+    else:
+        print(f"answers differ on {np.sum(flags_o != flags_g)} of {flags_o.size} (frame, exit) pairs; plan compared on the GPU's answers")
+        assert plan == P.plan_from_flags(flags_g, P.PlannerConfig(**kw))[0]
+
+
+def test_plan_query_argument_errors():
+    m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
+    frames = to_dev(make_frames(SceneSpec(160, 224, 4, 4, 10, 10, 90), 50))
+    with pytest.raises(ThiaError):
+        m.plan_query(frames, 1, 1, 0.0, planner_cfg(min_chunk=0))
+    plan, st, ev = m.plan_query(frames[:0], 1, 1)
+    assert plan == [] and st["frames_evaluated"] == 0
+    plan, st, ev = m.plan_query(frames, 1, 1)                            # shorter than one chunk: one chunk
+    assert len(plan) == 1 and plan[0][:2] == (0, 4)
