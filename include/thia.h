@@ -109,7 +109,7 @@ int thia_detect_chunk(thia_model* m, const uint8_t* frames, int n, int H, int W,
 /*
  * Run every exit on the same frames in one pass (Sec. 5.2, evaluation-based exit
  * selection: the planner scores all exits on each sampled frame against the reference
- * exit; Sec. 6.9: exits share parameters and the features already computed).  The
+ * exit; Sec. 6.8: exits share parameters and the features already computed).  The
  * backbone runs once to the last stage and exit e's units read stage e's tensor on the
  * way, so exit e's result is bit-identical to thia_detect_chunk(..., ep = e) while the
  * earlier stages are evaluated once instead of once per exit.

@@ -138,7 +138,7 @@ def test_detect_is_the_composition_of_the_pinned_steps(mini):
 
 
 def test_exit_k_backbone_is_prefix_of_exit_k_plus_1(mini):
-    """Exits share parameters and features (Sec. 6.7 memory discussion): stage k's tensor while
+    """Exits share parameters and features (Sec. 6.8 memory discussion): stage k's tensor while
     running the deepest exit is bit-identical to exit k's own backbone output."""
     blob, frames = mini
     m = oracle.Model(blob)
