@@ -80,10 +80,13 @@ def pick_best_ep(flags_sub, cfg):
 
 class Planner:
     """evaluate(f) -> bool [E]: every exit's answer to the query on frame f (the expensive step).
-    memo=False re-evaluates every sample (the paper's "no reuse" picture)."""
+    memo=False re-evaluates every sample (the paper's "no reuse" picture).
+    select(rows) -> (best_ep, posi_ratio) replaces PickBestEP on the stacked results of the samples (used by
+    estimation-based selection, Sec. 5.3, where evaluate returns (reference answer, OPT_EP) instead)."""
 
-    def __init__(self, evaluate, n, cfg=None, memo=True):
+    def __init__(self, evaluate, n, cfg=None, memo=True, select=None):
         self.evaluate, self.n, self.cfg, self.use_memo = evaluate, int(n), cfg or PlannerConfig(), memo
+        self.select = select or (lambda rows: pick_best_ep(rows, self.cfg))
         self.memo = {}
         self.evaluated = []      # frames passed to evaluate(), in order
         self.reused = 0
@@ -102,7 +105,7 @@ class Planner:
                 g = min(near, key=lambda g: (abs(g - f), g))
                 self.reused += 1
                 return self.memo[g]
-        r = np.asarray(self.evaluate(f), bool)
+        r = np.asarray(self.evaluate(f))
         self.evaluated.append(f)
         self.memo[f] = r
         return r
@@ -114,7 +117,7 @@ class Planner:
         span = int(1 / rate)                                   # sampling_span
         known = set(self.memo)
         sub = [self._result(f, a, b, known) for f in range(a, b, span)]   # V_sub = V[0, span, 2 span, ...]
-        best_ep, posi_ratio = pick_best_ep(np.stack(sub), cfg)
+        best_ep, posi_ratio = self.select(np.stack(sub))
         self.trace.append((a, b, span, best_ep, posi_ratio))
         small = (b - a) < 2 * cfg.min_chunk
         if (posi_ratio >= cfg.posi_enough and best_ep == 1) or small:
@@ -149,3 +152,14 @@ def accuracy_against_reference(flags, plan):
     prec, rec = precision_recall(ans, flags[:, -1])
     f1 = 0.0 if prec + rec == 0 else 2 * prec * rec / (prec + rec)
     return prec, rec, f1
+
+
+def plan_from_estimates(ref_pos, opt, n_exits, cfg=None, memo=True):
+    """Planner with estimation-based exit selection (Sec. 5.3) on tables: ref_pos bool [n] (reference
+    exit's answer), opt int [n] (OPT_EP per frame).  Only sampled rows are looked at."""
+    from .estimator import pick_best_ep_estimated
+    cfg = cfg or PlannerConfig()
+    ref_pos, opt = np.asarray(ref_pos, bool), np.asarray(opt)
+    p = Planner(lambda f: (int(ref_pos[f]), int(opt[f])), len(ref_pos), cfg, memo,
+                select=lambda rows: pick_best_ep_estimated(rows[:, 0].astype(bool), rows[:, 1], n_exits, cfg))
+    return p.plan(), p
