@@ -167,6 +167,8 @@ typedef struct thia_planner_cfg {
     int32_t reuse_dist;       /* a memoised frame of the same chunk within this many frames   */
                               /* stands in for a sample (0 = exact reuse only)                */
     int32_t eval_batch;       /* frames evaluated per device batch (0 = all of a level)       */
+    int32_t use_estimator;    /* 1: estimation-based exit selection (thia_plan_query only;    */
+                              /* needs thia_set_estimator), 0: evaluation-based               */
 } thia_planner_cfg;
 
 typedef struct thia_plan_stats {
@@ -189,6 +191,26 @@ int thia_eval_predicate(thia_model* m, const int32_t* labels, const float* score
                         uint8_t* flags);
 
 /*
+ * Exit estimator (Sec. 5.3): a two-layer network on the last backbone stage's features names,
+ * per frame, the fastest exit that is still right (OPT_EP).  This library's reading of the
+ * two layers: features averaged over the positions, hidden = relu(W1 x + b1), logits =
+ * W2 hidden + b2, OPT_EP = 1 + arg-max (the faster exit on a tie), all in fp32.
+ * thia_set_estimator copies the weights (host float32: w1 [hidden, C], b1 [hidden],
+ * w2 [n_exits, hidden], b2 [n_exits], C = channels of the last stage); hidden = 0 removes
+ * them.  C + hidden + n_exits must not exceed 16000.
+ */
+int thia_set_estimator(thia_model* m, int hidden, const float* w1, const float* b1, const float* w2, const float* b2);
+
+/*
+ * Reference exit and estimator on the same frames in one backbone pass: opt_ep dev int32 [n]
+ * (1..n_exits), logits dev float32 [n, n_exits] or NULL, out_* the last exit's detections as
+ * thia_detect_chunk(ep = n_exits) gives them (bit-identical).  The other exits' units are
+ * not run: this is what estimation-based planning saves on every sampled frame.
+ */
+int thia_estimate_exit(thia_model* m, const uint8_t* frames, int n, int H, int W, int32_t* opt_ep, float* logits,
+                       float* out_boxes, float* out_scores, int32_t* out_labels);
+
+/*
  * The planner on a table of answers (host only, touches no device): flags host uint8
  * [n,n_exits], flags[f*n_exits+e] = exit e+1's answer on frame f (only sampled rows are read;
  * the last exit is the reference).  Writes the plan in frame order to start/len/ep (host int32,
@@ -206,6 +228,11 @@ int thia_plan_from_flags(const uint8_t* flags, int n, int n_exits, const thia_pl
  * come back to the host.  Blocks until the plan is known (it synchronises the model's stream
  * once per batch) and allocates its staging buffers for the duration of the call.  Outputs as
  * for thia_plan_from_flags.  Execute the plan with thia_run_chunks.
+ * With cfg->use_estimator the samples go through thia_estimate_exit's path instead, and exit
+ * k's true/false positives and false negatives are extrapolated as Sec. 5.3 states them:
+ * on a frame the reference exit reports positive, exit k counts as a true positive when
+ * k >= OPT_EP and as a false negative otherwise; on a negative frame it counts as a false
+ * positive when k < OPT_EP.
  */
 int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, const thia_query* q,
                     const thia_planner_cfg* cfg, int cap, int32_t* start, int32_t* len, int32_t* ep,

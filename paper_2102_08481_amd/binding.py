@@ -24,7 +24,8 @@ KERNEL_CLASSES = ["stem", "pool", "conv", "fc", "topk", "nms", "roialign", "post
 
 EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_microbatch", "thia_get_info",
            "thia_detect_chunk", "thia_detect_all_exits", "thia_run_plan", "thia_run_chunks",
-           "thia_planner_defaults", "thia_eval_predicate", "thia_plan_from_flags", "thia_plan_query", "thia_last_error", "thia_set_debug", "thia_debug_tap",
+           "thia_planner_defaults", "thia_eval_predicate", "thia_plan_from_flags", "thia_plan_query",
+           "thia_set_estimator", "thia_estimate_exit", "thia_last_error", "thia_set_debug", "thia_debug_tap",
            "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
            "thia_op_rpn_proposals", "thia_op_nms", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
            "thia_op_stem", "thia_op_bottleneck", "thia_set_fusion"]
@@ -43,7 +44,8 @@ class ThiaQuery(C.Structure):
 
 class ThiaPlannerCfg(C.Structure):
     _fields_ = [("precision", C.c_double), ("recall", C.c_double), ("min_chunk", C.c_int32), ("final_span", C.c_int32),
-                ("posi_enough", C.c_double), ("posi_skip", C.c_double), ("reuse_dist", C.c_int32), ("eval_batch", C.c_int32)]
+                ("posi_enough", C.c_double), ("posi_skip", C.c_double), ("reuse_dist", C.c_int32), ("eval_batch", C.c_int32),
+                ("use_estimator", C.c_int32)]
 
 
 class ThiaPlanStats(C.Structure):
@@ -85,6 +87,8 @@ def lib():
     L.thia_plan_from_flags.argtypes = [vp, i32, i32, C.POINTER(ThiaPlannerCfg), i32, vp, vp, vp, C.POINTER(ThiaPlanStats), vp]
     L.thia_plan_query.argtypes = [vp, vp, i32, i32, i32, C.POINTER(ThiaQuery), C.POINTER(ThiaPlannerCfg), i32, vp, vp, vp,
                                   C.POINTER(ThiaPlanStats), vp]
+    L.thia_set_estimator.argtypes = [vp, i32, vp, vp, vp, vp]
+    L.thia_estimate_exit.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
     L.thia_last_error.argtypes = [vp]
     L.thia_last_error.restype = C.c_char_p
     L.thia_set_debug.argtypes = [vp, i32]
@@ -258,6 +262,28 @@ class Model:
         q = ThiaQuery(label, min_count, min_score)
         self._check(lib().thia_eval_predicate(self._h, _ptr(labels), _ptr(scores), rows, C.byref(q), _ptr(flags)))
         return flags
+
+    def set_estimator(self, w1, b1, w2, b2):
+        """Two-layer exit estimator: w1 [hidden, C_last], b1 [hidden], w2 [n_exits, hidden], b2 [n_exits] (host); None removes it."""
+        if w1 is None:
+            self._check(lib().thia_set_estimator(self._h, 0, None, None, None, None))
+            return
+        a = [np.ascontiguousarray(x, dtype=np.float32) for x in (w1, b1, w2, b2)]
+        hidden = a[0].shape[0]
+        assert a[1].shape == (hidden,) and a[2].shape == (self.n_exits, hidden) and a[3].shape == (self.n_exits,)
+        self._check(lib().thia_set_estimator(self._h, hidden, *[x.ctypes.data for x in a]))
+
+    def estimate_exit(self, frames, out=None):
+        """Returns (opt_ep int32 [n], logits float32 [n, E], (boxes, scores, labels) of the last exit)."""
+        _dev(frames, torch.uint8)
+        n, c, H, W = frames.shape
+        assert c == 3
+        opt = torch.empty(n, dtype=torch.int32, device=self.device)
+        logits = torch.empty((n, self.n_exits), dtype=torch.float32, device=self.device)
+        out = out or self.alloc_outputs(n)
+        self._check(lib().thia_estimate_exit(self._h, _ptr(frames), n, H, W, _ptr(opt), _ptr(logits), _ptr(out[0]), _ptr(out[1]),
+                                             _ptr(out[2])))
+        return opt, logits, out
 
     def plan_query(self, frames, label, min_count, min_score=0.0, cfg=None):
         """thia_plan_query on resident frames -> (plan, stats dict, evaluated mask [n])."""

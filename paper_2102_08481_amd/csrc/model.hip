@@ -78,6 +78,10 @@ struct thia_model {
     hipStream_t stream = nullptr;
     int user_mb = 0;
     bool fuse_blocks = true;  // identity bottlenecks as one kernel where a variant exists
+    // exit estimator (two layers on the pooled last-stage features); est_hidden == 0: none set
+    int est_hidden = 0;
+    float *est_w1t = nullptr, *est_b1 = nullptr, *est_w2 = nullptr, *est_b2 = nullptr, *est_pooled = nullptr;
+    size_t est_pooled_cap = 0;
     Workspace ws;
     bool debug = false;
     Tap taps[THIA_TAP_COUNT];
@@ -591,6 +595,46 @@ int detect_frames_all_exits(thia_model* m, const uint8_t* frames, int n, int H, 
     return rc;
 }
 
+void free_estimator(thia_model* m) {
+    (void)hipFree(m->est_w1t); (void)hipFree(m->est_b1); (void)hipFree(m->est_w2); (void)hipFree(m->est_b2); (void)hipFree(m->est_pooled);
+    m->est_w1t = m->est_b1 = m->est_w2 = m->est_b2 = m->est_pooled = nullptr;
+    m->est_hidden = 0; m->est_pooled_cap = 0;
+}
+
+// n frames to the last stage once: the estimator reads that stage's tensor, the last exit's units give the reference detections.
+int estimate_frames(thia_model* m, const uint8_t* frames, int n, int H, int W, int32_t* opt, float* logits, float* ob, float* os,
+                    int32_t* ol) {
+    TRY(ensure_workspace(m, H, W));
+    const int mb = m->ws.mb, D = m->D, E = m->n_exits;
+    const ExitGeom g = exit_geom(m, E, H, W);
+    const size_t need = (size_t)mb * g.C * sizeof(float);
+    if (need > m->est_pooled_cap) {
+        if (m->est_pooled) { HIP_TRY(m, hipStreamSynchronize(m->stream)); (void)hipFree(m->est_pooled); m->est_pooled = nullptr; m->est_pooled_cap = 0; }
+        HIP_TRY(m, hipMalloc(reinterpret_cast<void**>(&m->est_pooled), need));
+        m->est_pooled_cap = need;
+    }
+    const bool debug = m->debug;
+    m->debug = false;
+    int rc = THIA_OK;
+    for (int f0 = 0; f0 < n && rc == THIA_OK; f0 += mb) {
+        const int nb = std::min(mb, n - f0);
+        Trunk t;
+        rc = run_stem(m, frames + (size_t)f0 * 3 * H * W, nb, H, W, t);
+        for (int s = 0; s < E && rc == THIA_OK; ++s) rc = run_stage(m, s, nb, t);
+        if (rc != THIA_OK) break;
+        {
+            Scope sc(m, THIA_K_POST);
+            const hipError_t e = launch_estimator(t.x, nb, g.Hk * g.Wk, g.C, m->precision, m->est_pooled, m->est_hidden, E, m->est_w1t,
+                                                  m->est_b1, m->est_w2, m->est_b2, opt + f0, logits ? logits + (size_t)f0 * E : nullptr,
+                                                  m->stream);
+            if (e != hipSuccess) { rc = fail_hip(m, e, "launch_estimator"); break; }
+        }
+        rc = run_heads(m, t.x, f0, nb, H, W, E, ob + (size_t)f0 * D * 4, os + (size_t)f0 * D, ol + (size_t)f0 * D);
+    }
+    m->debug = debug;
+    return rc;
+}
+
 }  // namespace
 
 // =================================================================== C ABI
@@ -738,6 +782,7 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
 }
 
 void thia_free_model(thia_model* m) {
+    if (m) free_estimator(m);
     if (!m) return;
     (void)hipStreamSynchronize(m->stream);
     free_workspace(m);
@@ -879,7 +924,7 @@ void thia_planner_defaults(thia_planner_cfg* cfg) {
     cfg->precision = 0.8; cfg->recall = 0.8;
     cfg->min_chunk = 100; cfg->final_span = 10;
     cfg->posi_enough = 0.1; cfg->posi_skip = 0.0;
-    cfg->reuse_dist = 0; cfg->eval_batch = 32;
+    cfg->reuse_dist = 0; cfg->eval_batch = 32; cfg->use_estimator = 0;
 }
 
 int thia_eval_predicate(thia_model* m, const int32_t* labels, const float* scores, int rows, const thia_query* q, uint8_t* flags) {
@@ -887,6 +932,40 @@ int thia_eval_predicate(thia_model* m, const int32_t* labels, const float* score
     if (rows < 0 || !q || (rows > 0 && (!labels || !scores || !flags))) return fail(m, THIA_E_BADARG, "bad predicate arguments");
     HIP_TRY(m, launch_count_predicate(labels, scores, rows, m->D, q->label, q->min_count, q->min_score, flags, m->stream));
     return THIA_OK;
+}
+
+int thia_set_estimator(thia_model* m, int hidden, const float* w1, const float* b1, const float* w2, const float* b2) {
+    if (!m) return THIA_E_BADARG;
+    if (hidden < 0 || (hidden > 0 && (!w1 || !b1 || !w2 || !b2))) return fail(m, THIA_E_BADARG, "bad estimator arguments");
+    const int E = m->n_exits, Cl = 4 * (m->base_width << (E - 1));
+    if (hidden > 0 && Cl + hidden + E > 16000) return fail(m, THIA_E_SHAPE, "estimator too wide: channels + hidden + exits must not exceed 16000");
+    HIP_TRY(m, hipStreamSynchronize(m->stream));
+    free_estimator(m);
+    if (hidden == 0) return THIA_OK;
+    std::vector<float> w1t((size_t)Cl * hidden);
+    for (int j = 0; j < hidden; ++j)
+        for (int c = 0; c < Cl; ++c) w1t[(size_t)c * hidden + j] = w1[(size_t)j * Cl + c];
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&m->est_w1t), w1t.size() * 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&m->est_b1), (size_t)hidden * 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&m->est_w2), (size_t)E * hidden * 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&m->est_b2), (size_t)E * 4);
+    if (e == hipSuccess) e = hipMemcpy(m->est_w1t, w1t.data(), w1t.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(m->est_b1, b1, (size_t)hidden * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(m->est_w2, w2, (size_t)E * hidden * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(m->est_b2, b2, (size_t)E * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { free_estimator(m); return fail_hip(m, e, "thia_set_estimator"); }
+    m->est_hidden = hidden;
+    return THIA_OK;
+}
+
+int thia_estimate_exit(thia_model* m, const uint8_t* frames, int n, int H, int W, int32_t* opt_ep, float* logits, float* out_boxes,
+                       float* out_scores, int32_t* out_labels) {
+    int rc = check_frame_args(m, frames, n, H, W, out_boxes, out_scores, out_labels);
+    if (rc != THIA_OK) return rc;
+    if (n > 0 && !opt_ep) return fail(m, THIA_E_BADARG, "null pointer");
+    if (m->est_hidden == 0) return fail(m, THIA_E_BADARG, "no estimator set (thia_set_estimator)");
+    if (n == 0) return THIA_OK;
+    return estimate_frames(m, frames, n, H, W, opt_ep, logits, out_boxes, out_scores, out_labels);
 }
 
 namespace {
@@ -921,16 +1000,19 @@ int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, c
         return fail(m, THIA_E_BADARG, "bad planner arguments");
     if (const char* why = planner_cfg_error(*cfg)) return fail(m, THIA_E_BADARG, why);
     if (H < 32 || W < 32 || H > 16384 || W > 16384) return fail(m, THIA_E_SHAPE, "frame size must be within 32..16384");
+    const bool est = cfg->use_estimator != 0;
+    if (est && m->est_hidden == 0) return fail(m, THIA_E_BADARG, "use_estimator without an estimator (thia_set_estimator)");
     const int E = m->n_exits, D = m->D;
     const int kb = cfg->eval_batch > 0 ? cfg->eval_batch : 64;  // staging capacity; larger requests are cut into pieces
     const size_t fbytes = (size_t)3 * H * W;
     // staging: gathered frames, every exit's detections for them, the answers
     uint8_t *stage = nullptr, *dflags = nullptr;
     float *ob = nullptr, *os = nullptr;
-    int32_t* ol = nullptr;
+    int32_t *ol = nullptr, *dopt = nullptr;
     std::vector<uint8_t> hflags((size_t)E * kb);
+    std::vector<int32_t> hopt(kb);
     auto release = [&]() {
-        (void)hipFree(stage); (void)hipFree(dflags); (void)hipFree(ob); (void)hipFree(os); (void)hipFree(ol);
+        (void)hipFree(stage); (void)hipFree(dflags); (void)hipFree(ob); (void)hipFree(os); (void)hipFree(ol); (void)hipFree(dopt);
     };
     hipError_t he = hipSuccess;
     if (n > 0) {
@@ -939,6 +1021,7 @@ int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, c
         if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&ob), (size_t)E * kb * D * 16);
         if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&os), (size_t)E * kb * D * 4);
         if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&ol), (size_t)E * kb * D * 4);
+        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&dopt), (size_t)kb * 4);
         if (he != hipSuccess) { release(); return fail(m, THIA_E_NOMEM, std::string("planner staging: ") + hipGetErrorString(he)); }
     }
     PlanEval eval = [&](const int* fr, int k, uint8_t* out, std::string& err) -> int {
@@ -949,14 +1032,21 @@ int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, c
                                                      hipMemcpyDeviceToDevice, m->stream);
                 if (e1 != hipSuccess) { err = std::string("planner gather: ") + hipGetErrorString(e1); return THIA_E_HIP; }
             }
-            int rc = detect_frames_all_exits(m, stage, kk, H, W, ob, os, ol);
+            const int rows = est ? kk : E * kk;
+            int rc = est ? estimate_frames(m, stage, kk, H, W, dopt, nullptr, ob, os, ol) : detect_frames_all_exits(m, stage, kk, H, W, ob, os, ol);
             if (rc != THIA_OK) { err = m->err; return rc; }
-            hipError_t e2 = launch_count_predicate(ol, os, (long)E * kk, D, q->label, q->min_count, q->min_score, dflags, m->stream);
-            if (e2 == hipSuccess) e2 = hipMemcpyAsync(hflags.data(), dflags, (size_t)E * kk, hipMemcpyDeviceToHost, m->stream);
+            hipError_t e2 = launch_count_predicate(ol, os, rows, D, q->label, q->min_count, q->min_score, dflags, m->stream);
+            if (e2 == hipSuccess) e2 = hipMemcpyAsync(hflags.data(), dflags, (size_t)rows, hipMemcpyDeviceToHost, m->stream);
+            if (e2 == hipSuccess && est) e2 = hipMemcpyAsync(hopt.data(), dopt, (size_t)kk * 4, hipMemcpyDeviceToHost, m->stream);
             if (e2 == hipSuccess) e2 = hipStreamSynchronize(m->stream);
             if (e2 != hipSuccess) { err = std::string("planner predicate: ") + hipGetErrorString(e2); return THIA_E_HIP; }
             for (int i = 0; i < kk; ++i)
-                for (int e = 0; e < E; ++e) out[(size_t)(o + i) * E + e] = hflags[(size_t)e * kk + i];  // exit-major -> frame-major
+                for (int e = 0; e < E; ++e) {
+                    // evaluated: exit e+1's own answer (exit-major on the device).  Estimated (Sec. 5.3): exit k is taken to
+                    // answer like the reference exactly when k >= OPT_EP, which yields the section's TP, FP and FN sums.
+                    const bool ref = hflags[est ? i : (size_t)(E - 1) * kk + i] != 0;
+                    out[(size_t)(o + i) * E + e] = est ? ((e + 1 >= hopt[i]) == ref ? 1 : 0) : hflags[(size_t)e * kk + i];
+                }
         }
         return THIA_OK;
     };

@@ -26,6 +26,53 @@ __global__ void count_predicate_kernel(const int32_t* __restrict__ labels, const
     flags[r] = c >= min_count ? 1 : 0;
 }
 
+// Mean over the positions of an NHWC map, one thread per channel: feat [n][HW][C] -> pooled [n][C].
+template <typename T>
+__global__ void spatial_mean_kernel(const T* __restrict__ feat, int HW, int C, float* __restrict__ pooled) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x, f = blockIdx.y;
+    if (c >= C) return;
+    const T* p = feat + (size_t)f * HW * C + c;
+    float acc = 0.f;
+    for (int i = 0; i < HW; ++i) {
+        if constexpr (sizeof(T) == 2) acc += bf16_to_f32(p[(size_t)i * C]);
+        else acc += p[(size_t)i * C];
+    }
+    pooled[(size_t)f * C + c] = acc / (float)HW;
+}
+
+// The exit estimator's two layers on one frame per block (Sec. 5.3): hidden = relu(W1 pooled + b1),
+// logits = W2 hidden + b2, estimate = 1 + index of the largest logit (the first on a tie).
+// w1t is W1 transposed, [C][hid], so that consecutive threads read consecutive addresses.
+__global__ void __launch_bounds__(256) estimator_mlp_kernel(const float* __restrict__ pooled, int C, int hid, int E,
+                                                            const float* __restrict__ w1t, const float* __restrict__ b1,
+                                                            const float* __restrict__ w2, const float* __restrict__ b2,
+                                                            int32_t* __restrict__ opt, float* __restrict__ logits_out) {
+    extern __shared__ float sm[];
+    float *sp = sm, *sh = sm + C, *sl = sh + hid;
+    const int f = blockIdx.x, tid = threadIdx.x;
+    for (int c = tid; c < C; c += 256) sp[c] = pooled[(size_t)f * C + c];
+    __syncthreads();
+    for (int j = tid; j < hid; j += 256) {
+        float acc = b1[j];
+        for (int c = 0; c < C; ++c) acc += w1t[(size_t)c * hid + j] * sp[c];
+        sh[j] = acc > 0.f ? acc : 0.f;
+    }
+    __syncthreads();
+    for (int e = tid; e < E; e += 256) {
+        float acc = b2[e];
+        for (int j = 0; j < hid; ++j) acc += w2[(size_t)e * hid + j] * sh[j];
+        sl[e] = acc;
+        if (logits_out) logits_out[(size_t)f * E + e] = acc;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int best = 0;
+        for (int e = 1; e < E; ++e)
+            if (sl[e] > sl[best]) best = e;
+        opt[f] = best + 1;
+    }
+}
+
 struct Node {
     int a, b;
     long long span;
@@ -41,6 +88,17 @@ hipError_t launch_count_predicate(const int32_t* labels, const float* scores, lo
     const long blocks = (rows + threads - 1) / threads;
     hipLaunchKernelGGL(count_predicate_kernel, dim3((unsigned)blocks), dim3(threads), 0, s, labels, scores, rows, D, label, min_count,
                        min_score, flags);
+    return hipGetLastError();
+}
+
+hipError_t launch_estimator(const void* feat, int n, int HW, int C, int precision, float* pooled, int hid, int E, const float* w1t,
+                            const float* b1, const float* w2, const float* b2, int32_t* opt, float* logits, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    const dim3 grid((C + 255) / 256, n);
+    if (precision == 1) hipLaunchKernelGGL(spatial_mean_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(feat), HW, C, pooled);
+    else hipLaunchKernelGGL(spatial_mean_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(feat), HW, C, pooled);
+    const size_t lds = sizeof(float) * ((size_t)C + hid + E);
+    hipLaunchKernelGGL(estimator_mlp_kernel, dim3(n), dim3(256), lds, s, pooled, C, hid, E, w1t, b1, w2, b2, opt, logits);
     return hipGetLastError();
 }
 

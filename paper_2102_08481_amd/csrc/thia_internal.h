@@ -142,6 +142,10 @@ hipError_t launch_fill_empty(int n, int D, float* out_boxes, float* out_scores, 
 // flags[r] = (number of slots d of row r with labels[r][d] == label and scores[r][d] >= min_score) >= min_count
 hipError_t launch_count_predicate(const int32_t* labels, const float* scores, long rows, int D, int label, int min_count,
                                   float min_score, uint8_t* flags, hipStream_t s);
+// Exit estimator (Sec. 5.3) on NHWC last-stage features [n][HW][C]: pooled scratch [n][C]; w1t = W1 transposed [C][hid];
+// C + hid + E floats of LDS (the caller keeps that within 64 KB); opt int32 [n] in 1..E, logits [n][E] or nullptr.
+hipError_t launch_estimator(const void* feat, int n, int HW, int C, int precision, float* pooled, int hid, int E, const float* w1t,
+                            const float* b1, const float* w2, const float* b2, int32_t* opt, float* logits, hipStream_t s);
 struct PlanChunk { int start, len, ep; };
 // Evaluates every exit on k frames (indices in `frames`) and writes their answers, flags[i * E + e]; blocks until done.
 using PlanEval = std::function<int(const int* frames, int k, uint8_t* flags, std::string& err)>;

@@ -8,8 +8,9 @@ import pytest
 import torch
 
 import oracle
+from oracle import estimator as Est
 from oracle import planner as P
-from gpu_common import MINI_BF16, MINI_FP32, gpu_model, to_dev
+from gpu_common import MINI_BF16, MINI_FP32, gpu_model, nhwc_to_nchw, relerr, to_dev
 from paper_2102_08481_amd import ThiaError, planner_cfg
 from thia_synth import SceneSpec, make_frames
 
@@ -134,3 +135,78 @@ def test_plan_query_argument_errors():
     assert plan == [] and st["frames_evaluated"] == 0
     plan, st, ev = m.plan_query(frames, 1, 1)                            # shorter than one chunk: one chunk
     assert len(plan) == 1 and plan[0][:2] == (0, 4)
+
+
+def _estimator_weights(seed, C=2048, hidden=96, E=4):
+    rng = np.random.default_rng(seed)
+    return (rng.normal(0, C ** -0.5, (hidden, C)).astype(np.float32), rng.normal(0, 0.1, hidden).astype(np.float32),
+            rng.normal(0, hidden ** -0.5, (E, hidden)).astype(np.float32), rng.normal(0, 0.05, E).astype(np.float32))
+
+
+@pytest.mark.parametrize("spec,tol_full", [(MINI_FP32, 1e-4), (MINI_BF16, 2e-2)])
+def test_exit_estimator_matches_oracle(spec, tol_full):
+    """Logits against the oracle on the GPU's own last-stage tensor (fp32 accumulation vs float64: 1e-5) and on
+    the oracle's own backbone (the path's stated tolerance); the arg-max wherever the two best logits are
+    further apart than that error; the reference detections bit-identical to a call at the last exit."""
+    m, blob = gpu_model(spec, 0xBEEF + (50 if spec is MINI_FP32 else 51))
+    w = _estimator_weights(11)
+    m.set_estimator(*w)
+    fh = make_frames(SceneSpec(160, 224, 5, 4, 10, 10, 90), 52)
+    fd = to_dev(fh)
+    opt, logits, (b, s, l) = m.estimate_exit(fd)
+    torch.cuda.synchronize()
+    m.set_debug(True)
+    rb, rs, rl = m.detect_chunk(fd, 4)
+    torch.cuda.synchronize()
+    Ck, Hk, Wk, _ = oracle.Model(blob).exit_shape(4, 160, 224)
+    feat = nhwc_to_nchw(m.tap("feat").reshape(5, Hk, Wk, Ck))
+    m.set_debug(False)
+    assert torch.equal(b, rb) and torch.equal(s, rs) and torch.equal(l, rl)
+    opt, logits = opt.cpu().numpy(), logits.cpu().numpy()
+    o_opt, o_logits = Est.estimate_exit(feat, *w)
+    assert relerr(logits, o_logits) <= 1e-5
+    top2 = np.sort(o_logits, axis=1)[:, -2:]
+    clear = (top2[:, 1] - top2[:, 0]) > 1e-5 * np.abs(o_logits).max()
+    assert clear.any() and np.array_equal(opt[clear], o_opt[clear])
+    assert ((opt >= 1) & (opt <= 4)).all()
+    f_opt, f_logits = Est.estimate_exit(oracle.Model(blob).backbone(fh, 4), *w)
+    assert relerr(logits, f_logits) <= tol_full
+    # micro-batching does not change the estimate; removing the estimator makes the call fail
+    m.set_microbatch(2)
+    opt2, logits2, _ = m.estimate_exit(fd)
+    torch.cuda.synchronize()
+    m.set_microbatch(0)
+    assert np.array_equal(opt2.cpu().numpy(), opt) and np.array_equal(logits2.cpu().numpy(), logits)
+    m.set_estimator(None, None, None, None)
+    with pytest.raises(ThiaError):
+        m.estimate_exit(fd)
+    with pytest.raises(ThiaError):
+        m.plan_query(fd, 1, 1, 0.0, planner_cfg(use_estimator=1))
+
+
+def test_plan_query_with_estimator_equals_the_oracle_planner_on_the_same_estimates():
+    m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
+    n = 150
+    # five scenes, so that the pooled features (and with them the estimate) change along the video
+    fh = np.concatenate([make_frames(SceneSpec(160, 224, 30, 2 + 3 * i, 4 + 4 * i, 10, 40 + 12 * i), 60 + i) for i in range(5)])
+    frames = to_dev(fh)
+    w1, b1, w2, b2 = _estimator_weights(12)
+    m.set_estimator(w1, b1, w2, b2)
+    _, logits, _ = m.estimate_exit(frames)
+    torch.cuda.synchronize()
+    # centre every exit's output over the video (a stand-in for training, which needs labelled data): the estimate then varies
+    b2 = (b2 - logits.cpu().numpy().mean(axis=0)).astype(np.float32)
+    m.set_estimator(w1, b1, w2, b2)
+    label, t = _pick_query(m, frames)
+    opt, _, (b, s, l) = m.estimate_exit(frames)
+    torch.cuda.synchronize()
+    ref = P.count_predicate(l.cpu().numpy(), s.cpu().numpy(), label, t, 0.0)
+    opt = opt.cpu().numpy()
+    assert len(set(opt.tolist())) > 1 and 0 < ref.mean() < 1
+    kw = dict(min_chunk=9, final_span=2, posi_enough=0.1, posi_skip=0.0, reuse_dist=0)
+    plan_o, pl = P.plan_from_estimates(ref, opt, 4, P.PlannerConfig(**kw))
+    plan, st, ev = m.plan_query(frames, label, t, 0.0, planner_cfg(eval_batch=16, use_estimator=1, **kw))
+    m.set_estimator(None, None, None, None)
+    assert plan == plan_o
+    assert np.flatnonzero(ev).tolist() == sorted(pl.evaluated) and st["samples_reused"] == pl.reused
+    print("plan with estimator:", plan, st)

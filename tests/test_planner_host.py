@@ -65,3 +65,22 @@ def test_bad_configurations_are_refused():
             plan_from_flags(flags, planner_cfg(**bad))
     with pytest.raises(KeyError):
         planner_cfg(no_such_field=1)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_estimation_based_planning_through_the_answer_table(seed):
+    """Sec. 5.3: with OPT_EP per frame, exit k counts as right exactly when k >= OPT_EP.  The library plans
+    estimation-based by handing its planner that implied table; the oracle evaluates the section's TP/FP/FN
+    sums directly.  Same plan, same evaluated frames."""
+    rng = np.random.default_rng(9000 + seed)
+    n, E = int(rng.integers(1, 4000)), int(rng.integers(1, 6))
+    seg = np.cumsum(rng.integers(15, 300, 96))
+    sid = np.searchsorted(seg, np.arange(n), side="right")
+    ref = (rng.random(96) < rng.random())[sid] & (rng.random(n) < 0.95)
+    opt = np.clip(rng.integers(1, E + 1, 96)[sid] + (rng.random(n) < 0.1), 1, E)
+    kw = dict(min_chunk=int(rng.integers(1, 150)), final_span=int(rng.integers(1, 14)), reuse_dist=int(rng.choice([0, 2])))
+    plan_o, pl = P.plan_from_estimates(ref, opt, E, P.PlannerConfig(**kw))
+    implied = np.stack([(k >= opt) == ref for k in range(1, E + 1)], axis=1)
+    plan_l, st, ev = plan_from_flags(implied, planner_cfg(**kw))
+    assert plan_l == plan_o
+    assert np.flatnonzero(ev).tolist() == sorted(pl.evaluated) and st["samples_reused"] == pl.reused
