@@ -83,6 +83,19 @@ def measured_traffic(workload_key):
     return None
 
 
+def derive_query(labels, scores):
+    """A Table-2-style query (Count(class) >= t over detections above a confidence) that is true on about half of the given
+    frames.  Random-init predictors put nearly every detection in one class with nearly equal confidence, so the count is
+    taken over that class's detections above its median confidence and the threshold is the median such count.
+    labels, scores: numpy [n, D] of the reference exit.  Returns (label, t, min_score, ratio of positive frames)."""
+    import numpy as np
+    label = int(np.bincount(labels[labels > 0].ravel()).argmax())
+    min_score = float(np.median(scores[labels == label]))
+    cnt = ((labels == label) & (scores >= np.float32(min_score))).sum(axis=1)
+    t = max(1, int(np.ceil(np.median(cnt) + 0.5)))
+    return label, t, min_score, float((cnt >= t).mean())
+
+
 def planner_workload(args):
     """Beside the headline metric: query processing time on a long synthetic video, split the way the paper
     splits it (Sec. 6.5): optimisation (the planner's sampling, every exit per sampled frame in one backbone
@@ -105,14 +118,7 @@ def planner_workload(args):
     sub = frames[:: max(1, N // 64)][:64].contiguous()
     _, sc, lb = model.detect_chunk(sub, E)
     torch.cuda.synchronize()
-    lbh, sch = lb.cpu().numpy(), sc.cpu().numpy()
-    # random-init predictors put nearly every detection in one class with nearly equal confidence, so the count is
-    # taken over that class's detections above its median confidence, and the threshold is the median such count
-    label = int(np.bincount(lbh[lbh > 0].ravel()).argmax())
-    min_score = float(np.median(sch[lbh == label]))
-    cnt = ((lbh == label) & (sch >= np.float32(min_score))).sum(axis=1)
-    t = max(1, int(np.ceil(np.median(cnt) + 0.5)))
-    ratio = float((cnt >= t).mean())
+    label, t, min_score, ratio = derive_query(lb.cpu().numpy(), sc.cpu().numpy())
     pc = planner_cfg()
     model.detect_all_exits(sub[:32].contiguous())     # warm-up: workspace and code objects
     torch.cuda.synchronize()
@@ -251,6 +257,17 @@ def main():
         eb.record(stream)
         torch.cuda.synchronize()
         all_exits_ms = ea.elapsed_time(eb) / args.steps
+        # each exit's frame answers against the last exit's, on the paper's metric (Sec. 6.1: precision / recall / F-1
+        # relative to the reference model), for a query derived from the last exit's detections
+        E = len(exits)
+        qlabel, qt, qscore, qratio = derive_query(out_all[2][E - 1].cpu().numpy(), out_all[1][E - 1].cpu().numpy())
+        answers = model.eval_predicate(out_all[2], out_all[1], qlabel, qt, qscore)          # [E, B]
+        from paper_2102_08481_amd import metrics_from_counts
+        agreement = {"query": {"label": qlabel, "min_count": qt, "min_score": qscore, "positive_ratio_at_reference": qratio}}
+        for e in range(E):
+            c = model.answer_counts(answers[e].contiguous(), answers[E - 1].contiguous()).cpu().numpy()
+            p_, r_, f_ = metrics_from_counts(c)
+            agreement[f"EP{e + 1}"] = {"precision": p_, "recall": r_, "f1": f_}
 
     if args.pmc_calibration:
         # a plain copy of known size, so that a `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE` run of this command can
@@ -304,6 +321,7 @@ def main():
     if all_exits_ms is not None:
         result["all_exits_one_pass"] = {"ms_per_batch": all_exits_ms, "frames_per_s": B / (all_exits_ms * 1e-3),
                                         "vs_sweep": ms_per_step / all_exits_ms}
+        result["answers_vs_last_exit"] = agreement
     if not args.skip_cpu_baseline:
         import oracle
         orc = oracle.Model(blob)

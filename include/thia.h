@@ -191,6 +191,20 @@ int thia_eval_predicate(thia_model* m, const int32_t* labels, const float* score
                         uint8_t* flags);
 
 /*
+ * Accuracy of frame answers relative to the reference exit's (Sec. 6.1: every system is scored
+ * against the reference model's answers): answers, reference dev uint8 [n] (as written by
+ * thia_eval_predicate), counts dev int32 [3] = true positives, false positives, false negatives.
+ */
+int thia_answer_counts(thia_model* m, const uint8_t* answers, const uint8_t* reference, int n, int32_t* counts);
+
+/*
+ * Precision, recall and F-1 from such counts (host int32 [3] -> host double [3]).  An empty
+ * denominator gives 1 for precision / recall (no false claim made, nothing to recall); F-1 is
+ * the harmonic mean, 0 when both are 0.
+ */
+void thia_metrics_from_counts(const int32_t* counts, double* prf);
+
+/*
  * Exit estimator (Sec. 5.3): a two-layer network on the last backbone stage's features names,
  * per frame, the fastest exit that is still right (OPT_EP).  This library's reading of the
  * two layers: features averaged over the positions, hidden = relu(W1 x + b1), logits =

@@ -62,6 +62,16 @@ def precision_recall(pred, ref):
     return prec, rec
 
 
+def answer_metrics(pred, ref):
+    """Sec. 6.1: frame answers of a system against the reference exit's: (TP, FP, FN, precision, recall, F-1);
+    F-1 = harmonic mean of precision and recall, 0 when both are 0."""
+    pred, ref = np.asarray(pred, bool), np.asarray(ref, bool)
+    tp, fp, fn = int(np.sum(pred & ref)), int(np.sum(pred & ~ref)), int(np.sum(~pred & ref))
+    prec, rec = precision_recall(pred, ref)
+    f1 = 0.0 if prec + rec == 0 else 2 * prec * rec / (prec + rec)
+    return tp, fp, fn, prec, rec, f1
+
+
 def pick_best_ep(flags_sub, cfg):
     """PickBestEP: flags_sub bool [k, E] (frame answers per exit; the last exit is the
     reference).  Returns (fastest exit meeting P and R, 1-based; ratio of positive frames

@@ -3,7 +3,7 @@
 
 The names below mirror the C entry points; they only marshal arguments.
 """
-from .binding import (Model, ThiaError, ThiaInfo, ThiaQuery, ThiaPlannerCfg, ThiaPlanStats, lib, planner_cfg, plan_from_flags,
+from .binding import (Model, ThiaError, ThiaInfo, ThiaQuery, ThiaPlannerCfg, ThiaPlanStats, lib, planner_cfg, plan_from_flags, metrics_from_counts,
                       EXPORTS, TAPS, KERNEL_CLASSES, LIB_PATH)
 
 

@@ -25,7 +25,7 @@ KERNEL_CLASSES = ["stem", "pool", "conv", "fc", "topk", "nms", "roialign", "post
 EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_microbatch", "thia_get_info",
            "thia_detect_chunk", "thia_detect_all_exits", "thia_run_plan", "thia_run_chunks",
            "thia_planner_defaults", "thia_eval_predicate", "thia_plan_from_flags", "thia_plan_query",
-           "thia_set_estimator", "thia_estimate_exit", "thia_last_error", "thia_set_debug", "thia_debug_tap",
+           "thia_set_estimator", "thia_estimate_exit", "thia_answer_counts", "thia_metrics_from_counts", "thia_last_error", "thia_set_debug", "thia_debug_tap",
            "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
            "thia_op_rpn_proposals", "thia_op_nms", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
            "thia_op_stem", "thia_op_bottleneck", "thia_set_fusion"]
@@ -89,6 +89,9 @@ def lib():
                                   C.POINTER(ThiaPlanStats), vp]
     L.thia_set_estimator.argtypes = [vp, i32, vp, vp, vp, vp]
     L.thia_estimate_exit.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
+    L.thia_answer_counts.argtypes = [vp, vp, vp, i32, vp]
+    L.thia_metrics_from_counts.argtypes = [vp, vp]
+    L.thia_metrics_from_counts.restype = None
     L.thia_last_error.argtypes = [vp]
     L.thia_last_error.restype = C.c_char_p
     L.thia_set_debug.argtypes = [vp, i32]
@@ -146,6 +149,14 @@ def plan_from_flags(flags, cfg=None):
     if rc:
         raise ThiaError(rc, "thia_plan_from_flags")
     return _plan_result(bufs, stats, ev, n)
+
+
+def metrics_from_counts(counts):
+    """thia_metrics_from_counts: (TP, FP, FN) -> (precision, recall, F-1)."""
+    c = np.ascontiguousarray(counts, dtype=np.int32)
+    out = np.zeros(3, np.float64)
+    lib().thia_metrics_from_counts(c.ctypes.data, out.ctypes.data)
+    return tuple(float(x) for x in out)
 
 
 def _ptr(t):
@@ -262,6 +273,15 @@ class Model:
         q = ThiaQuery(label, min_count, min_score)
         self._check(lib().thia_eval_predicate(self._h, _ptr(labels), _ptr(scores), rows, C.byref(q), _ptr(flags)))
         return flags
+
+    def answer_counts(self, answers, reference):
+        """(TP, FP, FN) of answers against reference answers (cuda uint8 [n] each), as a device int32 [3] tensor."""
+        _dev(answers, torch.uint8)
+        _dev(reference, torch.uint8)
+        assert answers.shape == reference.shape
+        counts = torch.empty(3, dtype=torch.int32, device=self.device)
+        self._check(lib().thia_answer_counts(self._h, _ptr(answers), _ptr(reference), answers.numel(), _ptr(counts)))
+        return counts
 
     def set_estimator(self, w1, b1, w2, b2):
         """Two-layer exit estimator: w1 [hidden, C_last], b1 [hidden], w2 [n_exits, hidden], b2 [n_exits] (host); None removes it."""

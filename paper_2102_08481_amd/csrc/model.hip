@@ -934,6 +934,21 @@ int thia_eval_predicate(thia_model* m, const int32_t* labels, const float* score
     return THIA_OK;
 }
 
+int thia_answer_counts(thia_model* m, const uint8_t* answers, const uint8_t* reference, int n, int32_t* counts) {
+    if (!m) return THIA_E_BADARG;
+    if (n < 0 || !counts || (n > 0 && (!answers || !reference))) return fail(m, THIA_E_BADARG, "bad metric arguments");
+    HIP_TRY(m, launch_answer_counts(answers, reference, n, counts, m->stream));
+    return THIA_OK;
+}
+
+void thia_metrics_from_counts(const int32_t* c, double* prf) {
+    if (!c || !prf) return;
+    const double tp = c[0], fp = c[1], fn = c[2];
+    prf[0] = tp + fp == 0 ? 1.0 : tp / (tp + fp);
+    prf[1] = tp + fn == 0 ? 1.0 : tp / (tp + fn);
+    prf[2] = prf[0] + prf[1] == 0 ? 0.0 : 2 * prf[0] * prf[1] / (prf[0] + prf[1]);
+}
+
 int thia_set_estimator(thia_model* m, int hidden, const float* w1, const float* b1, const float* w2, const float* b2) {
     if (!m) return THIA_E_BADARG;
     if (hidden < 0 || (hidden > 0 && (!w1 || !b1 || !w2 || !b2))) return fail(m, THIA_E_BADARG, "bad estimator arguments");

@@ -26,6 +26,22 @@ __global__ void count_predicate_kernel(const int32_t* __restrict__ labels, const
     flags[r] = c >= min_count ? 1 : 0;
 }
 
+// TP, FP, FN of frame answers against the reference answers (Sec. 6.1).  One block; integer sums, so the order is immaterial.
+__global__ void __launch_bounds__(1024) answer_counts_kernel(const uint8_t* __restrict__ ans, const uint8_t* __restrict__ ref, long n,
+                                                             int32_t* __restrict__ counts) {
+    __shared__ int s[3];
+    if (threadIdx.x < 3) s[threadIdx.x] = 0;
+    __syncthreads();
+    int tp = 0, fp = 0, fn = 0;
+    for (long i = threadIdx.x; i < n; i += 1024) {
+        const bool a = ans[i] != 0, r = ref[i] != 0;
+        tp += (a && r) ? 1 : 0; fp += (a && !r) ? 1 : 0; fn += (!a && r) ? 1 : 0;
+    }
+    atomicAdd(&s[0], tp); atomicAdd(&s[1], fp); atomicAdd(&s[2], fn);
+    __syncthreads();
+    if (threadIdx.x < 3) counts[threadIdx.x] = s[threadIdx.x];
+}
+
 // Mean over the positions of an NHWC map, one thread per channel: feat [n][HW][C] -> pooled [n][C].
 template <typename T>
 __global__ void spatial_mean_kernel(const T* __restrict__ feat, int HW, int C, float* __restrict__ pooled) {
@@ -88,6 +104,11 @@ hipError_t launch_count_predicate(const int32_t* labels, const float* scores, lo
     const long blocks = (rows + threads - 1) / threads;
     hipLaunchKernelGGL(count_predicate_kernel, dim3((unsigned)blocks), dim3(threads), 0, s, labels, scores, rows, D, label, min_count,
                        min_score, flags);
+    return hipGetLastError();
+}
+
+hipError_t launch_answer_counts(const uint8_t* ans, const uint8_t* ref, long n, int32_t* counts, hipStream_t s) {
+    hipLaunchKernelGGL(answer_counts_kernel, dim3(1), dim3(1024), 0, s, ans, ref, n, counts);
     return hipGetLastError();
 }
 

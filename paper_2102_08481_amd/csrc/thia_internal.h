@@ -142,6 +142,8 @@ hipError_t launch_fill_empty(int n, int D, float* out_boxes, float* out_scores, 
 // flags[r] = (number of slots d of row r with labels[r][d] == label and scores[r][d] >= min_score) >= min_count
 hipError_t launch_count_predicate(const int32_t* labels, const float* scores, long rows, int D, int label, int min_count,
                                   float min_score, uint8_t* flags, hipStream_t s);
+// counts[0..2] = TP, FP, FN of answers against reference answers (both uint8 [n], non-zero = positive)
+hipError_t launch_answer_counts(const uint8_t* ans, const uint8_t* ref, long n, int32_t* counts, hipStream_t s);
 // Exit estimator (Sec. 5.3) on NHWC last-stage features [n][HW][C]: pooled scratch [n][C]; w1t = W1 transposed [C][hid];
 // C + hid + E floats of LDS (the caller keeps that within 64 KB); opt int32 [n] in 1..E, logits [n][E] or nullptr.
 hipError_t launch_estimator(const void* feat, int n, int HW, int C, int precision, float* pooled, int hid, int E, const float* w1t,

@@ -28,6 +28,18 @@ def test_predicate_kernel_is_bit_exact():
             assert np.array_equal(got, P.count_predicate(labels, scores, label, t, s)), (rows, label, t, s)
 
 
+def test_answer_counts_are_exact():
+    from paper_2102_08481_amd import metrics_from_counts
+    m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
+    rng = np.random.default_rng(4)
+    for n in (0, 1, 1023, 1024, 50001):
+        a, r = (rng.random(n) < 0.4).astype(np.uint8), (rng.random(n) < 0.6).astype(np.uint8)
+        c = m.answer_counts(to_dev(a), to_dev(r)).cpu().numpy()
+        o = P.answer_metrics(a, r)
+        assert tuple(int(v) for v in c) == o[:3], n
+        assert metrics_from_counts(c) == pytest.approx(o[3:], abs=0, rel=1e-15)
+
+
 def test_chunks_of_unequal_length_match_stand_alone_calls():
     m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
     frames = to_dev(make_frames(SceneSpec(160, 224, 20, 4, 10, 10, 90), 43))

@@ -4,7 +4,7 @@ from fractions import Fraction
 
 import numpy as np
 import pytest
-from sklearn.metrics import precision_score, recall_score
+from sklearn.metrics import confusion_matrix, f1_score, precision_score, recall_score
 
 from oracle import planner as P
 
@@ -45,6 +45,20 @@ def test_precision_recall_match_the_library_routine():
         pr, rc = P.precision_recall(pred, ref)
         assert pr == pytest.approx(precision_score(ref, pred, zero_division=1.0))
         assert rc == pytest.approx(recall_score(ref, pred, zero_division=1.0))
+
+
+def test_answer_metrics_match_the_library_routines():
+    rng = np.random.default_rng(8)
+    for _ in range(200):
+        k = int(rng.integers(1, 60))
+        pred, ref = rng.random(k) < rng.random(), rng.random(k) < rng.random()
+        tp, fp, fn, pr, rc, f1 = P.answer_metrics(pred, ref)
+        tn_, fp_, fn_, tp_ = confusion_matrix(ref, pred, labels=[False, True]).ravel()
+        assert (tp, fp, fn) == (tp_, fp_, fn_)
+        if tp + fp > 0 and tp + fn > 0:                     # where nothing is empty the conventions do not matter
+            assert f1 == pytest.approx(f1_score(ref, pred, zero_division=0.0))
+    assert P.answer_metrics([0, 0], [0, 0])[3:] == (1.0, 1.0, 1.0)
+    assert P.answer_metrics([1, 0], [0, 1])[3:] == (0.0, 0.0, 0.0)
 
 
 def test_pick_best_ep_is_the_fastest_exit_meeting_both_constraints():

@@ -84,3 +84,15 @@ def test_estimation_based_planning_through_the_answer_table(seed):
     plan_l, st, ev = plan_from_flags(implied, planner_cfg(**kw))
     assert plan_l == plan_o
     assert np.flatnonzero(ev).tolist() == sorted(pl.evaluated) and st["samples_reused"] == pl.reused
+
+
+def test_metrics_from_counts_equal_the_oracle():
+    from paper_2102_08481_amd import metrics_from_counts
+    rng = np.random.default_rng(4)
+    cases = [(0, 0, 0), (5, 0, 0), (0, 3, 0), (0, 0, 2), (0, 3, 2)] + [tuple(int(v) for v in rng.integers(0, 50, 3)) for _ in range(50)]
+    for tp, fp, fn in cases:
+        pred = np.r_[np.ones(tp + fp, bool), np.zeros(fn, bool)]
+        ref = np.r_[np.ones(tp, bool), np.zeros(fp, bool), np.ones(fn, bool)]
+        o = P.answer_metrics(pred, ref)
+        assert o[:3] == (tp, fp, fn)
+        assert metrics_from_counts((tp, fp, fn)) == pytest.approx(o[3:], abs=0, rel=1e-15)
