@@ -96,6 +96,35 @@ def test_mini_bf16_all_exits(ep):
     _check_detections(gb.cpu().numpy(), gs.cpu().numpy(), gl.cpu().numpy(), r16, min_frac=0.95)
 
 
+@pytest.mark.parametrize("precision,ep", [(0, 1), (0, 3), (0, 4), (1, 2), (1, 4)])
+def test_exit_units_sized_to_the_stage_without_lateral(precision, ep):
+    """Table 4's layer configuration: the first layer of each exit's RPN and ROI unit is sized to the stage's own
+    channel count (256 / 512 / 1024 / 2048), with no 1x1 lateral in front.  Continuous tensors against the oracle,
+    every discrete step re-derived by the oracle from the GPU's own upstream tensors."""
+    spec = ModelSpec(precision=precision, blocks=(1, 1, 1, 1), has_lateral=0, fc_dim=128, pre_nms=300, post_nms=100, n_classes=5)
+    m, blob = gpu_model(spec, 0xBEEF + 53)
+    H, W, n = 160, 192, 2
+    frames = make_frames(SceneSpec(H, W, n, 4, 10, 10, 90), 61 + ep)
+    m.set_debug(True)
+    gb, gs, gl = m.detect_chunk(to_dev(frames), ep)
+    torch.cuda.synchronize()
+    orc = oracle.Model(blob)
+    Ck, Hk, Wk, _ = orc.exit_shape(ep, H, W)
+    assert Ck == 256 << (ep - 1)
+    ref = orc.detect(frames, ep, taps=["feat", "head_feat", "rpn_logits", "rpn_deltas"])
+    assert ref["head_feat"].shape[1] == Ck                      # the units read the stage tensor itself
+    tol = TOL_BF16 if precision else TOL_F32
+    r32 = oracle.Model(blob, precision=0).detect(frames, ep, taps=["rpn_logits", "rpn_deltas"]) if precision else ref
+    assert relerr(m.tap("rpn_logits").reshape(r32["rpn_logits"].shape), r32["rpn_logits"]) <= tol
+    assert relerr(m.tap("rpn_deltas").reshape(r32["rpn_deltas"].shape), r32["rpn_deltas"]) <= tol
+    for f in range(n):
+        chain_check(m, blob, spec, H, W, ep, n, f, gb, gs, gl, step_tol=2.0 ** -7 if precision else TOL_F32)
+    m.set_debug(False)
+    ab, as_, al = m.detect_all_exits(to_dev(frames))
+    torch.cuda.synchronize()
+    assert torch.equal(ab[ep - 1], gb) and torch.equal(as_[ep - 1], gs) and torch.equal(al[ep - 1], gl)
+
+
 def test_microbatch_and_repeat_are_bit_identical():
     m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
     frames = to_dev(make_frames(SceneSpec(160, 224, 7, 4, 10, 10, 90), 41))
