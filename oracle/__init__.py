@@ -193,6 +193,7 @@ class Model:
         self.pre, self.post, self.P = int(hi[25]), int(hi[26]), int(hi[28])
         self.Kc, self.D = int(hi[31]), int(hi[34])
         self.precision = int(hi[2]) if precision < 0 else precision
+        self.stem_exit = 1 if hi[38] else 0
 
     def close(self):
         if self._h:
@@ -223,8 +224,8 @@ class Model:
         if not stages:
             return out
         st = []
-        for s in range(ep):
-            Cs, Hs, Ws, _ = self.exit_shape(s + 1, H, W)
+        for s in range(ep - self.stem_exit):
+            Cs, Hs, Ws, _ = self.exit_shape(s + 1 + self.stem_exit, H, W)
             st.append(np.ctypeslib.as_array(so[s], shape=(n, Cs, Hs, Ws)).copy())
             lib().free(so[s])
         return out, st

@@ -40,6 +40,7 @@
 #define ORC_MAGIC 0x41494854
 #define ORC_HEADER_BYTES 256
 #define ORC_MAX_STAGE 4
+#define ORC_MAX_EXIT 5
 
 typedef struct {
     const float *w, *b;
@@ -69,7 +70,10 @@ typedef struct orc_model {
     float *store;             /* private copy of all tensors */
     orc_layer stem;
     orc_block *blk[ORC_MAX_STAGE];
-    orc_exit ex[ORC_MAX_STAGE];
+    orc_exit ex[ORC_MAX_EXIT];
+    /* 1: exit 1 reads the pooled stem output and exit k >= 2 reads conv(k)_x (the paper's five exits, Sec. 4.2,
+     * Table 4: EP-1 on the 64-channel stage); 0: exit k reads conv(k+1)_x */
+    int stem_exit;
 } orc_model;
 
 /* ---------------------------------------------------------------- bf16 (RB) */
@@ -119,7 +123,8 @@ orc_model *orc_load(const void *blob, size_t nbytes, int precision_override) {
     for (int i = 0; i < 4; ++i) m->blocks[i] = h[4 + i];
     m->stem_ch = h[8]; m->has_lateral = h[9]; m->head_ch = h[10];
     m->n_sizes = h[11]; m->n_ratios = h[12];
-    if (m->n_exits < 1 || m->n_exits > 4 || m->n_sizes < 1 || m->n_sizes > 8 || m->n_ratios < 1 || m->n_ratios > 4) { free(m); return NULL; }
+    m->stem_exit = h[38] ? 1 : 0;
+    if (m->n_exits < 1 || m->n_exits > 4 + m->stem_exit || m->n_sizes < 1 || m->n_sizes > 8 || m->n_ratios < 1 || m->n_ratios > 4) { free(m); return NULL; }
     for (int i = 0; i < 8; ++i) m->sizes[i] = hf[13 + i];
     for (int i = 0; i < 4; ++i) m->ratios[i] = hf[21 + i];
     m->pre_nms = h[25]; m->post_nms = h[26]; m->rpn_nms_thr = hf[27];
@@ -133,7 +138,7 @@ orc_model *orc_load(const void *blob, size_t nbytes, int precision_override) {
     const float *p = m->store, *end = m->store + nfl;
     int ok = take_layer(&m->stem, m->stem_ch, 3, 7, &p, end);
     int cin = m->stem_ch;
-    for (int s = 0; s < m->n_exits && ok; ++s) {
+    for (int s = 0; s < m->n_exits - m->stem_exit && ok; ++s) {
         int w = m->base_width << s;
         m->blk[s] = (orc_block *)calloc((size_t)m->blocks[s] + 1, sizeof(orc_block));
         for (int b = 0; b < m->blocks[s] && ok; ++b) {
@@ -150,7 +155,8 @@ orc_model *orc_load(const void *blob, size_t nbytes, int precision_override) {
     int A = m->n_sizes * m->n_ratios;
     for (int e = 0; e < m->n_exits && ok; ++e) {
         orc_exit *E = &m->ex[e];
-        int ce = 4 * (m->base_width << e), hc = ce;
+        int st = e - m->stem_exit; /* stage the exit reads; -1 = the pooled stem output */
+        int ce = st < 0 ? m->stem_ch : 4 * (m->base_width << st), hc = ce;
         if (m->has_lateral) { ok = ok && take_layer(&E->lateral, m->head_ch, ce, 1, &p, end); hc = m->head_ch; }
         ok = ok && take_layer(&E->rpn_conv, hc, hc, 3, &p, end);
         ok = ok && take_layer(&E->rpn_obj, A, hc, 1, &p, end);
@@ -173,8 +179,9 @@ int orc_num_threads(void) { return omp_get_max_threads(); }
 static int conv_out(int n, int k, int s, int p) { return (n + 2 * p - k) / s + 1; }
 void orc_exit_shape(const orc_model *m, int ep, int H, int W, int *C, int *Hk, int *Wk, int *stride) {
     int h = conv_out(conv_out(H, 7, 2, 3), 3, 2, 1), w = conv_out(conv_out(W, 7, 2, 3), 3, 2, 1);
-    for (int s = 1; s < ep; ++s) { h = conv_out(h, 3, 2, 1); w = conv_out(w, 3, 2, 1); }
-    *C = 4 * (m->base_width << (ep - 1)); *Hk = h; *Wk = w; *stride = 4 << (ep - 1);
+    int st = ep - m->stem_exit; /* bottleneck stages in front of the exit; 0 = the pooled stem output */
+    for (int s = 1; s < st; ++s) { h = conv_out(h, 3, 2, 1); w = conv_out(w, 3, 2, 1); }
+    *C = st == 0 ? m->stem_ch : 4 * (m->base_width << (st - 1)); *Hk = h; *Wk = w; *stride = st == 0 ? 4 : 4 << (st - 1);
 }
 
 /* ------------------------------------------------------------------- steps */
@@ -489,7 +496,8 @@ static void run_layer(const orc_layer *L, const float *in, int N, int H, int W, 
  * bottleneck stages conv2_x .. conv(ep+1)_x and nothing after them (early
  * inference: later stages are never evaluated).  Returns a malloc'd [n,C,Hk,Wk].
  * If stage_out != NULL, stage_out[s] receives a malloc'd copy of stage s+1's
- * output for every s < ep (used to check the prefix property).
+ * output for every stage run (used to check the prefix property).  With a stem
+ * exit, exit 1 stops after the max-pool and exit k runs k - 1 stages.
  */
 float *orc_backbone(const orc_model *m, const uint8_t *frames, int n, int H, int W, int ep, float **stage_out) {
     const int bf = m->precision;
@@ -504,7 +512,7 @@ float *orc_backbone(const orc_model *m, const uint8_t *frames, int n, int H, int
     orc_maxpool3x3s2(y, n, m->stem_ch, h, w, x);
     free(y);
     h = hp; w = wp;
-    for (int s = 0; s < ep; ++s) {
+    for (int s = 0; s < ep - m->stem_exit; ++s) {
         for (int b = 0; b < m->blocks[s]; ++b) {
             const orc_block *B = &m->blk[s][b];
             int ho = conv_out(h, 3, B->stride, 1), wo = conv_out(w, 3, B->stride, 1);

@@ -11,6 +11,7 @@ import torch.nn.functional as F
 
 import oracle
 from thia_synth import ModelSpec, SceneSpec, make_blob, make_frames, split_blob, CONFIGS
+from thia_synth.weights import tensor_list
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -231,3 +232,49 @@ def test_bad_blob_and_bad_exit():
     m = oracle.Model(blob)
     with pytest.raises(ValueError):
         m.detect(np.zeros((1, 3, 32, 32), np.uint8), 5)
+
+
+STEM5 = ModelSpec(precision=0, n_exits=5, stem_exit=1, blocks=(1, 1, 1, 1), has_lateral=0, fc_dim=16, pre_nms=60, post_nms=20,
+                  n_classes=4, base_width=8, stem_ch=8, sizes=(16.0, 32.0), ratios=(1.0,))
+
+
+def test_five_exit_variant_with_an_exit_on_the_stem_stage():
+    """The paper's case study has five exits, the first on the 64-channel stage in front of the bottleneck stages and
+    each unit's first layer sized to its stage (Sec. 4.2, Table 4).  With the stem-exit flag exit 1 reads the pooled
+    stem output at stride 4, exit k >= 2 reads what exit k - 1 of the four-exit numbering reads, and the same
+    weights give the same detections there."""
+    blob5 = make_blob(STEM5, 5)
+    frames = make_frames(replace(MINI_SCENE, n_frames=2), 81)
+    H, W = frames.shape[2:]
+    m5 = oracle.Model(blob5)
+    assert [m5.exit_shape(k, H, W)[0] for k in range(1, 6)] == [8, 32, 64, 128, 256]
+    assert [m5.exit_shape(k, H, W)[3] for k in range(1, 6)] == [4, 4, 8, 16, 32]
+    assert m5.exit_shape(1, H, W)[1:3] == m5.exit_shape(2, H, W)[1:3]
+    # exit 1's tensor is the max-pooled stem output, computed by the step functions
+    w = split_blob(STEM5, blob5)
+    x = oracle.maxpool3x3s2(oracle.conv2d(oracle.normalize(frames), w["stem.w"], w["stem.b"], stride=2, pad=3, relu=True))
+    r1 = m5.detect(frames, 1, taps=["feat", "head_feat"])
+    assert np.array_equal(r1["feat"], x) and np.array_equal(r1["head_feat"], x)
+    assert (r1["labels"][:, 0] >= 1).all()
+    # the same tensors under the four-exit numbering: drop exit 1's unit from the blob
+    spec4 = replace(STEM5, n_exits=4, stem_exit=0)
+    names4 = [n for n, _, _ in tensor_list(spec4)]
+    w4 = {n: w[n if not n.startswith("e") else f"e{int(n[1]) + 1}{n[2:]}"] for n in names4}
+    blob4 = make_blob(spec4, 5)
+    for n, v in split_blob(spec4, blob4).items():
+        v[...] = w4[n]
+    m4 = oracle.Model(blob4)
+    for k in (1, 2, 3, 4):
+        a, b = m4.detect(frames, k), m5.detect(frames, k + 1)
+        for key in ("boxes", "scores", "labels"):
+            assert np.array_equal(a[key], b[key]), (k, key)
+    # prefix property with the shifted numbering, and bounds
+    full, stages = m5.backbone(frames, 5, stages=True)
+    assert len(stages) == 4 and np.array_equal(full, stages[3])
+    assert np.array_equal(m5.backbone(frames, 3), stages[1])
+    with pytest.raises(ValueError):
+        m5.detect(frames, 6)
+    bad = blob5.copy()
+    bad[:256].view(np.int32)[38] = 0                                   # five exits need the stem exit
+    with pytest.raises(ValueError):
+        oracle.Model(bad)

@@ -9,7 +9,7 @@ describes data; it holds no detector arithmetic.
 Header words (i = int32, f = float32):
   0 i magic 0x41494854 ("THIA")     1 i version (1)
   2 i precision: 0 fp32, 1 bf16 storage with fp32 accumulation
-  3 i n_exits (1..4)                4-7 i bottleneck blocks in conv2_x..conv5_x
+  3 i n_exits (1..4, or 1..5 with a stem exit)   4-7 i bottleneck blocks in conv2_x..conv5_x
   8 i stem channels                 9 i has_lateral (0/1)
  10 i head channels (lateral / RPN width, ROI feature channels)
  11 i n_sizes  12 i n_ratios        13-20 f anchor sizes (px)   21-24 f ratios h/w
@@ -19,7 +19,10 @@ Header words (i = int32, f = float32):
  31 i classes incl. background      32 f score threshold
  33 f detection NMS IoU threshold   34 i max detections per frame D
  35 f pixel mean                    36 f pixel std
- 37 i bottleneck base width (64)    38-63 reserved, zero
+ 37 i bottleneck base width (64)
+ 38 i stem exit (0/1): 1 = exit 1 reads the pooled stem output (stem channels, stride 4) and exit k >= 2 reads
+      conv(k)_x, as in the paper's five-exit case study; 0 = exit k reads conv(k+1)_x
+ 39-63 reserved, zero
 """
 from dataclasses import dataclass, field, replace
 import struct
@@ -52,17 +55,25 @@ class ModelSpec:
     mean: float = 114.0
     std: float = 58.0
     base_width: int = 64
+    stem_exit: int = 0                 # 1: exit 1 sits on the pooled stem output (paper's EP-1, Table 4)
+
+    @property
+    def n_stages(self):
+        """Bottleneck stages the deepest exit needs."""
+        return self.n_exits - self.stem_exit
 
     @property
     def n_anchors(self):
         return len(self.sizes) * len(self.ratios)
 
     def stage_channels(self, k):
-        """Output channels of exit k (1-based): 256, 512, 1024, 2048."""
-        return 4 * self.base_width * (1 << (k - 1))
+        """Channels of the tensor exit k (1-based) reads: 256, 512, 1024, 2048 (with a stem exit: 64 first)."""
+        k -= self.stem_exit
+        return self.stem_ch if k == 0 else 4 * self.base_width * (1 << (k - 1))
 
     def stride(self, k):
-        return 4 << (k - 1)
+        k -= self.stem_exit
+        return 4 if k == 0 else 4 << (k - 1)
 
     def header(self):
         w = [0] * 64
@@ -79,7 +90,7 @@ class ModelSpec:
         w[25], w[26], w[27] = self.pre_nms, self.post_nms, f(self.rpn_nms_thr)
         w[28], w[29], w[30], w[31] = self.pool, self.sampling, self.fc_dim, self.n_classes
         w[32], w[33], w[34] = f(self.score_thr), f(self.det_nms_thr), self.max_det
-        w[35], w[36], w[37] = f(self.mean), f(self.std), self.base_width
+        w[35], w[36], w[37], w[38] = f(self.mean), f(self.std), self.base_width, self.stem_exit
         return struct.pack("<64i", *w)
 
 

@@ -4,7 +4,7 @@ Tensor order (conv weights [Cout, Cin, kh, kw]; FC weights [out, in]; every
 weight is followed by its bias [Cout]):
 
   stem 7x7
-  for stage s = 1 .. n_exits, block b = 0 .. blocks[s-1]-1:
+  for stage s = 1 .. n_stages (= n_exits, or n_exits - 1 with a stem exit), block b = 0 .. blocks[s-1]-1:
       conv1 1x1 (Cin -> w), conv2 3x3 (w -> w), conv3 1x1 (w -> 4w),
       and for b == 0 only: shortcut 1x1 (Cin -> 4w)          with w = base_width * 2**(s-1)
   for exit e = 1 .. n_exits:
@@ -40,7 +40,7 @@ def tensor_list(spec: ModelSpec):
 
     conv("stem", spec.stem_ch, 3, 7)
     cin = spec.stem_ch
-    for s in range(1, spec.n_exits + 1):
+    for s in range(1, spec.n_stages + 1):
         w = spec.base_width << (s - 1)
         for b in range(spec.blocks[s - 1]):
             p = f"s{s}.b{b}"
