@@ -22,7 +22,10 @@
  *  - Return value: THIA_OK (0) or a negative THIA_E_* code; thia_last_error() gives a
  *    message.  On an argument error nothing is enqueued and outputs are untouched.
  *  - Exits are numbered 1..n_exits (exit k reads the output of backbone stage
- *    conv(k+1)_x, stride 4 * 2^(k-1)); 0 means "skip the chunk".
+ *    conv(k+1)_x, stride 4 * 2^(k-1)); 0 means "skip the chunk".  A model whose header
+ *    sets the stem-exit flag has up to five exits as in the paper's case study (Sec. 4.2,
+ *    Table 4): exit 1 reads the pooled stem output (64 channels, stride 4) and exit
+ *    k >= 2 reads conv(k)_x.
  *  - Detections: at most D = thia_info.max_det per frame, sorted by descending score.
  *    out_boxes [n,D,4] = (x1,y1,x2,y2) in pixels, out_scores [n,D], out_labels [n,D]
  *    = foreground class 1..n_classes-1.  Unused slots: box 0, score 0, label -1.
@@ -72,7 +75,8 @@ typedef struct thia_info {
  * fp32 tensors, conv weights [Cout,Cin,kh,kw], FC weights [out,in] with FC1's input
  * index = c*pool*pool + ph*pool + pw, each weight followed by its bias; order: stem,
  * stages, then per exit lateral (optional), rpn.conv, rpn.obj, rpn.delta, fc1, fc2,
- * cls, box.  n_exits must equal the header's.  The blob may be freed after the call.
+ * cls, box.  n_exits must equal the header's (1..4, or 1..5 with the stem-exit flag,
+ * header word 38).  The blob may be freed after the call.
  * Blocking (allocates and uploads).  All channel counts except the 3 input channels
  * and the predictor outputs must be multiples of 64.
  */

@@ -65,6 +65,8 @@ struct Workspace {
 
 struct thia_model {
     int precision = 0, n_exits = 0, blocks_n[4] = {0, 0, 0, 0}, stem_ch = 64, has_lateral = 0, head_ch = 256;
+    // 1: exit 1 reads the pooled stem output and exit k >= 2 reads conv(k)_x (five exits, Sec. 4.2 / Table 4); 0: exit k reads conv(k+1)_x
+    int stem_exit = 0;
     AnchorSpec anc{};
     int pre = 0, post = 0, pool = 7, sampling = 2, fc_dim = 0, Kc = 0, D = 0, base_width = 64;
     float rpn_thr = 0.7f, score_thr = 0.05f, det_thr = 0.5f, mean = 0.f, stdv = 1.f;
@@ -73,7 +75,7 @@ struct thia_model {
     bf16_t* stem_wk = nullptr;  // device bf16 [64][22][8] (matrix-core path)
     float* stem_b = nullptr;
     std::vector<Block> stage[4];
-    ExitUnit ex[4];
+    ExitUnit ex[5];
     char* warena = nullptr;
     hipStream_t stream = nullptr;
     int user_mb = 0;
@@ -193,12 +195,19 @@ void free_layer(Layer& L) {
 
 // ---------------------------------------------------------------- geometry
 struct ExitGeom { int C, Hk, Wk, stride; };
+// Bottleneck stages in front of exit ep (0 = the exit reads the pooled stem output).
+int exit_stages(const thia_model* m, int ep) { return ep - m->stem_exit; }
+int exit_channels(const thia_model* m, int ep) {
+    const int st = exit_stages(m, ep);
+    return st == 0 ? m->stem_ch : 4 * (m->base_width << (st - 1));
+}
 ExitGeom exit_geom(const thia_model* m, int ep, int H, int W) {
     int h = conv_out(conv_out(H, 7, 2, 3), 3, 2, 1), w = conv_out(conv_out(W, 7, 2, 3), 3, 2, 1);
-    for (int s = 1; s < ep; ++s) { h = conv_out(h, 3, 2, 1); w = conv_out(w, 3, 2, 1); }
-    return {4 * (m->base_width << (ep - 1)), h, w, 4 << (ep - 1)};
+    const int st = exit_stages(m, ep);
+    for (int s = 1; s < st; ++s) { h = conv_out(h, 3, 2, 1); w = conv_out(w, 3, 2, 1); }
+    return {exit_channels(m, ep), h, w, st == 0 ? 4 : 4 << (st - 1)};
 }
-int head_channels(const thia_model* m, int ep) { return m->has_lateral ? m->head_ch : 4 * (m->base_width << (ep - 1)); }
+int head_channels(const thia_model* m, int ep) { return m->has_lateral ? m->head_ch : exit_channels(m, ep); }
 
 int next_pow2(int v) {
     int p = 1;
@@ -211,7 +220,7 @@ size_t max_act_elems(const thia_model* m, int H, int W) {
     int h = conv_out(H, 7, 2, 3), w = conv_out(W, 7, 2, 3);
     size_t mx = (size_t)h * w * m->stem_ch;
     h = conv_out(h, 3, 2, 1); w = conv_out(w, 3, 2, 1);
-    for (int s = 0; s < m->n_exits; ++s) {
+    for (int s = 0; s < exit_stages(m, m->n_exits); ++s) {
         const int width = m->base_width << s;
         if (s > 0) {
             mx = std::max(mx, (size_t)h * w * width);  // conv1 output before the strided 3x3
@@ -446,7 +455,7 @@ int run_stage(thia_model* m, int s, int nb, Trunk& t) {
 int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int ep, const void** feat) {
     Trunk t;
     TRY(run_stem(m, frames, nb, H, W, t));
-    for (int s = 0; s < ep; ++s) TRY(run_stage(m, s, nb, t));
+    for (int s = 0; s < exit_stages(m, ep); ++s) TRY(run_stage(m, s, nb, t));
     *feat = t.x;
     return THIA_OK;
 }
@@ -584,11 +593,11 @@ int detect_frames_all_exits(thia_model* m, const uint8_t* frames, int n, int H, 
         const int nb = std::min(mb, n - f0);
         Trunk t;
         rc = run_stem(m, frames + (size_t)f0 * 3 * H * W, nb, H, W, t);
-        for (int s = 0; s < m->n_exits && rc == THIA_OK; ++s) {
-            rc = run_stage(m, s, nb, t);
+        for (int e = 1; e <= m->n_exits && rc == THIA_OK; ++e) {
+            if (exit_stages(m, e) > 0) rc = run_stage(m, exit_stages(m, e) - 1, nb, t);
             if (rc != THIA_OK) break;
-            const size_t o = (size_t)s * n + f0;
-            rc = run_heads(m, t.x, f0, nb, H, W, s + 1, ob + o * D * 4, os + o * D, ol + o * D);
+            const size_t o = (size_t)(e - 1) * n + f0;
+            rc = run_heads(m, t.x, f0, nb, H, W, e, ob + o * D * 4, os + o * D, ol + o * D);
         }
     }
     m->debug = debug;
@@ -620,7 +629,7 @@ int estimate_frames(thia_model* m, const uint8_t* frames, int n, int H, int W, i
         const int nb = std::min(mb, n - f0);
         Trunk t;
         rc = run_stem(m, frames + (size_t)f0 * 3 * H * W, nb, H, W, t);
-        for (int s = 0; s < E && rc == THIA_OK; ++s) rc = run_stage(m, s, nb, t);
+        for (int s = 0; s < exit_stages(m, E) && rc == THIA_OK; ++s) rc = run_stage(m, s, nb, t);
         if (rc != THIA_OK) break;
         {
             Scope sc(m, THIA_K_POST);
@@ -649,12 +658,14 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
     std::memcpy(h, weights, 256);
     std::memcpy(hf, weights, 256);
     if (h[0] != kMagic || h[1] != 1) return THIA_E_BLOB;
-    if (h[3] != n_exits || n_exits < 1 || n_exits > 4) return THIA_E_BLOB;
+    const int stem_exit = h[38] ? 1 : 0;
+    if (h[3] != n_exits || n_exits < 1 || n_exits > 4 + stem_exit) return THIA_E_BLOB;
     thia_model* m = new (std::nothrow) thia_model();
     if (!m) return THIA_E_NOMEM;
     m->precision = h[2];
     m->esz = m->precision ? 2 : 4;
     m->n_exits = n_exits;
+    m->stem_exit = stem_exit;
     for (int i = 0; i < 4; ++i) m->blocks_n[i] = h[4 + i];
     m->stem_ch = h[8]; m->has_lateral = h[9]; m->head_ch = h[10];
     m->anc.n_sizes = h[11]; m->anc.n_ratios = h[12];
@@ -695,7 +706,7 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
         if (hipMemcpy(m->stem_wk, wk.data(), wk.size() * 2, hipMemcpyHostToDevice) != hipSuccess) return bad(THIA_E_HIP);
     }
     int cin = m->stem_ch;
-    for (int s = 0; s < n_exits; ++s) {
+    for (int s = 0; s < n_exits - stem_exit; ++s) {
         const int w = m->base_width << s;
         if (m->blocks_n[s] < 1 || m->blocks_n[s] > 64) return bad(THIA_E_BLOB);
         m->stage[s].resize(m->blocks_n[s]);
@@ -740,7 +751,7 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
     const int A = m->anc.n_sizes * m->anc.n_ratios;
     for (int e = 0; e < n_exits; ++e) {
         ExitUnit& E = m->ex[e];
-        const int ce = 4 * (m->base_width << e);
+        const int ce = exit_channels(m, e + 1);
         int hc = ce, rc = THIA_OK;
         HostLayer lat, rc3, obj, dl, fc1, fc2, cls, box;
         if (m->has_lateral) {
@@ -799,7 +810,7 @@ void thia_free_model(thia_model* m) {
             if (B.f3) (void)hipFree(B.f3);
             B.f1 = B.f2 = B.f3 = nullptr;
         }
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < 5; ++e) {
         ExitUnit& E = m->ex[e];
         free_layer(E.lateral); free_layer(E.rpn_conv); free_layer(E.rpn_head); free_layer(E.fc1); free_layer(E.fc2); free_layer(E.pred);
         if (E.head_f) (void)hipFree(E.head_f);
@@ -952,7 +963,7 @@ void thia_metrics_from_counts(const int32_t* c, double* prf) {
 int thia_set_estimator(thia_model* m, int hidden, const float* w1, const float* b1, const float* w2, const float* b2) {
     if (!m) return THIA_E_BADARG;
     if (hidden < 0 || (hidden > 0 && (!w1 || !b1 || !w2 || !b2))) return fail(m, THIA_E_BADARG, "bad estimator arguments");
-    const int E = m->n_exits, Cl = 4 * (m->base_width << (E - 1));
+    const int E = m->n_exits, Cl = exit_channels(m, E);
     if (hidden > 0 && Cl + hidden + E > 16000) return fail(m, THIA_E_SHAPE, "estimator too wide: channels + hidden + exits must not exceed 16000");
     HIP_TRY(m, hipStreamSynchronize(m->stream));
     free_estimator(m);

@@ -10,6 +10,7 @@ import oracle
 from conftest import get_blob
 from gpu_common import MINI_BF16, MINI_FP32, chain_check, gpu_model, match_fraction, nhwc_to_nchw, relerr, to_dev
 from thia_synth import CONFIGS, ModelSpec, SceneSpec, make_frames
+from paper_2102_08481_amd import ThiaError as ThiaErr
 
 pytestmark = pytest.mark.gpu
 
@@ -123,6 +124,44 @@ def test_exit_units_sized_to_the_stage_without_lateral(precision, ep):
     ab, as_, al = m.detect_all_exits(to_dev(frames))
     torch.cuda.synchronize()
     assert torch.equal(ab[ep - 1], gb) and torch.equal(as_[ep - 1], gs) and torch.equal(al[ep - 1], gl)
+
+
+@pytest.mark.parametrize("precision,lateral", [(0, 0), (1, 0), (1, 1)])
+def test_five_exits_with_an_exit_on_the_stem_stage(precision, lateral):
+    """The paper's five-exit case study (Sec. 4.2, Table 4): exit 1 sits on the 64-channel stage in front of the
+    bottleneck stages.  Exit 1 is checked step by step against the oracle; all five come out of one backbone pass
+    bit-identical to their own calls; exit 5 is the deepest stage."""
+    spec = ModelSpec(precision=precision, n_exits=5, stem_exit=1, blocks=(1, 1, 1, 1), has_lateral=lateral, fc_dim=128,
+                     pre_nms=300, post_nms=100, n_classes=5)
+    m, blob = gpu_model(spec, 0xBEEF + 54 + lateral)
+    assert m.n_exits == 5
+    H, W, n = 160, 192, 2
+    frames = make_frames(SceneSpec(H, W, n, 4, 10, 10, 90), 71)
+    fd = to_dev(frames)
+    orc = oracle.Model(blob)
+    tol = TOL_BF16 if precision else TOL_F32
+    for ep in (1, 5):
+        m.set_debug(True)
+        gb, gs, gl = m.detect_chunk(fd, ep)
+        torch.cuda.synchronize()
+        Ck, Hk, Wk, stride = orc.exit_shape(ep, H, W)
+        assert (Ck, stride) == ((64, 4) if ep == 1 else (2048, 32))
+        r32 = oracle.Model(blob, precision=0).detect(frames, ep, taps=["rpn_logits", "rpn_deltas"])
+        assert relerr(m.tap("rpn_logits").reshape(r32["rpn_logits"].shape), r32["rpn_logits"]) <= tol
+        assert relerr(m.tap("rpn_deltas").reshape(r32["rpn_deltas"].shape), r32["rpn_deltas"]) <= tol
+        for f in range(n):
+            chain_check(m, blob, spec, H, W, ep, n, f, gb, gs, gl, step_tol=2.0 ** -7 if precision else TOL_F32)
+        m.set_debug(False)
+    ab, as_, al = m.detect_all_exits(fd)
+    torch.cuda.synchronize()
+    assert ab.shape[0] == 5
+    for ep in range(1, 6):
+        b, s, l = m.detect_chunk(fd, ep)
+        torch.cuda.synchronize()
+        assert torch.equal(ab[ep - 1], b) and torch.equal(as_[ep - 1], s) and torch.equal(al[ep - 1], l), ep
+        assert (l[:, 0] >= 1).all()
+    with pytest.raises(ThiaErr):
+        m.detect_chunk(fd, 6)
 
 
 def test_microbatch_and_repeat_are_bit_identical():
