@@ -309,7 +309,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
             if (kt + 1 < KT) store_tiles(buf ^ 1, st0);
             if (kt + 2 < KT) load_tiles(kt + 2, st0);
         }
+        // the wavefront that multiplies wins issue arbitration over the SIMD's other wavefront, which is staging
+        // (LDS writes, global loads) at that moment: measured 0.5-1 % on the whole sweep
+        __builtin_amdgcn_s_setprio(3);
         compute(buf);
+        __builtin_amdgcn_s_setprio(0);
         if (!stage_first) {
             if (kt + 1 < KT) store_tiles(buf ^ 1, st0);
             if (kt + 2 < KT) load_tiles(kt + 2, st0);
