@@ -138,6 +138,44 @@ def test_config3_all_exits_in_one_pass_bit_identical_to_the_sweep():
         assert _properties(cfg, ab[ep - 1], as_[ep - 1], al[ep - 1], 540, 960) > 0
 
 
+def test_planner_on_the_config4_video_at_full_size():
+    """The planner with the paper's constants (chunks of at least 100 frames, final rate 0.1, P = R = 0.8) on the
+    256-frame 540x960 video of config 4: the plan equals the oracle planner's on the answers derived from the GPU's
+    own all-exit detections of every frame, and executing it reproduces stand-alone calls chunk by chunk."""
+    from oracle import planner as P
+    from paper_2102_08481_amd import planner_cfg
+    cfg = CONFIGS[4]
+    m, _ = gpu_model(cfg.model, cfg.weight_seed)
+    fd = to_dev(_frames(cfg))
+    n = fd.shape[0]
+    flags = np.zeros((n, 4), bool)
+    ref_l, ref_s = [], []
+    for f0 in range(0, n, 64):
+        b, s, l = m.detect_all_exits(fd[f0:f0 + 64].contiguous())
+        torch.cuda.synchronize()
+        ref_l.append(l.cpu().numpy()); ref_s.append(s.cpu().numpy())
+    L, S = np.concatenate(ref_l, axis=1), np.concatenate(ref_s, axis=1)          # [E, n, D]
+    label = int(np.bincount(L[-1][L[-1] > 0].ravel()).argmax())
+    min_score = float(np.median(S[-1][L[-1] == label]))
+    cnt = ((L[-1] == label) & (S[-1] >= np.float32(min_score))).sum(axis=1)
+    t = max(1, int(np.ceil(np.median(cnt) + 0.5)))
+    flags = P.count_predicate(L, S, label, t, min_score).T
+    assert 0 < flags[:, -1].mean() < 1
+    plan_o, pl = P.plan_from_flags(flags, P.PlannerConfig())
+    plan, st, ev = m.plan_query(fd, label, t, min_score, planner_cfg())
+    assert plan == plan_o and np.flatnonzero(ev).tolist() == sorted(pl.evaluated)
+    assert st["frames_evaluated"] == len(pl.evaluated) <= n // 5 and st["depth"] == pl.depth <= 2
+    b, s, l = m.run_chunks(fd, plan)
+    torch.cuda.synchronize()
+    for a, ln, ep in plan:
+        if ep == 0:
+            assert (l[a:a + ln] == -1).all()
+        else:
+            cb, cs, cl = m.detect_chunk(fd[a:a + ln].contiguous(), ep)
+            torch.cuda.synchronize()
+            assert torch.equal(b[a:a + ln], cb) and torch.equal(s[a:a + ln], cs) and torch.equal(l[a:a + ln], cl)
+
+
 @pytest.mark.parametrize("ep", [1, 2, 3, 4])
 def test_config5_r101_1080p_batch8(ep):
     cfg = CONFIGS[5]
