@@ -14,6 +14,9 @@
 //            wavefront-private LDS transpose so that residual loads and stores are 16 bytes per lane
 //            and cover whole lines of the NHWC tensors.
 // Both intermediates are rounded to bf16 exactly where the layer-by-layer path stores them.
+// Optionally (TAILN > 0) a fourth phase applies the 1x1 layer that reads this block's output - the exit's lateral or
+// the next stage's first 1x1 - to the output tile while it is still on the CU, so that layer's own launch, and its
+// read of the wide tensor, disappear.
 // Weights never pass through LDS: they are pre-packed in MFMA fragment order (one coalesced 1 KiB
 // load per 32-channel x 16-k fragment) and stay in L2.
 #include <type_traits>
@@ -59,9 +62,11 @@ constexpr int NPX = TH * TW;            // 128
 // FIRST = true:  a stage's first block at stride 1: x has WD channels and enters the output through the
 //                projection shortcut; w3f holds [W3 | Ws] along K (2 WD) and b3 the summed biases, so phase 3 is one
 //                contraction over (t2 channels, x channels) with the x operand read from the staging tile.
-template <int WD, bool FIRST>
+// TAILN = 128 or 256 (identity blocks only): z = [relu](Wt y + bt) with TAILN output channels is written to a.z as well.
+template <int WD, bool FIRST, int TAILN = 0>
 __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlockArgs a) {
     static_assert(WD == 64, "work split below is written for 64-channel intermediates");
+    static_assert(TAILN == 0 || (!FIRST && (TAILN == 128 || TAILN == 256)), "tail layer: identity blocks, 128 or 256 outputs");
     constexpr int C4 = 4 * WD;
     constexpr int CIN = FIRST ? WD : C4;
     constexpr int BK = 64;                 // phase-1 K step (channels)
@@ -272,6 +277,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
     // The residual is added in accumulator layout (fp32), the sum is rounded once, and only the bf16 tile goes
     // through the wavefront's LDS region to be re-read as 16-byte runs of 8 channels per lane.
     unsigned char* ep = smem + wv * (32 * EPITCH);
+    u32x2_t ypk[TAILN ? 4 : 1][2][4];   // tail layer: the block's rounded output in accumulator layout
     static_for<0, 4>([&](auto ptc) {
         constexpr int pt = decltype(ptc)::value;
         f32x16_t acc3[2] = {b3t[0], b3t[1]};
@@ -300,6 +306,7 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
                 const float r3 = fmaxf(acc3[i][4 * v + 3] + __uint_as_float(q.y & 0xffff0000u), 0.f);
                 u32x2_t o = {pack2(r0, r1), pack2(r2, r3)};
                 *reinterpret_cast<u32x2_t*>(ep + l32 * EPITCH + (i * 32 + 8 * v + 4 * lh) * 2) = o;
+                if constexpr (TAILN > 0) ypk[pt][i][v] = o;
             }
         __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the region is private to this wavefront
         __builtin_amdgcn_wave_barrier();
@@ -312,6 +319,91 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused_kernel(const FusedBlo
         __builtin_amdgcn_s_waitcnt(0xc07f);
         __builtin_amdgcn_wave_barrier();
     });
+
+    // ------------------------------------------------------------------ phase 4 (optional): z = [relu](Wt y + bt)
+    // The output tile is laid out once more in LDS, now as one row of all 4 WD channels per pixel (the MFMA pixel
+    // operand of a contraction over those channels); wavefront wv computes output channels TAILN / 4 * wv .. of all
+    // 128 pixels with its weight fragments streamed from L2.
+    if constexpr (TAILN > 0) {
+        constexpr int YP = C4 * 2 + 16;            // row pitch of the output tile (bytes)
+        constexpr int NTW = TAILN / 128;           // 32-channel tiles per wavefront
+        constexpr int KS4 = C4 / 16;               // k-steps (16)
+        constexpr int TRING = 8;                   // k-steps of weight fragments in flight
+        constexpr int ZPITCH = NTW * 64 + 16;      // staging row: the wavefront's channels of one pixel + pad (bytes)
+        static_assert(NPX * YP <= NHP * (TP + XP) + NPX * TP, "output tile fits in the block's LDS");
+        static_assert(4 * 32 * ZPITCH <= NPX * YP, "staging fits");
+        unsigned char* Y = smem;
+        const u32x4_t* __restrict__ wtf = reinterpret_cast<const u32x4_t*>(a.wtf) + (size_t)(wv * NTW) * KS4 * 64 + lane;
+        u32x4_t tring[NTW][TRING];
+#pragma unroll
+        for (int i = 0; i < NTW; ++i)
+#pragma unroll
+            for (int k = 0; k < TRING; ++k) tring[i][k] = wtf[(i * KS4 + k) * 64];
+        f32x16_t acc4[NTW][4];
+#pragma unroll
+        for (int i = 0; i < NTW; ++i) {
+            acc4[i][0] = bias_tile(a.bt + (wv * NTW + i) * 32);
+#pragma unroll
+            for (int j = 1; j < 4; ++j) acc4[i][j] = acc4[i][0];
+        }
+        pin_vmem();
+        __syncthreads();   // every wavefront is done with t2 and with its staging region
+#pragma unroll
+        for (int pt = 0; pt < 4; ++pt)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    *reinterpret_cast<u32x2_t*>(Y + (pt * 32 + l32) * YP + (wv * 64 + i * 32 + 8 * v + 4 * lh) * 2) = ypk[pt][i][v];
+        __syncthreads();
+        static_for<0, KS4>([&](auto kc) {
+            constexpr int kk = decltype(kc)::value;
+            u32x4_t wf[NTW];
+#pragma unroll
+            for (int i = 0; i < NTW; ++i) {
+                wf[i] = tring[i][kk % TRING];
+                if (kk + TRING < KS4) tring[i][kk % TRING] = wtf[(i * KS4 + kk + TRING) * 64];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x4_t b = *reinterpret_cast<const u32x4_t*>(Y + (j * 32 + l32) * YP + kk * 32 + lh * 16);
+#pragma unroll
+                for (int i = 0; i < NTW; ++i) mma(acc4[i][j], wf[i], b);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        __syncthreads();   // the output tile is dead: its space becomes the wavefronts' staging regions
+        unsigned char* zp = smem + wv * (32 * ZPITCH);
+        bf16_t* __restrict__ zout = a.z + (size_t)img * a.H * a.W * TAILN;
+        const bool zrelu = a.tail_relu != 0;
+        static_for<0, 4>([&](auto ptc) {
+            constexpr int pt = decltype(ptc)::value;
+#pragma unroll
+            for (int i = 0; i < NTW; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float r0 = acc4[i][pt][4 * v], r1 = acc4[i][pt][4 * v + 1], r2 = acc4[i][pt][4 * v + 2], r3 = acc4[i][pt][4 * v + 3];
+                    if (zrelu) { r0 = fmaxf(r0, 0.f); r1 = fmaxf(r1, 0.f); r2 = fmaxf(r2, 0.f); r3 = fmaxf(r3, 0.f); }
+                    u32x2_t o = {pack2(r0, r1), pack2(r2, r3)};
+                    *reinterpret_cast<u32x2_t*>(zp + l32 * ZPITCH + (i * 32 + 8 * v + 4 * lh) * 2) = o;
+                }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+            constexpr int CPP = NTW * 4;           // 16-byte chunks per pixel of this wavefront's channels
+#pragma unroll
+            for (int it = 0; it < 32 * CPP / 64; ++it) {
+                const int item = lane + 64 * it;
+                const int pr = item / CPP, chunk = item % CPP;
+                const int p = pt * 32 + pr;
+                const int oy = y0 + p / TW, ox = x0 + p % TW;
+                const u32x4_t o = *reinterpret_cast<const u32x4_t*>(zp + pr * ZPITCH + chunk * 16);
+                if (oy < a.H && ox < a.W)
+                    *reinterpret_cast<u32x4_t*>(zout + (size_t)(oy * a.W + ox) * TAILN + wv * (32 * NTW) + chunk * 8) = o;
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+        });
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -580,6 +672,9 @@ __global__ __launch_bounds__(256, 2) void bottleneck_fused128_kernel(const Fused
 bool fused_block_supported(const FusedBlockArgs& a, int width) {
     if (width != 64 && !(width == 128 && !a.first)) return false;   // 128-wide: identity blocks only
     if (!a.x || !a.y || a.x == a.y || !a.w1f || !a.w2f || !a.w3f || !a.b1 || !a.b2 || !a.b3) return false;
+    if (a.tail_n != 0) {   // tail layer: 64-wide identity blocks, 128 or 256 outputs
+        if (width != 64 || a.first || (a.tail_n != 128 && a.tail_n != 256) || !a.wtf || !a.bt || !a.z || a.z == a.y || a.z == a.x) return false;
+    }
     if (a.N <= 0 || a.H <= 0 || a.W <= 0) return false;
     if ((long long)a.H * a.W * 4 * width >= (1ll << 31)) return false;   // 32-bit element offsets within a frame
     const long long tiles = (long long)a.N * ((a.H + TH - 1) / TH) * ((a.W + TW - 1) / TW);
@@ -603,8 +698,10 @@ hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s)
     if (!fused_block_supported(a, width)) return hipErrorInvalidValue;
     constexpr size_t lds64 = (size_t)NHP * ((64 * 2 + 16) + (64 * 2 + 16)) + (size_t)NPX * (64 * 2 + 16);
     constexpr size_t lds128 = (size_t)NH * 256 + (size_t)NPX * 256;
-    static bool set_first = false, set_ident = false, set_128 = false;
+    static bool set_first = false, set_ident = false, set_128 = false, set_t128 = false, set_t256 = false;
     if (width == 128) return launch_fused_kernel(bottleneck_fused128_kernel, lds128, set_128, a, s);
+    if (a.tail_n == 128) return launch_fused_kernel(bottleneck_fused_kernel<64, false, 128>, lds64, set_t128, a, s);
+    if (a.tail_n == 256) return launch_fused_kernel(bottleneck_fused_kernel<64, false, 256>, lds64, set_t256, a, s);
     if (a.first) return launch_fused_kernel(bottleneck_fused_kernel<64, true>, lds64, set_first, a, s);
     return launch_fused_kernel(bottleneck_fused_kernel<64, false>, lds64, set_ident, a, s);
 }

@@ -31,6 +31,9 @@ struct Block {
     int stride = 1;
     // identity blocks the single-kernel bottleneck covers: the three weight matrices in MFMA fragment order
     bf16_t *f1 = nullptr, *f2 = nullptr, *f3 = nullptr;
+    // first block of the 128-wide stage: its 1x1 (256 -> 128) in fragment order, for use as the tail layer of the
+    // 64-wide stage's last single-kernel block
+    bf16_t* tf = nullptr;
 };
 struct ExitUnit {
     Layer lateral, rpn_conv, rpn_head /* obj (A) ++ delta (4A) */, fc1, fc2, pred /* cls (Kc) ++ box (4Kc) */;
@@ -38,6 +41,7 @@ struct ExitUnit {
     // in MFMA fragment order, and the matching fp32 bias; null when the exit has no fused variant
     bf16_t* head_f = nullptr;
     float* head_fb = nullptr;
+    bf16_t* lat_f = nullptr;   // lateral 256 -> 256 in fragment order (tail layer of the 64-wide stage's last block); else null
 };
 
 struct Tap {
@@ -394,6 +398,16 @@ int tap_copy(thia_model* m, int which, int f0, int nb, const void* src) {
 struct Trunk {
     void *x = nullptr, *y = nullptr;
     int h = 0, w = 0;
+    bool c1_done = false;   // the next stage's first 1x1 was applied by the previous stage's last block (result in ws.act[2])
+    bool hf_done = false;   // the exit's lateral was applied by the stage's last block (result in ws.hf)
+};
+
+// A 1x1 layer applied by the stage's last single-kernel block to its own output tile (FusedBlockArgs::wtf ...).
+struct Tail {
+    const bf16_t* wtf = nullptr;
+    const float* bt = nullptr;
+    void* z = nullptr;
+    int n = 0, relu = 0;
 };
 
 // Normalisation, stem and max-pool.
@@ -416,12 +430,33 @@ int run_stem(thia_model* m, const uint8_t* frames, int nb, int H, int W, Trunk& 
     return THIA_OK;
 }
 
-// Bottleneck stage s (0-based) applied to t.x; the stage's output becomes t.x.
-int run_stage(thia_model* m, int s, int nb, Trunk& t) {
+// The 1x1 layer that reads stage s's output next: exit `ep_here`'s lateral if the backbone stops after this stage
+// (ep_here > 0), else the first 1x1 of stage s + 1.  Empty when no fragment-ordered copy of that layer exists.
+Tail stage_tail(const thia_model* m, int s, int ep_here) {
+    Tail tl;
+    if (!m->fuse_blocks || m->precision != 1) return tl;
+    if (ep_here > 0) {
+        const ExitUnit& E = m->ex[ep_here - 1];
+        if (m->has_lateral && E.lat_f) { tl.wtf = E.lat_f; tl.bt = E.lateral.b; tl.z = m->ws.hf; tl.n = E.lateral.co; tl.relu = 0; }
+    } else if (s + 1 < 4 && !m->stage[s + 1].empty()) {
+        const Block& N = m->stage[s + 1][0];
+        if (N.tf) { tl.wtf = N.tf; tl.bt = N.c1.b; tl.z = m->ws.act[2]; tl.n = N.c1.co; tl.relu = 1; }
+    }
+    return tl;
+}
+
+// Bottleneck stage s (0-based) applied to t.x; the stage's output becomes t.x.  `tail` (optional) is handed to the
+// stage's last block if that block runs as a single kernel of the 64-wide variant; *tail_applied tells whether it was.
+int run_stage(thia_model* m, int s, int nb, Trunk& t, const Tail* tail = nullptr, bool* tail_applied = nullptr) {
     Workspace& ws = m->ws;
     void *&x = t.x, *&y = t.y;
     int &h = t.h, &w = t.w;
-    for (const Block& B : m->stage[s]) {
+    const bool skip_c1 = t.c1_done;   // first block only: its 1x1 already sits in ws.act[2]
+    t.c1_done = false;
+    if (tail_applied) *tail_applied = false;
+    const size_t nblocks = m->stage[s].size();
+    for (size_t bi = 0; bi < nblocks; ++bi) {
+        const Block& B = m->stage[s][bi];
         const int ho = conv_out(h, 3, B.stride, 1), wo = conv_out(w, 3, B.stride, 1);
         if (B.f1 && m->fuse_blocks) {
             FusedBlockArgs fa{};
@@ -429,13 +464,20 @@ int run_stage(thia_model* m, int s, int nb, Trunk& t) {
             fa.w1f = B.f1; fa.w2f = B.f2; fa.w3f = B.f3; fa.b1 = B.c1.b; fa.b2 = B.c2.b; fa.b3 = B.c3.b;
             fa.N = nb; fa.H = h; fa.W = w; fa.first = B.has_sc ? 1 : 0;
             if (B.stride == 1 && fused_block_supported(fa, B.c1.co)) {
+                bool with_tail = false;
+                if (tail && tail->wtf && bi + 1 == nblocks && !B.has_sc && B.c1.co == 64) {
+                    FusedBlockArgs ft = fa;
+                    ft.wtf = tail->wtf; ft.bt = tail->bt; ft.z = static_cast<bf16_t*>(tail->z); ft.tail_n = tail->n; ft.tail_relu = tail->relu;
+                    if (fused_block_supported(ft, B.c1.co)) { fa = ft; with_tail = true; }
+                }
                 Scope sc(m, THIA_K_CONV);
                 HIP_TRY(m, launch_fused_block(fa, B.c1.co, m->stream));
+                if (with_tail && tail_applied) *tail_applied = true;
                 std::swap(x, y);
                 continue;
             }
         }
-        TRY(run_conv(m, THIA_K_CONV, B.c1, x, nb, h, w, 1, 0, nullptr, true, false, ws.act[2]));
+        if (!(bi == 0 && skip_c1)) TRY(run_conv(m, THIA_K_CONV, B.c1, x, nb, h, w, 1, 0, nullptr, true, false, ws.act[2]));
         TRY(run_conv(m, THIA_K_CONV, B.c2, ws.act[2], nb, h, w, B.stride, 1, nullptr, true, false, ws.act[3]));
         if (B.has_sc) {
             // last 1x1 and projection shortcut share one accumulator: y = relu(W3 t2 + Ws x(strided) + b3 + bs)
@@ -452,17 +494,24 @@ int run_stage(thia_model* m, int s, int nb, Trunk& t) {
 }
 
 // Backbone truncated at exit ep for nb frames; returns the exit-stage tensor (NHWC) in *feat.
-int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int ep, const void** feat) {
+int run_backbone(thia_model* m, const uint8_t* frames, int nb, int H, int W, int ep, const void** feat, bool* hf_done = nullptr) {
     Trunk t;
     TRY(run_stem(m, frames, nb, H, W, t));
-    for (int s = 0; s < exit_stages(m, ep); ++s) TRY(run_stage(m, s, nb, t));
+    const int ns = exit_stages(m, ep);
+    for (int s = 0; s < ns; ++s) {
+        const Tail tl = stage_tail(m, s, s + 1 == ns ? ep : 0);
+        bool applied = false;
+        TRY(run_stage(m, s, nb, t, &tl, &applied));
+        if (applied) (s + 1 == ns ? t.hf_done : t.c1_done) = true;
+    }
     *feat = t.x;
+    if (hf_done) *hf_done = t.hf_done;
     return THIA_OK;
 }
 
 // Heads of exit ep on nb frames whose exit-stage tensor is `feat`.
 int run_heads(thia_model* m, const void* feat, int f0, int nb, int H, int W, int ep, float* out_boxes, float* out_scores,
-              int32_t* out_labels) {
+              int32_t* out_labels, bool hf_ready = false) {
     Workspace& ws = m->ws;
     const ExitUnit& E = m->ex[ep - 1];
     const ExitGeom g = exit_geom(m, ep, H, W);
@@ -470,7 +519,8 @@ int run_heads(thia_model* m, const void* feat, int f0, int nb, int H, int W, int
     const long nA = (long)g.Hk * g.Wk * A;
     const void* hf = feat;
     if (m->has_lateral) {
-        TRY(run_conv(m, THIA_K_CONV, E.lateral, feat, nb, g.Hk, g.Wk, 1, 0, nullptr, false, false, ws.hf));
+        // (hf_ready: the stage's last block has already applied the lateral to its output tile)
+        if (!hf_ready) TRY(run_conv(m, THIA_K_CONV, E.lateral, feat, nb, g.Hk, g.Wk, 1, 0, nullptr, false, false, ws.hf));
         hf = ws.hf;
     }
     bool fused_heads = false;
@@ -575,8 +625,9 @@ int detect_frames(thia_model* m, const uint8_t* frames, int n, int H, int W, int
     for (int f0 = 0; f0 < n; f0 += mb) {
         const int nb = std::min(mb, n - f0);
         const void* feat = nullptr;
-        TRY(run_backbone(m, frames + (size_t)f0 * 3 * H * W, nb, H, W, ep, &feat));
-        TRY(run_heads(m, feat, f0, nb, H, W, ep, ob + (size_t)f0 * D * 4, os + (size_t)f0 * D, ol + (size_t)f0 * D));
+        bool hf_done = false;
+        TRY(run_backbone(m, frames + (size_t)f0 * 3 * H * W, nb, H, W, ep, &feat, &hf_done));
+        TRY(run_heads(m, feat, f0, nb, H, W, ep, ob + (size_t)f0 * D * 4, os + (size_t)f0 * D, ol + (size_t)f0 * D, hf_done));
     }
     return THIA_OK;
 }
@@ -594,7 +645,14 @@ int detect_frames_all_exits(thia_model* m, const uint8_t* frames, int n, int H, 
         Trunk t;
         rc = run_stem(m, frames + (size_t)f0 * 3 * H * W, nb, H, W, t);
         for (int e = 1; e <= m->n_exits && rc == THIA_OK; ++e) {
-            if (exit_stages(m, e) > 0) rc = run_stage(m, exit_stages(m, e) - 1, nb, t);
+            if (exit_stages(m, e) > 0) {
+                // every stage is followed by the next one here, so the tail layer is the next stage's first 1x1
+                const int sidx = exit_stages(m, e) - 1;
+                const Tail tl = e < m->n_exits ? stage_tail(m, sidx, 0) : Tail{};
+                bool applied = false;
+                rc = run_stage(m, sidx, nb, t, &tl, &applied);
+                if (applied) t.c1_done = true;
+            }
             if (rc != THIA_OK) break;
             const size_t o = (size_t)(e - 1) * n + f0;
             rc = run_heads(m, t.x, f0, nb, H, W, e, ob + o * D * 4, os + o * D, ol + o * D);
@@ -629,7 +687,12 @@ int estimate_frames(thia_model* m, const uint8_t* frames, int n, int H, int W, i
         const int nb = std::min(mb, n - f0);
         Trunk t;
         rc = run_stem(m, frames + (size_t)f0 * 3 * H * W, nb, H, W, t);
-        for (int s = 0; s < exit_stages(m, E) && rc == THIA_OK; ++s) rc = run_stage(m, s, nb, t);
+        for (int s = 0; s < exit_stages(m, E) && rc == THIA_OK; ++s) {
+            const Tail tl = s + 1 < exit_stages(m, E) ? stage_tail(m, s, 0) : Tail{};
+            bool applied = false;
+            rc = run_stage(m, s, nb, t, &tl, &applied);
+            if (applied) t.c1_done = true;
+        }
         if (rc != THIA_OK) break;
         {
             Scope sc(m, THIA_K_POST);
@@ -731,6 +794,7 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
                 HostLayer cat;
                 cat.w = wcat.data(); cat.b = bcat.data(); cat.co = 4 * w; cat.ci = w + cin; cat.k = 1;
                 if (!rc) rc = upload_layer(m, cat, nullptr, B.c3);
+                if (m->precision == 1 && w == 128 && cin == 256 && !rc) rc = upload_fragments(m, c1, &B.tf);
                 if (m->precision == 1 && w == 64 && cin == 64 && B.stride == 1) {   // projection block of the 64-wide stage
                     if (!rc) rc = upload_fragments(m, c1, &B.f1);
                     if (!rc) rc = upload_fragments(m, c2, &B.f2);
@@ -758,6 +822,7 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
             if (!take_layer(r, lat, m->head_ch, ce, 1)) return bad(THIA_E_BLOB);
             hc = m->head_ch;
             rc = upload_layer(m, lat, nullptr, E.lateral);
+            if (!rc && m->precision == 1 && ce == 256 && hc == 256) rc = upload_fragments(m, lat, &E.lat_f);
         }
         if (!take_layer(r, rc3, hc, hc, 3) || !take_layer(r, obj, A, hc, 1) || !take_layer(r, dl, 4 * A, hc, 1) ||
             !take_layer(r, fc1, m->fc_dim, hc, m->pool) || !take_layer(r, fc2, m->fc_dim, m->fc_dim, 1) ||
@@ -808,14 +873,16 @@ void thia_free_model(thia_model* m) {
             if (B.f1) (void)hipFree(B.f1);
             if (B.f2) (void)hipFree(B.f2);
             if (B.f3) (void)hipFree(B.f3);
-            B.f1 = B.f2 = B.f3 = nullptr;
+            if (B.tf) (void)hipFree(B.tf);
+            B.f1 = B.f2 = B.f3 = B.tf = nullptr;
         }
     for (int e = 0; e < 5; ++e) {
         ExitUnit& E = m->ex[e];
         free_layer(E.lateral); free_layer(E.rpn_conv); free_layer(E.rpn_head); free_layer(E.fc1); free_layer(E.fc2); free_layer(E.pred);
         if (E.head_f) (void)hipFree(E.head_f);
         if (E.head_fb) (void)hipFree(E.head_fb);
-        E.head_f = nullptr; E.head_fb = nullptr;
+        if (E.lat_f) (void)hipFree(E.lat_f);
+        E.head_f = nullptr; E.head_fb = nullptr; E.lat_f = nullptr;
     }
     delete m;
 }

@@ -86,6 +86,12 @@ struct FusedBlockArgs {
     const float *b1, *b2, *b3;
     int N, H, W;
     int first;
+    // optional tail layer (64-wide identity blocks): z = [relu](Wt y + bt), Wt [tail_n][4 * width] in fragment order,
+    // z [N, H, W, tail_n]; tail_n = 0: none
+    const bf16_t* wtf = nullptr;
+    const float* bt = nullptr;
+    bf16_t* z = nullptr;
+    int tail_n = 0, tail_relu = 0;
 };
 bool fused_block_supported(const FusedBlockArgs& a, int width);
 hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s);

@@ -179,9 +179,12 @@ def test_microbatch_and_repeat_are_bit_identical():
             assert torch.equal(a, b)
 
 
-def test_fused_blocks_match_layer_by_layer_path():
-    """The single-kernel identity bottlenecks walk K in the same order as the layer-by-layer kernels, so the
-    exit tensor and the detections agree (asserted to one bf16 ulp of the tensor's max; equality reported)."""
+@pytest.mark.parametrize("ep", [1, 2])
+def test_fused_blocks_match_layer_by_layer_path(ep):
+    """The single-kernel bottlenecks walk K in the same order as the layer-by-layer kernels, so the exit tensor and
+    the detections agree (asserted to one bf16 ulp of the tensor's max; equality reported).  The last block of the
+    64-wide stage also applies the layer that reads its output - the lateral at exit 1, the next stage's first 1x1
+    at exit 2 - to its output tile: the lateral's result is compared as well."""
     spec = ModelSpec(precision=1, blocks=(3, 2, 1, 1), fc_dim=128, pre_nms=1000, post_nms=300, n_classes=8)
     m, _ = gpu_model(spec, 0xBEEF + 52)
     frames = to_dev(make_frames(SceneSpec(200, 264, 3, 4, 10, 10, 90), 44))
@@ -189,13 +192,16 @@ def test_fused_blocks_match_layer_by_layer_path():
     m.set_debug(True)
     for on in (True, False):
         m.set_fusion(on)
-        o = m.detect_chunk(frames, 2)
+        o = m.detect_chunk(frames, ep)
         torch.cuda.synchronize()
-        res.append(([t.clone() for t in o], m.tap("feat").astype(np.float32)))
+        res.append(([t.clone() for t in o], m.tap("feat").astype(np.float32), m.tap("head_feat").astype(np.float32),
+                    m.tap("rpn_logits").copy()))
     m.set_fusion(True)
     m.set_debug(False)
     assert relerr(res[0][1], res[1][1]) <= 2.0 ** -7
-    if np.array_equal(res[0][1], res[1][1]):
+    assert relerr(res[0][2], res[1][2]) <= 2.0 ** -7
+    assert relerr(res[0][3], res[1][3]) <= 2.0 ** -6
+    if np.array_equal(res[0][2], res[1][2]):
         for a, b in zip(res[0][0], res[1][0]):
             assert torch.equal(a, b)
 
