@@ -358,6 +358,16 @@ int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int w
                        const float* w2, const float* b2, const float* w3, const float* b3, const float* ws,
                        const float* bs, void* out);
 
+/*
+ * The same kernel with a tail layer (Sec. 4.2: an exit's unit, or the next stage, reads the
+ * stage's output): the 64-wide identity block also applies z = [relu](Wt y + bt), Wt host
+ * float32 [tail_n, 256, 1, 1], tail_n = 128 or 256, to its output tile y and writes
+ * out_tail dev [n,H,W,tail_n] next to out.  bf16 models only.
+ */
+int thia_op_bottleneck_tail(thia_model* m, const void* in, int n, int H, int W, const float* w1, const float* b1,
+                            const float* w2, const float* b2, const float* w3, const float* b3, const float* wt,
+                            const float* bt, int tail_n, int tail_relu, void* out, void* out_tail);
+
 /* Stem of the backbone on frames dev uint8 [n,3,H,W]: normalise, 7x7/2 conv + ReLU,
  * 3x3/2 max-pool; out T [n,Hp,Wp,stem_ch] NHWC. */
 int thia_op_stem(thia_model* m, const uint8_t* frames, int n, int H, int W, void* out);

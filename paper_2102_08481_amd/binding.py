@@ -28,7 +28,7 @@ EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_mi
            "thia_set_estimator", "thia_estimate_exit", "thia_answer_counts", "thia_metrics_from_counts", "thia_last_error", "thia_set_debug", "thia_debug_tap",
            "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
            "thia_op_rpn_proposals", "thia_op_nms", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
-           "thia_op_stem", "thia_op_bottleneck", "thia_set_fusion"]
+           "thia_op_stem", "thia_op_bottleneck", "thia_op_bottleneck_tail", "thia_set_fusion"]
 
 
 class ThiaInfo(C.Structure):
@@ -108,6 +108,7 @@ def lib():
     L.thia_op_conv.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i32, i32, i32, vp, i32, i32, vp]
     L.thia_op_stem.argtypes = [vp, vp, i32, i32, i32, vp]
     L.thia_op_bottleneck.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.thia_op_bottleneck_tail.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
     L.thia_set_fusion.argtypes = [vp, i32]
     for name in EXPORTS:
         getattr(L, name)
@@ -412,6 +413,18 @@ class Model:
         self._check(lib().thia_op_bottleneck(self._h, _ptr(x), n, H, W, width, *[None if v is None else v.ctypes.data for v in arrs],
                                              _ptr(out)))
         return out
+
+    def op_bottleneck_tail(self, x, w1, b1, w2, b2, w3, b3, wt, bt, relu):
+        """64-wide identity block plus the 1x1 tail layer wt [N,256,1,1] (N = 128 or 256) on its output: returns (y, z)."""
+        _dev(x, self.elem)
+        n, H, W, _ = x.shape
+        arrs = [np.ascontiguousarray(v, dtype=np.float32) for v in (w1, b1, w2, b2, w3, b3, wt, bt)]
+        tail_n = arrs[6].shape[0]
+        out = torch.empty((n, H, W, 256), dtype=self.elem, device=self.device)
+        out_tail = torch.empty((n, H, W, tail_n), dtype=self.elem, device=self.device)
+        self._check(lib().thia_op_bottleneck_tail(self._h, _ptr(x), n, H, W, *[v.ctypes.data for v in arrs], tail_n, int(relu),
+                                                  _ptr(out), _ptr(out_tail)))
+        return out, out_tail
 
     def op_stem(self, frames):
         _dev(frames, torch.uint8)

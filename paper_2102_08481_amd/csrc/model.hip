@@ -1286,8 +1286,10 @@ int thia_set_fusion(thia_model* m, int on) {
     return THIA_OK;
 }
 
-int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int width, const float* w1, const float* b1, const float* w2,
-                       const float* b2, const float* w3, const float* b3, const float* ws, const float* bs, void* out) {
+namespace {
+int op_bottleneck_impl(thia_model* m, const void* in, int n, int H, int W, int width, const float* w1, const float* b1, const float* w2,
+                       const float* b2, const float* w3, const float* b3, const float* ws, const float* bs, void* out, const float* wt,
+                       const float* bt, int tail_n, int tail_relu, void* out_tail) {
     if (!m || !in || !out || !w1 || !b1 || !w2 || !b2 || !w3 || !b3 || n <= 0 || H <= 0 || W <= 0 || in == out || (ws == nullptr) != (bs == nullptr))
         return fail(m, THIA_E_BADARG, "bad arguments");
     if (m->precision != 1) return fail(m, THIA_E_SHAPE, "the single-kernel bottleneck exists for bf16 models only");
@@ -1311,7 +1313,7 @@ int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int w
     FusedBlockArgs fa{};
     fa.x = static_cast<const bf16_t*>(in); fa.y = static_cast<bf16_t*>(out);
     fa.N = n; fa.H = H; fa.W = W; fa.first = first ? 1 : 0;
-    bf16_t* f[3] = {nullptr, nullptr, nullptr};
+    bf16_t* f[4] = {nullptr, nullptr, nullptr, nullptr};
     float* bias = nullptr;
     auto cleanup = [&]() {
         for (bf16_t* q : f) if (q) (void)hipFree(q);
@@ -1320,17 +1322,24 @@ int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int w
     int rc = upload_fragments(m, l1, &f[0]);
     if (!rc) rc = upload_fragments(m, l2, &f[1]);
     if (!rc) rc = upload_fragments(m, l3, &f[2]);
-    if (!rc && hipMalloc(reinterpret_cast<void**>(&bias), (size_t)6 * width * 4) != hipSuccess) rc = fail(m, THIA_E_NOMEM, "bias allocation failed");
+    if (!rc && tail_n > 0) {
+        HostLayer lt;
+        lt.w = wt; lt.b = bt; lt.co = tail_n; lt.ci = 4 * width; lt.k = 1;
+        rc = upload_fragments(m, lt, &f[3]);
+    }
+    if (!rc && hipMalloc(reinterpret_cast<void**>(&bias), ((size_t)6 * width + tail_n) * 4) != hipSuccess) rc = fail(m, THIA_E_NOMEM, "bias allocation failed");
     if (!rc) {
-        std::vector<float> hb((size_t)6 * width);
+        std::vector<float> hb((size_t)6 * width + tail_n);
         std::memcpy(hb.data(), b1, sizeof(float) * width);
         std::memcpy(hb.data() + width, b2, sizeof(float) * width);
         std::memcpy(hb.data() + 2 * width, b3v.data(), sizeof(float) * 4 * width);
+        if (tail_n > 0) std::memcpy(hb.data() + 6 * width, bt, sizeof(float) * tail_n);
         if (hipMemcpy(bias, hb.data(), hb.size() * 4, hipMemcpyHostToDevice) != hipSuccess) rc = fail(m, THIA_E_HIP, "bias upload failed");
     }
     if (rc) { cleanup(); return rc; }
     fa.w1f = f[0]; fa.w2f = f[1]; fa.w3f = f[2];
     fa.b1 = bias; fa.b2 = bias + width; fa.b3 = bias + 2 * width;
+    if (tail_n > 0) { fa.wtf = f[3]; fa.bt = bias + 6 * width; fa.z = static_cast<bf16_t*>(out_tail); fa.tail_n = tail_n; fa.tail_relu = tail_relu; }
     hipError_t e = fused_block_supported(fa, width) ? launch_fused_block(fa, width, m->stream) : hipErrorInvalidValue;
     hipError_t e2 = hipStreamSynchronize(m->stream);
     cleanup();
@@ -1338,6 +1347,20 @@ int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int w
     if (e != hipSuccess) return fail_hip(m, e, "launch_fused_block");
     if (e2 != hipSuccess) return fail_hip(m, e2, "bottleneck sync");
     return THIA_OK;
+}
+}  // namespace
+
+int thia_op_bottleneck(thia_model* m, const void* in, int n, int H, int W, int width, const float* w1, const float* b1, const float* w2,
+                       const float* b2, const float* w3, const float* b3, const float* ws, const float* bs, void* out) {
+    return op_bottleneck_impl(m, in, n, H, W, width, w1, b1, w2, b2, w3, b3, ws, bs, out, nullptr, nullptr, 0, 0, nullptr);
+}
+
+int thia_op_bottleneck_tail(thia_model* m, const void* in, int n, int H, int W, const float* w1, const float* b1, const float* w2,
+                            const float* b2, const float* w3, const float* b3, const float* wt, const float* bt, int tail_n, int tail_relu,
+                            void* out, void* out_tail) {
+    if (!m) return THIA_E_BADARG;
+    if (!wt || !bt || !out_tail || (tail_n != 128 && tail_n != 256)) return fail(m, THIA_E_BADARG, "bad tail arguments");
+    return op_bottleneck_impl(m, in, n, H, W, 64, w1, b1, w2, b2, w3, b3, nullptr, nullptr, out, wt, bt, tail_n, tail_relu, out_tail);
 }
 
 int thia_op_stem(thia_model* m, const uint8_t* frames, int n, int H, int W, void* out) {

@@ -126,6 +126,35 @@ def test_bottleneck_op_matches_oracle(shape, variant):
     assert differ <= 0.02, (shape, differ)
 
 
+@pytest.mark.parametrize("tail_n,relu", [(128, True), (256, False)])
+@pytest.mark.parametrize("shape", [(2, 21, 37), (1, 5, 7), (1, 8, 16)])
+def test_bottleneck_tail_layer_matches_oracle(shape, tail_n, relu):
+    """The 1x1 layer applied by the block to its own output tile (next stage's first 1x1 with ReLU, or an exit's lateral
+    without): the block output is unchanged by the extra phase, and the tail equals the oracle's 1x1 convolution of that
+    very output (bf16 storage) up to one-ulp flips of the rounded result."""
+    m, _ = _model(1)
+    n, H, W = shape
+    wd = 64
+    rs = np.random.RandomState(H * 17 + W + tail_n)
+    x = _bf16(np.abs(rs.randn(n, 4 * wd, H, W)).astype(np.float32))
+    w1 = (rs.randn(wd, 4 * wd, 1, 1) * np.sqrt(2.0 / (4 * wd))).astype(np.float32)
+    w2 = (rs.randn(wd, wd, 3, 3) * np.sqrt(2.0 / (9 * wd))).astype(np.float32)
+    w3 = (rs.randn(4 * wd, wd, 1, 1) * np.sqrt(2.0 / wd)).astype(np.float32)
+    wt = (rs.randn(tail_n, 4 * wd, 1, 1) * np.sqrt(2.0 / (4 * wd))).astype(np.float32)
+    b1, b2, b3, bt = [(rs.randn(c) * 0.1).astype(np.float32) for c in (wd, wd, 4 * wd, tail_n)]
+    xd = to_dev(nchw_to_nhwc(x), m.elem)
+    y0 = m.op_bottleneck(xd, w1, b1, w2, b2, w3, b3)
+    y, z = m.op_bottleneck_tail(xd, w1, b1, w2, b2, w3, b3, wt, bt, relu)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y0)
+    yh = nhwc_to_nchw(y.float().cpu().numpy())
+    ref = oracle.conv2d(yh, wt, bt, relu=relu, bf16_weights=1, round_out=1)
+    got = nhwc_to_nchw(z.float().cpu().numpy())
+    assert got.shape == ref.shape == (n, tail_n, H, W)
+    assert relerr(got, ref) <= 2.0 ** -7, relerr(got, ref)
+    assert float(np.mean(got != ref)) <= 0.02
+
+
 def test_bottleneck_op_rejects_unsupported():
     from paper_2102_08481_amd import ThiaError
     m, _ = _model(1)
