@@ -92,9 +92,10 @@ int thia_set_stream(thia_model* m, void* hip_stream);
  * default.  Results never depend on it: every frame is computed independently. */
 int thia_set_microbatch(thia_model* m, int frames);
 
-/* Identity bottleneck blocks that have a single-kernel variant run through it (on, the
- * default) or layer by layer (off).  Both give the same tensors up to the accumulation
- * order; the switch exists for measurements and tests. */
+/* Bottleneck blocks and layer pairs that have a fused kernel variant run through it (on = 1,
+ * the default, where the variant pays; on = 2: wherever it applies, also at sizes too small
+ * for it to pay) or layer by layer (on = 0).  All give the same tensors up to the
+ * accumulation order; the switch exists for measurements and tests. */
 int thia_set_fusion(thia_model* m, int on);
 
 int thia_get_info(const thia_model* m, thia_info* out);

@@ -401,7 +401,7 @@ class Model:
         return out
 
     def set_fusion(self, on):
-        self._check(lib().thia_set_fusion(self._h, int(bool(on))))
+        self._check(lib().thia_set_fusion(self._h, int(on)))   # 0 off, 1 where it pays (default), 2 wherever it applies
 
     def op_bottleneck(self, x, w1, b1, w2, b2, w3, b3, ws=None, bs=None):
         """x: cuda bf16 [n,H,W,Cin]; weights numpy fp32 in [Cout,Cin,k,k] order; ws/bs: projection shortcut."""

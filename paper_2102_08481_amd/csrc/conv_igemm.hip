@@ -105,10 +105,11 @@ __device__ inline void static_for(F&& f) {
     }
 }
 
-// MODE 0: any filter size; 1: 1x1 unpadded (no tap bookkeeping); 2: 1x1 with a second source tensor.
+// MODE 0: any filter size; 1: 1x1 unpadded (no tap bookkeeping); 2: 1x1 with a second source tensor;
+// 4: any filter size, followed by the expansion tail (ConvArgs::tail_*) on the block's output tile.
 template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, int MODE, typename OutT>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(const ConvArgs a) {
-    constexpr bool ONE = MODE >= 1, DUAL = MODE == 2;
+    constexpr bool ONE = MODE == 1 || MODE == 2, DUAL = MODE == 2;
     constexpr int NT = 64 * WAVES_M * WAVES_N;  // threads per block
     constexpr int BK = BKB / (int)sizeof(T);   // K elements per tile row
     constexpr int EPC = 16 / (int)sizeof(T);   // elements per 16-byte chunk
@@ -399,6 +400,123 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
         }
     }
 
+    // ---- expansion tail (large bf16 tile only): the block's ReLU'd 256 x 256 tile, rounded to bf16 as the stored tensor
+    // would be, is parked in LDS (unpadded 512-byte rows, 16-byte chunk index XOR-ed with the row) and contracted with the
+    // next 1x1 layer's weights (fragment order, streamed from L2).  Wavefront wv owns output channels tail_n / 8 * wv ..
+    // and walks them 64 at a time over the two 128-pixel halves of the tile.  Residual and result pass through a 4 KB
+    // wavefront-private LDS region as bf16 (32 pixels x 64 channels), so that global loads and stores are 16 bytes per
+    // lane and cover whole 128-byte lines; the sum is formed in accumulator layout in fp32 and rounded once.
+    if constexpr (std::is_same<T, bf16_t>::value && std::is_same<OutT, bf16_t>::value && BM == 256 && BN == 256 && WAVES_M == 2 &&
+                  WAVES_N == 4 && MODE == 4) {
+        constexpr int TKS = BN / 16;               // k-steps of the tail contraction (16)
+        constexpr int TR = 4;                      // k-steps of weight fragments in flight
+        const int lh = lane >> 5;
+        auto yoff = [](int row, int byteoff) { return row * 512 + ((((byteoff >> 4) ^ row) & 31) << 4) + (byteoff & 15); };
+        auto roff = [](int row, int byteoff) { return row * 128 + ((((byteoff >> 4) ^ row) & 7) << 4) + (byteoff & 15); };
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int ch = wn * WN + i * 32 + 8 * v + 4 * lh;
+                    const f32x4_t bv = *reinterpret_cast<const f32x4_t*>(a.bias + n0 + ch);
+                    u32x2_t o = {pack_bf16x2(fmaxf(acc[i][j][4 * v] + bv.x, 0.f), fmaxf(acc[i][j][4 * v + 1] + bv.y, 0.f)),
+                                 pack_bf16x2(fmaxf(acc[i][j][4 * v + 2] + bv.z, 0.f), fmaxf(acc[i][j][4 * v + 3] + bv.w, 0.f))};
+                    *reinterpret_cast<u32x2_t*>(smem + yoff(wm * WM + j * 32 + frag_row, ch * 2)) = o;
+                }
+        __syncthreads();
+        const int N3 = a.tail_n, ctw = N3 / 256;   // 32-channel tiles per wavefront
+        const u32x4_t* __restrict__ twf = reinterpret_cast<const u32x4_t*>(a.tail_w) + lane;
+        const T* __restrict__ tres = static_cast<const T*>(a.tail_res);
+        T* __restrict__ tout = static_cast<T*>(a.tail_out);
+        unsigned char* R = smem + 256 * 512 + wv * 4096;
+        // pixel operand of the tail's MFMAs: row q * 128 + j * 32 + frag_row, logical chunk 2 ks + lane / 32; the rows of one
+        // fragment differ in their low five bits only (= frag_row), so the swizzled chunk is (x0 ^ 2 ks) for every j and q
+        const int x0 = ((lane >> 5) ^ frag_row) & 31;
+        const unsigned char* ylane = smem + frag_row * 512;
+        const int pr0 = lane >> 3, chunk = lane & 7;   // this lane's 16-byte pieces: pixels pr0 + 8 it, channels 8 chunk .. + 7
+        for (int cp = 0; cp < ctw; cp += 2) {
+            const int ct0 = wv * ctw + cp;
+            for (int q = 0; q < 2; ++q) {
+                u32x4_t rq[2][4];
+                auto fetch_res = [&](int j, u32x4_t* dst) {
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) {
+                        const int pix = m0 + q * 128 + j * 32 + pr0 + 8 * it;
+                        dst[it] = *reinterpret_cast<const u32x4_t*>(tres + (size_t)(pix < M ? pix : 0) * N3 + ct0 * 32 + chunk * 8);
+                    }
+                };
+                fetch_res(0, rq[0]);
+                u32x4_t tw[2][TR];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int k = 0; k < TR; ++k) tw[i][k] = twf[((size_t)(ct0 + i) * TKS + k) * 64];
+                f32x16_t t4[2][4];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const f32x4_t bq = *reinterpret_cast<const f32x4_t*>(a.tail_b + (ct0 + i) * 32 + 8 * v + 4 * lh);
+                        t4[i][0][4 * v] = bq.x; t4[i][0][4 * v + 1] = bq.y; t4[i][0][4 * v + 2] = bq.z; t4[i][0][4 * v + 3] = bq.w;
+                    }
+#pragma unroll
+                    for (int j = 1; j < 4; ++j) t4[i][j] = t4[i][0];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<0, TKS>([&](auto kc) {
+                    constexpr int ks = decltype(kc)::value;
+                    u32x4_t wf[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        wf[i] = tw[i][ks % TR];
+                        if (ks + TR < TKS) tw[i][ks % TR] = twf[((size_t)(ct0 + i) * TKS + ks + TR) * 64];
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const u32x4_t b = *reinterpret_cast<const u32x4_t*>(ylane + (q * 128 + j * 32) * 512 + ((x0 ^ (2 * ks)) << 4));
+#pragma unroll
+                        for (int i = 0; i < 2; ++i) mma_step<T>(t4[i][j], wf[i], b);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                static_for<0, 4>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    if (j + 1 < 4) fetch_res(j + 1, rq[(j + 1) & 1]);
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) *reinterpret_cast<u32x4_t*>(R + roff(pr0 + 8 * it, chunk * 16)) = rq[j & 1][it];
+                    __builtin_amdgcn_s_waitcnt(0xc07f);
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            unsigned char* pp = R + roff(frag_row, (i * 32 + 8 * v + 4 * lh) * 2);
+                            const u32x2_t r = *reinterpret_cast<const u32x2_t*>(pp);
+                            const float r0 = fmaxf(t4[i][j][4 * v] + __uint_as_float(r.x << 16), 0.f);
+                            const float r1 = fmaxf(t4[i][j][4 * v + 1] + __uint_as_float(r.x & 0xffff0000u), 0.f);
+                            const float r2 = fmaxf(t4[i][j][4 * v + 2] + __uint_as_float(r.y << 16), 0.f);
+                            const float r3 = fmaxf(t4[i][j][4 * v + 3] + __uint_as_float(r.y & 0xffff0000u), 0.f);
+                            const u32x2_t o = {pack_bf16x2(r0, r1), pack_bf16x2(r2, r3)};
+                            *reinterpret_cast<u32x2_t*>(pp) = o;   // the lane rewrites exactly the bytes it has read
+                        }
+                    __builtin_amdgcn_s_waitcnt(0xc07f);
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) {
+                        const int pix = m0 + q * 128 + j * 32 + pr0 + 8 * it;
+                        const u32x4_t o = *reinterpret_cast<const u32x4_t*>(R + roff(pr0 + 8 * it, chunk * 16));
+                        if (pix < M) *reinterpret_cast<u32x4_t*>(tout + (size_t)pix * N3 + ct0 * 32 + chunk * 8) = o;
+                    }
+                    __builtin_amdgcn_s_waitcnt(0xc07f);
+                    __builtin_amdgcn_wave_barrier();
+                });
+            }
+        }
+        return;
+    }
+
     // ---- epilogue.  Accumulator element e of lane l: channel 8*(e/4) + 4*(l/32) + e%4, pixel l%32.
     OutT* __restrict__ out0 = static_cast<OutT*>(a.out0);
     OutT* __restrict__ out1 = static_cast<OutT*>(a.out1);
@@ -527,7 +645,8 @@ bool conv_supported(const ConvArgs& a, int precision) {
 template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, int MODE, typename OutT>
 static hipError_t launch_cfg(const ConvArgs& a, hipStream_t s) {
     static bool attr_set = false;
-    const size_t lds = (size_t)2 * (BN + BM) * (BKB + 16);
+    // (the expansion tail parks an unpadded 256 x 512-byte tile and gives each of the 8 wavefronts 4 KB beside it: the CU's whole LDS)
+    const size_t lds = MODE == 4 ? (size_t)160 * 1024 : (size_t)2 * (BN + BM) * (BKB + 16);
     auto kern = conv_igemm_kernel<T, BM, BN, BKB, WAVES_M, WAVES_N, MODE, OutT>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -553,8 +672,21 @@ static hipError_t launch_one(const ConvArgs& a, hipStream_t s) {
     return launch_cfg<T, BM, BN, BKB, WAVES_M, WAVES_N, 0, OutT>(a, s);
 }
 
+bool conv_tail_supported(const ConvArgs& a, int precision) {
+    if (precision != 1 || !conv_supported(a, precision)) return false;
+    if (!a.tail_w || !a.tail_b || !a.tail_res || !a.tail_out || a.tail_res == a.tail_out) return false;
+    if (a.tail_n < 512 || a.tail_n % 512 || a.tail_n > 4096) return false;
+    if (a.Cout != 256 || !a.relu || a.res != nullptr || a.out1 != nullptr || a.in2 != nullptr || a.head_w != nullptr) return false;
+    const long long M = (long long)a.N * a.Ho * a.Wo;
+    return M * a.tail_n < (1ll << 31);
+}
+
 hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream_t s) {
     if (!conv_supported(a, precision)) return hipErrorInvalidValue;
+    if (a.tail_w != nullptr) {   // expansion tail: one kernel variant only
+        if (out_f32 || !conv_tail_supported(a, precision)) return hipErrorInvalidValue;
+        return launch_cfg<bf16_t, 256, 256, 128, 2, 4, 4, bf16_t>(a, s);
+    }
     if (a.head_w != nullptr) {   // fused predictors exist in one kernel variant only
         if (out_f32 || !conv_heads_supported(a, precision)) return hipErrorInvalidValue;
         return launch_one<bf16_t, 256, 256, 128, 2, 4, bf16_t, true>(a, s);

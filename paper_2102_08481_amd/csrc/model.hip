@@ -34,6 +34,9 @@ struct Block {
     // first block of the 128-wide stage: its 1x1 (256 -> 128) in fragment order, for use as the tail layer of the
     // 64-wide stage's last single-kernel block
     bf16_t* tf = nullptr;
+    // identity blocks with 256-channel intermediates: the last 1x1 (256 -> 1024) in fragment order, applied by the 3x3's
+    // kernel to its own output tile (ConvArgs::tail_*)
+    bf16_t* t3f = nullptr;
 };
 struct ExitUnit {
     Layer lateral, rpn_conv, rpn_head /* obj (A) ++ delta (4A) */, fc1, fc2, pred /* cls (Kc) ++ box (4Kc) */;
@@ -84,6 +87,7 @@ struct thia_model {
     hipStream_t stream = nullptr;
     int user_mb = 0;
     bool fuse_blocks = true;  // identity bottlenecks as one kernel where a variant exists
+    bool fuse_always = false; // take fused variants also below the sizes where they pay (tests)
     // exit estimator (two layers on the pooled last-stage features); est_hidden == 0: none set
     int est_hidden = 0;
     float *est_w1t = nullptr, *est_b1 = nullptr, *est_w2 = nullptr, *est_b2 = nullptr, *est_pooled = nullptr;
@@ -478,6 +482,20 @@ int run_stage(thia_model* m, int s, int nb, Trunk& t, const Tail* tail = nullptr
             }
         }
         if (!(bi == 0 && skip_c1)) TRY(run_conv(m, THIA_K_CONV, B.c1, x, nb, h, w, 1, 0, nullptr, true, false, ws.act[2]));
+        if (B.t3f && m->fuse_blocks && !B.has_sc && B.stride == 1) {
+            // 3x3 and the last 1x1 (+ residual) in one launch: the 256-channel tensor between them stays in LDS.  Worth it
+            // only where the 3x3 runs on the large tile anyway (enough 256-pixel tiles to fill the chip).
+            ConvArgs a;
+            fill_conv_args(m, a, B.c2, ws.act[2], nb, h, w, 1, 1, nullptr, true, ws.act[3], nullptr, -1, nullptr);
+            a.tail_w = B.t3f; a.tail_b = B.c3.b; a.tail_res = x; a.tail_out = y; a.tail_n = B.c3.co;
+            const long long tiles_l = ((long long)nb * h * w + 255) / 256;
+            if ((tiles_l >= 200 || m->fuse_always) && conv_tail_supported(a, m->precision)) {
+                Scope sc(m, THIA_K_CONV);
+                HIP_TRY(m, launch_conv(a, m->precision, false, m->stream));
+                std::swap(x, y);
+                continue;
+            }
+        }
         TRY(run_conv(m, THIA_K_CONV, B.c2, ws.act[2], nb, h, w, B.stride, 1, nullptr, true, false, ws.act[3]));
         if (B.has_sc) {
             // last 1x1 and projection shortcut share one accumulator: y = relu(W3 t2 + Ws x(strided) + b3 + bs)
@@ -802,6 +820,7 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
                 }
             } else {
                 if (!rc) rc = upload_layer(m, c3, nullptr, B.c3);
+                if (m->precision == 1 && w == 256 && !rc) rc = upload_fragments(m, c3, &B.t3f);
                 if (m->precision == 1 && (w == 64 || w == 128)) {   // widths the single-kernel bottleneck is written for
                     if (!rc) rc = upload_fragments(m, c1, &B.f1);
                     if (!rc) rc = upload_fragments(m, c2, &B.f2);
@@ -874,7 +893,8 @@ void thia_free_model(thia_model* m) {
             if (B.f2) (void)hipFree(B.f2);
             if (B.f3) (void)hipFree(B.f3);
             if (B.tf) (void)hipFree(B.tf);
-            B.f1 = B.f2 = B.f3 = B.tf = nullptr;
+            if (B.t3f) (void)hipFree(B.t3f);
+            B.f1 = B.f2 = B.f3 = B.tf = B.t3f = nullptr;
         }
     for (int e = 0; e < 5; ++e) {
         ExitUnit& E = m->ex[e];
@@ -1283,6 +1303,7 @@ int thia_op_conv(thia_model* m, const void* in, int n, int H, int W, int Cin, co
 int thia_set_fusion(thia_model* m, int on) {
     if (!m) return THIA_E_BADARG;
     m->fuse_blocks = on != 0;
+    m->fuse_always = on == 2;
     return THIA_OK;
 }
 

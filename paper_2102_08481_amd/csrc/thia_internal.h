@@ -64,6 +64,15 @@ struct ConvArgs {
     float* head_logits;
     float* head_deltas;
     int head_a;
+    // Optional expansion tail (bf16, Cout == 256, ReLU, large-tile kernel only; conv_tail_supported): the bottleneck's
+    // last 1x1 is applied to the block's own 256-pixel x 256-channel output tile while it sits in LDS, so neither the
+    // 256-channel tensor nor a second launch is needed: tail_out[m, n] = relu(tb[n] + sum_c Wt[n, c] t[m, c] + tail_res[m, n]),
+    // n < tail_n (a multiple of 512).  tail_w: bf16 [tail_n][256] in MFMA fragment order; tail_res / tail_out: bf16 [M][tail_n].
+    const void* tail_w = nullptr;  // null = no tail
+    const float* tail_b = nullptr;
+    const void* tail_res = nullptr;
+    void* tail_out = nullptr;
+    int tail_n = 0;
 };
 // precision 0: float tensors, fp32 MFMA; 1: bf16 tensors, bf16 MFMA with fp32 accumulation.
 // out_f32: store float outputs even when tensors are bf16.  Returns hipSuccess or the launch error.
@@ -72,6 +81,8 @@ hipError_t launch_conv(const ConvArgs& a, int precision, bool out_f32, hipStream
 bool conv_supported(const ConvArgs& a, int precision);
 // True if launch_conv would run `a` (bf16, with head_* set) on the kernel variant that has the fused predictors.
 bool conv_heads_supported(const ConvArgs& a, int precision);
+// True if `a` (bf16, with tail_* set) fits the kernel variant with the expansion tail.
+bool conv_tail_supported(const ConvArgs& a, int precision);
 
 // ---------------------------------------------------------------- single-kernel bottleneck (bf16, stride 1)
 // first == 0 (identity block): y = relu(W3 relu(W2 * relu(W1 x + b1) + b2) + b3 + x), x [N][H][W][4*width].

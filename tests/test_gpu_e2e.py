@@ -206,6 +206,33 @@ def test_fused_blocks_match_layer_by_layer_path(ep):
             assert torch.equal(a, b)
 
 
+def test_3x3_with_expansion_tail_matches_separate_layers():
+    """Identity blocks with 256-channel intermediates: the 3x3's kernel applies the last 1x1 (+ residual, ReLU) to its own
+    output tile in LDS.  Forced on at a test size (it is only taken at sizes with enough large tiles otherwise): the
+    exit tensor agrees with the layer-by-layer path to one bf16 ulp of its max, on ragged tile counts and several frames."""
+    spec = ModelSpec(precision=1, blocks=(1, 1, 3, 1), fc_dim=128, pre_nms=300, post_nms=100, n_classes=5)
+    m, blob = gpu_model(spec, 0xBEEF + 56)
+    fh = make_frames(SceneSpec(328, 424, 3, 4, 10, 10, 90), 46)            # 21 x 27 positions at stride 16: 1701 pixels, 7 tiles
+    frames = to_dev(fh)
+    res = []
+    m.set_debug(True)
+    for mode in (2, 0):
+        m.set_fusion(mode)
+        o = m.detect_chunk(frames, 3)
+        torch.cuda.synchronize()
+        res.append(([t.clone() for t in o], m.tap("feat").astype(np.float32)))
+    m.set_fusion(1)
+    m.set_debug(False)
+    assert np.isfinite(res[0][1]).all()
+    assert relerr(res[0][1], res[1][1]) <= 2.0 ** -7, relerr(res[0][1], res[1][1])
+    Ck, Hk, Wk, _ = oracle.Model(blob).exit_shape(3, 328, 424)
+    ref = oracle.Model(blob).backbone(fh, 3)
+    assert relerr(nhwc_to_nchw(res[0][1].reshape(3, Hk, Wk, Ck)), ref) <= 2.0 ** -5
+    if np.array_equal(res[0][1], res[1][1]):
+        for a, b in zip(res[0][0], res[1][0]):
+            assert torch.equal(a, b)
+
+
 def test_fused_rpn_predictors_match_separate_launches():
     """At sizes where the RPN 3x3 runs on the large tile, its ReLU'd output stays in LDS and both 1x1
     predictors are applied in the same kernel.  Same bf16 rounding of the intermediate and same K order as
