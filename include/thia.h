@@ -257,6 +257,19 @@ int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, c
                     const thia_planner_cfg* cfg, int cap, int32_t* start, int32_t* len, int32_t* ep,
                     thia_plan_stats* stats, uint8_t* evaluated);
 
+/*
+ * A whole query (Sec. 3: query -> plan -> execution -> frame IDs; Table 2's form "select frameID where
+ * Count(class) >= t"): plans with thia_plan_query, executes the plan with thia_run_chunks and applies
+ * the predicate to the detections.  frames dev uint8 [n,3,H,W]; answers dev uint8 [n] (1 = the frame
+ * satisfies the predicate; frames of skipped chunks are 0).  plan outputs (start/len/ep, capacity cap)
+ * and stats as for thia_plan_query; they may be used to see which exit answered which frame.
+ * Blocks while planning; the execution and the predicate are enqueued on the model's stream.
+ * Allocates detection buffers for n frames for the duration of the call.
+ */
+int thia_run_query(thia_model* m, const uint8_t* frames, int n, int H, int W, const thia_query* q,
+                   const thia_planner_cfg* cfg, uint8_t* answers, int cap, int32_t* start, int32_t* len,
+                   int32_t* ep, thia_plan_stats* stats);
+
 const char* thia_last_error(const thia_model* m);
 
 /* ---------------------------------------------------------------- inspection

@@ -37,6 +37,11 @@ def thia_plan_query(model, frames, label, min_count, min_score=0.0, cfg=None):
     return model.plan_query(frames, label, min_count, min_score, cfg)
 
 
+def thia_run_query(model, frames, label, min_count, min_score=0.0, cfg=None):
+    """Plan, execute and apply the predicate: returns (answers cuda uint8 [n], plan, stats)."""
+    return model.run_query(frames, label, min_count, min_score, cfg)
+
+
 def thia_plan_from_flags(flags, cfg=None):
     """The planner on a host table of per-frame, per-exit answers [n, E]."""
     return plan_from_flags(flags, cfg)

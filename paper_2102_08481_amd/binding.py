@@ -25,7 +25,7 @@ KERNEL_CLASSES = ["stem", "pool", "conv", "fc", "topk", "nms", "roialign", "post
 EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_microbatch", "thia_get_info",
            "thia_detect_chunk", "thia_detect_all_exits", "thia_run_plan", "thia_run_chunks",
            "thia_planner_defaults", "thia_eval_predicate", "thia_plan_from_flags", "thia_plan_query",
-           "thia_set_estimator", "thia_estimate_exit", "thia_answer_counts", "thia_metrics_from_counts", "thia_last_error", "thia_set_debug", "thia_debug_tap",
+           "thia_set_estimator", "thia_estimate_exit", "thia_run_query", "thia_answer_counts", "thia_metrics_from_counts", "thia_last_error", "thia_set_debug", "thia_debug_tap",
            "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
            "thia_op_rpn_proposals", "thia_op_nms", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
            "thia_op_stem", "thia_op_bottleneck", "thia_op_bottleneck_tail", "thia_set_fusion"]
@@ -92,6 +92,8 @@ def lib():
     L.thia_answer_counts.argtypes = [vp, vp, vp, i32, vp]
     L.thia_metrics_from_counts.argtypes = [vp, vp]
     L.thia_metrics_from_counts.restype = None
+    L.thia_run_query.argtypes = [vp, vp, i32, i32, i32, C.POINTER(ThiaQuery), C.POINTER(ThiaPlannerCfg), vp, i32, vp, vp, vp,
+                                 C.POINTER(ThiaPlanStats)]
     L.thia_last_error.argtypes = [vp]
     L.thia_last_error.restype = C.c_char_p
     L.thia_set_debug.argtypes = [vp, i32]
@@ -317,6 +319,20 @@ class Model:
         self._check(lib().thia_plan_query(self._h, _ptr(frames), n, H, W, C.byref(q), C.byref(cfg), cap, bufs[0].ctypes.data,
                                           bufs[1].ctypes.data, bufs[2].ctypes.data, C.byref(stats), ev.ctypes.data))
         return _plan_result(bufs, stats, ev, n)
+
+    def run_query(self, frames, label, min_count, min_score=0.0, cfg=None):
+        """thia_run_query -> (answers cuda uint8 [n], plan, stats dict)."""
+        _dev(frames, torch.uint8)
+        n, c, H, W = frames.shape
+        assert c == 3
+        cfg = cfg or planner_cfg()
+        cap, bufs, stats, _ = _plan_buffers(n, cfg)
+        answers = torch.zeros(n, dtype=torch.uint8, device=self.device)
+        q = ThiaQuery(label, min_count, min_score)
+        self._check(lib().thia_run_query(self._h, _ptr(frames), n, H, W, C.byref(q), C.byref(cfg), _ptr(answers), cap,
+                                         bufs[0].ctypes.data, bufs[1].ctypes.data, bufs[2].ctypes.data, C.byref(stats)))
+        plan, st, _ = _plan_result(bufs, stats, np.zeros(max(n, 1), np.uint8), n)
+        return answers, plan, st
 
     # -- inspection
     def set_debug(self, on):

@@ -1172,6 +1172,29 @@ int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, c
     return THIA_OK;
 }
 
+int thia_run_query(thia_model* m, const uint8_t* frames, int n, int H, int W, const thia_query* q, const thia_planner_cfg* cfg,
+                   uint8_t* answers, int cap, int32_t* start, int32_t* len, int32_t* ep, thia_plan_stats* stats) {
+    if (!m) return THIA_E_BADARG;
+    if (n > 0 && !answers) return fail(m, THIA_E_BADARG, "null pointer");
+    TRY(thia_plan_query(m, frames, n, H, W, q, cfg, cap, start, len, ep, stats, nullptr));
+    if (n == 0) return THIA_OK;
+    const size_t D = (size_t)m->D;
+    float *ob = nullptr, *os = nullptr;
+    int32_t* ol = nullptr;
+    auto release = [&]() { (void)hipFree(ob); (void)hipFree(os); (void)hipFree(ol); };
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ob), (size_t)n * D * 16);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&os), (size_t)n * D * 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ol), (size_t)n * D * 4);
+    if (e != hipSuccess) { release(); return fail(m, THIA_E_NOMEM, std::string("query buffers: ") + hipGetErrorString(e)); }
+    int rc = thia_run_chunks(m, frames, n, H, W, stats->n_chunks, start, len, ep, ob, os, ol);
+    if (rc == THIA_OK) rc = thia_eval_predicate(m, ol, os, n, q, answers);
+    const hipError_t e2 = hipStreamSynchronize(m->stream);   // the buffers are released below
+    release();
+    if (rc != THIA_OK) return rc;
+    if (e2 != hipSuccess) return fail_hip(m, e2, "thia_run_query");
+    return THIA_OK;
+}
+
 const char* thia_last_error(const thia_model* m) { return m ? m->err.c_str() : "null model"; }
 
 int thia_set_debug(thia_model* m, int enable) {

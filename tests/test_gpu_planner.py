@@ -222,3 +222,28 @@ def test_plan_query_with_estimator_equals_the_oracle_planner_on_the_same_estimat
     assert plan == plan_o
     assert np.flatnonzero(ev).tolist() == sorted(pl.evaluated) and st["samples_reused"] == pl.reused
     print("plan with estimator:", plan, st)
+
+
+def test_run_query_is_plan_then_execution_then_predicate():
+    m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
+    n = 150
+    frames = to_dev(make_frames(SceneSpec(160, 224, n, 4, 10, 10, 90), 48))
+    label, t = _pick_query(m, frames)
+    kw = dict(min_chunk=9, final_span=2)
+    answers, plan, st = m.run_query(frames, label, t, 0.0, planner_cfg(**kw))
+    torch.cuda.synchronize()
+    plan2, st2, _ = m.plan_query(frames, label, t, 0.0, planner_cfg(**kw))
+    assert plan == plan2 and st == st2
+    b, s, l = m.run_chunks(frames, plan)
+    want = m.eval_predicate(l, s, label, t, 0.0)
+    torch.cuda.synchronize()
+    assert torch.equal(answers, want)
+    # against the oracle's metrics: frames of skipped chunks answer "no"
+    flags = _answers_of_every_frame(m, frames, label, t, 0.0)
+    exp = np.zeros(n, bool)
+    for a, ln, ep in plan:
+        if ep:
+            exp[a:a + ln] = flags[a:a + ln, ep - 1]
+    assert np.array_equal(answers.cpu().numpy().astype(bool), exp)
+    e, plan0, st0 = m.run_query(frames[:0], label, t)
+    assert e.numel() == 0 and plan0 == []
