@@ -338,6 +338,19 @@ int thia_op_rpn_proposals(thia_model* m, const float* logits, const float* delta
 int thia_op_nms(thia_model* m, const float* boxes, const int32_t* counts, int n, int cap, float thr, int max_keep,
                 int32_t* out_keep, int32_t* out_n);
 
+/* thia_op_nms for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels, same
+ * results, but the k x k overlap bit matrix lives in a fixed 8 MiB device buffer inside the
+ * library (one per GPU, resolved when a model is loaded on that GPU, held until the process
+ * ends), and the call neither allocates, frees nor waits: it enqueues on the model's stream
+ * and returns.  Limit: n * cap * ceil(cap / 64) <= 2^20 (e.g. 32 frames at cap 1000, 16 at
+ * cap 2000, 4 at cap 4096); beyond it THIA_E_SHAPE and nothing is enqueued.  Every word of the
+ * buffer that a call reads it has written itself, so nothing needs clearing between calls.  All
+ * calls on one GPU share the buffer: calls that overlap in time on one GPU (different streams or
+ * models) race; calls on one stream are ordered and safe. */
+int thia_op_nms_noalloc(thia_model* m, const float* boxes, const int32_t* counts, int n, int cap, float thr,
+                        int max_keep, int32_t* out_keep, int32_t* out_n);
+
 /* ROIAlign (P x P bins, 2 x 2 samples, texel centres at j + 0.5) of rois [n,post,4]
  * (pixels) on feat T [n,Hk,Wk,Ch] with the given stride; out T [n,post,P*P,Ch]. */
 int thia_op_roialign(thia_model* m, const void* feat, const float* rois, int n, int Hk, int Wk, int stride, void* out);

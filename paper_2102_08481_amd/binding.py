@@ -27,7 +27,7 @@ EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_mi
            "thia_planner_defaults", "thia_eval_predicate", "thia_plan_from_flags", "thia_plan_query",
            "thia_set_estimator", "thia_estimate_exit", "thia_run_query", "thia_answer_counts", "thia_metrics_from_counts", "thia_last_error", "thia_set_debug", "thia_debug_tap",
            "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
-           "thia_op_rpn_proposals", "thia_op_nms", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
+           "thia_op_rpn_proposals", "thia_op_nms", "thia_op_nms_noalloc", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
            "thia_op_stem", "thia_op_bottleneck", "thia_op_bottleneck_tail", "thia_set_fusion"]
 
 
@@ -105,6 +105,7 @@ def lib():
     L.thia_profile_end.argtypes = [vp]
     L.thia_op_rpn_proposals.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     L.thia_op_nms.argtypes = [vp, vp, vp, i32, i32, C.c_float, i32, vp, vp]
+    L.thia_op_nms_noalloc.argtypes = [vp, vp, vp, i32, i32, C.c_float, i32, vp, vp]
     L.thia_op_roialign.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
     L.thia_op_select_detections.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp]
     L.thia_op_conv.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i32, i32, i32, vp, i32, i32, vp]
@@ -382,6 +383,15 @@ class Model:
         keep = torch.empty((n, max_keep), dtype=torch.int32, device=self.device)
         cnt = torch.empty((n,), dtype=torch.int32, device=self.device)
         self._check(lib().thia_op_nms(self._h, _ptr(boxes), _ptr(counts), n, cap, thr, max_keep, _ptr(keep), _ptr(cnt)))
+        return keep, cnt
+
+    def op_nms_noalloc(self, boxes, counts, thr, max_keep, keep, cnt):
+        """Same as op_nms, into caller tensors keep int32 [n,max_keep] and cnt int32 [n]; the library allocates nothing."""
+        _dev(boxes, torch.float32), _dev(counts, torch.int32), _dev(keep, torch.int32), _dev(cnt, torch.int32)
+        n, cap = boxes.shape[0], boxes.shape[1]
+        if tuple(keep.shape) != (n, max_keep) or tuple(cnt.shape) != (n,):
+            raise ValueError("keep must be [n, max_keep] and cnt [n]")
+        self._check(lib().thia_op_nms_noalloc(self._h, _ptr(boxes), _ptr(counts), n, cap, thr, max_keep, _ptr(keep), _ptr(cnt)))
         return keep, cnt
 
     def op_roialign(self, feat, rois, stride):

@@ -104,6 +104,13 @@ struct thia_model {
 
 namespace {
 
+// Overlap bit matrix of thia_op_nms_noalloc: fixed device storage, one copy per GPU, held until the process ends.
+// Host code never uses this name as an address: it resolves the current device's copy once (nms_scratch_ptr).
+constexpr size_t kNmsScratchWords = (size_t)1 << 20;   // 8 MiB
+static __device__ __align__(256) unsigned long long nms_scratch[kNmsScratchWords];
+constexpr int kMaxDevices = 64;
+uint64_t* g_nms_scratch_ptr[kMaxDevices] = {};
+
 int fail(thia_model* m, int code, const std::string& msg) {
     if (m) m->err = msg;
     return code;
@@ -116,6 +123,21 @@ int fail_hip(thia_model* m, hipError_t e, const char* what) {
         hipError_t e__ = (expr);                                  \
         if (e__ != hipSuccess) return fail_hip((m), e__, #expr);  \
     } while (0)
+
+// Device address of the current GPU's copy of nms_scratch (each GPU holds its own copy at its own address).
+int nms_scratch_ptr(thia_model* m, uint64_t** out) {
+    int dev = -1;
+    HIP_TRY(m, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(m, THIA_E_HIP, "device ordinal beyond the table of fixed buffers");
+    if (!g_nms_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(m, hipGetSymbolAddress(&p, HIP_SYMBOL(nms_scratch)));
+        if (!p) return fail(m, THIA_E_HIP, "hipGetSymbolAddress returned a null address");
+        g_nms_scratch_ptr[dev] = static_cast<uint64_t*>(p);
+    }
+    *out = g_nms_scratch_ptr[dev];
+    return THIA_OK;
+}
 
 inline int conv_out(int n, int k, int s, int p) { return (n + 2 * p - k) / s + 1; }
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
@@ -754,6 +776,10 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
     m->fc_dim = h[30]; m->Kc = h[31]; m->score_thr = hf[32]; m->det_thr = hf[33]; m->D = h[34];
     m->mean = hf[35]; m->stdv = hf[36]; m->base_width = h[37];
     auto bad = [&](int code) { thia_free_model(m); return code; };
+    {   // resolve this GPU's copy of the fixed NMS buffer now, so that thia_op_nms_noalloc only ever reads the table
+        uint64_t* unused = nullptr;
+        if (nms_scratch_ptr(m, &unused) != THIA_OK) return bad(THIA_E_HIP);
+    }
     if ((m->precision != 0 && m->precision != 1) || m->anc.n_sizes < 1 || m->anc.n_sizes > 8 || m->anc.n_ratios < 1 ||
         m->anc.n_ratios > 4 || m->pre < 1 || m->pre > 4096 || m->post < 1 || m->post > m->pre || m->Kc < 2 || m->Kc > 256 ||
         m->D < 1 || m->D > 512 || m->pool < 1 || m->pool > 16 || !(m->stdv > 0.f))
@@ -1279,6 +1305,19 @@ int thia_op_nms(thia_model* m, const float* boxes, const int32_t* counts, int n,
     (void)hipFree(mask);
     if (e != hipSuccess) return fail_hip(m, e, "launch_nms");
     if (e2 != hipSuccess) return fail_hip(m, e2, "nms sync");
+    return THIA_OK;
+}
+
+int thia_op_nms_noalloc(thia_model* m, const float* boxes, const int32_t* counts, int n, int cap, float thr, int max_keep,
+                        int32_t* out_keep, int32_t* out_n) {
+    if (!m || !boxes || !counts || !out_keep || !out_n || n <= 0) return fail(m, THIA_E_BADARG, "bad arguments");
+    if (cap < 1 || cap > 4096 || max_keep < 1 || max_keep > 4096) return fail(m, THIA_E_SHAPE, "cap and max_keep must be within 1..4096");
+    const size_t words = (size_t)(cap + 63) / 64;
+    if ((size_t)n * cap * words > kNmsScratchWords)
+        return fail(m, THIA_E_SHAPE, "thia_op_nms_noalloc: n * cap * ceil(cap / 64) exceeds the 1 Mi words (8 MiB) of the fixed overlap-matrix buffer");
+    uint64_t* mask = nullptr;
+    TRY(nms_scratch_ptr(m, &mask));
+    HIP_TRY(m, launch_nms(boxes, counts, n, cap, thr, max_keep, mask, out_keep, out_n, nullptr, m->stream));
     return THIA_OK;
 }
 
