@@ -96,6 +96,17 @@ __device__ inline void store8(float* p, const float r[8]) {
     *reinterpret_cast<f32x4_t*>(p + 4) = hi;
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l's bytes land at lds + 16 l (lds is uniform over the
+// wavefront).  Counted by vmcnt like any vector memory load.  (The builtin exists in the device pass only.)
+__device__ inline void load_to_lds16(const void* g, void* lds) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_global_load_lds(g, lds, 16, 0, 0);
+#endif
+}
+
+// 16 zero bytes (and some more) in global memory: what a padded filter tap fetches on the direct-to-LDS path
+__device__ __align__(256) unsigned char g_zero_page[256];
+
 // compile-time loop: the body sees the index as a constant (keeps accumulator indices static)
 template <int I, int N, typename F>
 __device__ inline void static_for(F&& f) {
@@ -116,7 +127,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     constexpr int CPR = BKB / 16;              // 16-byte chunks per tile row
     constexpr int RPP = NT / CPR;              // tile rows covered by one pass of the block's threads
     constexpr int PB = BM / RPP, PA = BN / RPP;  // chunks staged per thread (activations, weights)
-    constexpr int LDS_ROW = BKB + 16;          // padded LDS row pitch (an odd multiple of 16 bytes)
+    // DIRECT (128-byte K rows): operand tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane l of
+    // a wavefront instruction lands at the instruction's LDS base + 16 l, i.e. one instruction fills 8 whole tile rows),
+    // without staging registers or LDS-write instructions.  Rows are unpadded; instead a lane fetches the 16-byte chunk
+    // (slot ^ swz(row)) of its row, swz(row) = (row & 7) ^ ((row >> 3) & 1), so that the fragment reads of 16 consecutive
+    // rows at one logical chunk fall on 16 different 16-byte slots modulo 256 bytes (and any 8 aligned rows on 8 modulo 128).
+    constexpr bool DIRECT = BKB == 128;
+    constexpr int LDS_ROW = DIRECT ? BKB : BKB + 16;   // staged path: padded row pitch (an odd multiple of 16 bytes)
     constexpr int KK = BKB / 32;               // MFMA k-steps per tile row (32 bytes = 2 lane halves x 16 bytes)
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront tile (pixels x channels)
     constexpr int TM = WM / 32, TN = WN / 32;  // 32x32 MFMA tiles per wavefront
@@ -126,6 +143,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     constexpr int EPITCH = WN * 4 + 16;        // epilogue: padded fp32 row pitch in LDS (bytes)
     constexpr bool PREFETCH_RES = TM * NIT <= 8;  // residual tile small enough to hold across the K loop
     static_assert(WAVES_M * WAVES_N * 32 * EPITCH <= 2 * (BN + BM) * LDS_ROW, "epilogue tile must fit in the pipeline buffers");
+    static_assert(!DIRECT || (CPR == 8 && (NT / 64) % 2 == 0), "direct loads: 8 chunks per row, an even number of wavefronts");
     static_assert(BM % RPP == 0 && BN % RPP == 0, "tile rows must be a multiple of the rows staged per pass");
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -151,7 +169,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     const T* __restrict__ wgt = static_cast<const T*>(a.w);
 
     // ---- per-thread load coordinates: tile row lrow + RPP*p, 16-byte chunk lchunk of the row
-    const int lrow = t / CPR, lchunk = t % CPR;
+    const int lrow = t / CPR;
+    // staged path: the thread's chunk of the row; direct path: the chunk whose LDS slot is t % CPR (see DIRECT above;
+    // row & 7 = lane / 8 and (row >> 3) & 1 = wavefront & 1 for every row lrow + RPP * p of this thread)
+    const int lchunk = DIRECT ? ((t % CPR) ^ ((lane >> 3) ^ (wv & 1))) & 7 : t % CPR;
     size_t b_base[PB];
     size_t b_base2[DUAL ? PB : 1];
     const T* __restrict__ in2 = static_cast<const T*>(a.in2);
@@ -245,6 +266,39 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
         }
     };
 
+    // direct path: request K tile kt into LDS buffer buf (PA + PB wavefront instructions, each filling 8 rows)
+    auto issue_tiles = [&](int kt, int buf) {
+        unsigned char* dA = sA + (size_t)(buf * BN + (wv * 64) / CPR) * LDS_ROW;
+        unsigned char* dB = sB + (size_t)(buf * BM + (wv * 64) / CPR) * LDS_ROW;
+        if constexpr (ONE) {
+            const int kt1 = a.Cin / BK;  // K tiles of the first source
+            if (!DUAL || kt < kt1) {
+#pragma unroll
+                for (int p = 0; p < PB; ++p)
+                    load_to_lds16(in + b_base[p] + (size_t)kt * BK, dB + (size_t)(RPP * p) * LDS_ROW);
+            } else {
+#pragma unroll
+                for (int p = 0; p < PB; ++p)
+                    load_to_lds16(in2 + b_base2[DUAL ? p : 0] + (size_t)(kt - kt1) * BK, dB + (size_t)(RPP * p) * LDS_ROW);
+            }
+        } else {
+            const int tap = kt / cin_tiles;
+            const int c0 = (kt - tap * cin_tiles) * BK;
+            const int ky = tap / a.kw, kx = tap - ky * a.kw;
+            const long long tap_off = ((long long)ky * a.W + kx) * a.Cin + c0;   // uniform over the block
+#pragma unroll
+            for (int p = 0; p < PB; ++p) {
+                // a padded tap reads 16 zero bytes instead
+                const bool ok = (b_taps[ONE ? 0 : p] >> tap) & 1u;
+                const T* src = ok ? in + (b_off0[ONE ? 0 : p] + tap_off) : reinterpret_cast<const T*>(g_zero_page);
+                load_to_lds16(src, dB + (size_t)(RPP * p) * LDS_ROW);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            load_to_lds16(wgt + a_base[p] + (size_t)kt * BK, dA + (size_t)(RPP * p) * LDS_ROW);
+    };
+
     f32x16_t acc[TN][TM];
 #pragma unroll
     for (int i = 0; i < TN; ++i)
@@ -268,22 +322,30 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     }
 
     const int frag_row = lane & 31, frag_off = (lane >> 5) * 16;
+    // direct path: slot of logical chunk c in this lane's fragment row is c ^ frag_swz (tile row offsets are multiples of 16)
+    const int frag_swz = (frag_row & 7) ^ ((frag_row >> 3) & 1);
+    struct Frags { u32x4_t a[TN], b[TM]; };
+    auto read_frags = [&](int buf, int kk, Frags& f) {
+        const int koff = DIRECT ? ((2 * kk + (lane >> 5)) ^ frag_swz) * 16 : kk * 32 + frag_off;
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+            f.a[i] = *reinterpret_cast<const u32x4_t*>(sA + (size_t)(buf * BN + wn * WN + i * 32 + frag_row) * LDS_ROW + koff);
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+            f.b[j] = *reinterpret_cast<const u32x4_t*>(sB + (size_t)(buf * BM + wm * WM + j * 32 + frag_row) * LDS_ROW + koff);
+    };
+    auto mma_frags = [&](const Frags& f) {
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j) mma_step<T>(acc[i][j], f.a[i], f.b[j]);
+    };
     auto compute = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            u32x4_t fa[TN], fb[TM];
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-                fa[i] = *reinterpret_cast<const u32x4_t*>(
-                    sA + (size_t)(buf * BN + wn * WN + i * 32 + frag_row) * LDS_ROW + kk * 32 + frag_off);
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-                fb[j] = *reinterpret_cast<const u32x4_t*>(
-                    sB + (size_t)(buf * BM + wm * WM + j * 32 + frag_row) * LDS_ROW + kk * 32 + frag_off);
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-#pragma unroll
-                for (int j = 0; j < TM; ++j) mma_step<T>(acc[i][j], fa[i], fb[j]);
+            Frags f;
+            read_frags(buf, kk, f);
+            mma_frags(f);
         }
     };
 
@@ -294,6 +356,33 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     // address unit takes ~20 cycles per 1 KiB instruction and a wavefront issues in order - but spreading the
     // loads between the MFMAs of the step, pinned with scheduling barriers, was measured 3-8 % slower, also
     // with the two wavefronts of a SIMD taking turns.)
+    if constexpr (DIRECT) {
+        // Two LDS buffers: tile kt + 1 is requested as soon as every wavefront has finished reading its buffer (the
+        // barrier that ends step kt - 1) and has the whole of step kt to arrive.
+        // The fragments of k-step kk + 1 are read while k-step kk is multiplied, and the barrier sits in front of a
+        // tile's LAST k-step: by then every wavefront has read the whole tile (so its buffer can be refilled) and still
+        // has a k-step of matrix work queued, which covers the first fragment reads of the next tile.
+        static_assert(KK % 2 == 0, "the fragment double buffer alternates per k-step");
+        issue_tiles(0, 0);
+        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+        __syncthreads();
+        if (KT > 1) issue_tiles(1, 1);
+        Frags f0, f1;
+        read_frags(0, 0, f0);
+        for (int kt = 0; kt < KT; ++kt) {
+            const int buf = kt & 1;
+            static_for<0, KK - 1>([&](auto kc) {
+                constexpr int kk = decltype(kc)::value;
+                read_frags(buf, kk + 1, (kk & 1) ? f0 : f1);
+                mma_frags((kk & 1) ? f1 : f0);
+            });
+            __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this thread's part of tile kt + 1 is in LDS
+            __syncthreads();
+            if (kt + 2 < KT) issue_tiles(kt + 2, buf);
+            if (kt + 1 < KT) read_frags(buf ^ 1, 0, f0);
+            mma_frags(f1);
+        }
+    } else {
     load_tiles(0, st0);
     store_tiles(0, st0);
     if (KT > 1) load_tiles(1, st0);
@@ -321,6 +410,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
         }
         __syncthreads();
     }
+    }
 
     // ---- fused RPN predictors (large bf16 tile only): the block's ReLU'd 256 x 256 tile, rounded to bf16 as the
     // stored tensor would be, stays in LDS and is contracted with the 1x1 predictor weights right away.
@@ -330,7 +420,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
             constexpr int YP = BN * 2 + 16;            // LDS row pitch of the bf16 tile
             constexpr int HKS = BN / 16;               // k-steps of the predictor contraction (16)
             constexpr int HP = 96 * 4 + 16;            // fp32 row pitch of the per-wavefront output tile
-            static_assert(BM * YP <= 2 * (BN + BM) * LDS_ROW && 32 * HP <= 32 * YP, "tile and output staging fit");
+            static_assert(BM * YP <= 160 * 1024 && 32 * HP <= 32 * YP, "tile and output staging fit (launch_cfg requests BM * YP bytes)");
             const u32x4_t* __restrict__ hwf = reinterpret_cast<const u32x4_t*>(a.head_w) + lane;
 #pragma unroll
             for (int j = 0; j < TM; ++j)
@@ -646,7 +736,10 @@ template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, int MOD
 static hipError_t launch_cfg(const ConvArgs& a, hipStream_t s) {
     static bool attr_set = false;
     // (the expansion tail parks an unpadded 256 x 512-byte tile and gives each of the 8 wavefronts 4 KB beside it: the CU's whole LDS)
-    const size_t lds = MODE == 4 ? (size_t)160 * 1024 : (size_t)2 * (BN + BM) * (BKB + 16);
+    const size_t pipe = (size_t)2 * (BN + BM) * (BKB == 128 ? BKB : BKB + 16);
+    // (the fused-predictor path of the large bf16 tile parks a padded 256 x 528-byte tile, more than the two pipeline buffers)
+    const size_t heads = (std::is_same<T, bf16_t>::value && BM == 256 && BN == 256 && MODE == 0) ? (size_t)BM * (BN * 2 + 16) : 0;
+    const size_t lds = MODE == 4 ? (size_t)160 * 1024 : (pipe > heads ? pipe : heads);
     auto kern = conv_igemm_kernel<T, BM, BN, BKB, WAVES_M, WAVES_N, MODE, OutT>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
