@@ -14,9 +14,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-RES_GAIN, PRED_STD = 0.25, 0.01        # data-only gains of the synthetic weights
 PEAK_BF16_TFLOPS = 2500.0              # MI355X dense bf16 MFMA peak
-CONV_CLASSES = ("conv", "fc")          # launches of the implicit-GEMM MFMA kernels (layer-by-layer and fused blocks)
+CONV_CLASSES = ("conv", "rpn", "fc")   # launches of the implicit-GEMM MFMA kernels: backbone (layers and fused blocks), exit unit, FCs
 
 
 def conv_out(n, k, s, p):
@@ -71,16 +70,32 @@ def conv_layer_bytes(spec, H, W, ep, esz=2):
     return total
 
 
+def kernel_sources_sha1():
+    """Content hash of the library's kernel sources: the committed counter summary names the sources it was measured on."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2102_08481_amd", "csrc")
+    h = hashlib.sha1()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()
+
+
 def measured_traffic(workload_key):
-    """HBM bytes per step of the dominant kernel from the committed rocprofv3 --pmc summary, if present."""
+    """HBM bytes per step of the dominant kernel class from the committed rocprofv3 --pmc summary; None when there is no
+    summary or when it was taken on other kernel sources than the ones in this tree (a stale figure is worse than none)."""
     path = os.path.join(ROOT, "profiles", "mfma_kernels_config3_sweep_pmc_fetch_write.txt")
+    value, stamp = None, None
     try:
         for line in open(path):
             if line.startswith("TRAFFIC_BYTES_PER_STEP " + workload_key):
-                return float(line.split()[2])
+                value = float(line.split()[2])
+            if line.startswith("KERNEL_SOURCES_SHA1 "):
+                stamp = line.split()[1]
     except OSError:
-        pass
-    return None
+        return None
+    return value if stamp == kernel_sources_sha1() else None
 
 
 def derive_query(labels, scores):
@@ -103,11 +118,11 @@ def planner_workload(args):
     import numpy as np
     import torch
     from paper_2102_08481_amd import planner_cfg, thia_load_model
-    from thia_synth import CONFIGS, SceneSpec, make_blob, make_frames
+    from thia_synth import CONFIGS, SceneSpec, make_blob, make_frames, recipe_for
 
     cfg = CONFIGS[3]
     spec, H, W, N, seg = cfg.model, 540, 960, args.video_frames, 256
-    model = thia_load_model(make_blob(spec, cfg.weight_seed, res_gain=RES_GAIN, pred_std=PRED_STD), spec.n_exits)
+    model = thia_load_model(make_blob(spec, cfg.weight_seed, **recipe_for(spec)), spec.n_exits)
     frames = torch.empty((N, 3, H, W), dtype=torch.uint8, device="cuda")
     for i, s0 in enumerate(range(0, N, seg)):         # scenes of 256 frames, alternately sparse and busy
         k = min(seg, N - s0)
@@ -196,12 +211,12 @@ def main():
     import numpy as np
     import torch
     from paper_2102_08481_amd import thia_load_model, thia_detect_chunk
-    from thia_synth import CONFIGS, make_blob, make_frames
+    from thia_synth import CONFIGS, make_blob, make_frames, recipe_for
 
     cfg = CONFIGS[3]
     spec, scene = cfg.model, cfg.scene
     B, H, W = scene.n_frames, scene.height, scene.width
-    blob = make_blob(spec, cfg.weight_seed, res_gain=RES_GAIN, pred_std=PRED_STD)
+    blob = make_blob(spec, cfg.weight_seed, **recipe_for(spec))
     frames_h = make_frames(scene, cfg.frame_seed)
     model = thia_load_model(blob, spec.n_exits)
     if args.microbatch:
@@ -234,15 +249,19 @@ def main():
 
     # ---- the same K steps again with the library's HIP events around every kernel launch (two event
     # records per launch, a few per cent slower): per-kernel-class device time for the roofline figure
+    # (one exit at a time, so that every class time is also known per exit)
     model.profile_begin()
     torch.cuda.synchronize()
     t2 = time.perf_counter()
-    for k in range(args.steps):
-        step()
+    prof_exit = {}
+    for ep in exits:
+        for k in range(args.steps):
+            thia_detect_chunk(model, frames, ep, out)
+        prof_exit[ep] = model.profile_read()
     torch.cuda.synchronize()
     t3 = time.perf_counter()
-    prof = model.profile_read()
     model.profile_end()
+    prof = {c: (sum(prof_exit[ep][c][0] for ep in exits), sum(prof_exit[ep][c][1] for ep in exits)) for c in prof_exit[exits[0]]}
 
     # ---- beside the metric: the same batch with every exit evaluated in ONE backbone pass (what the planner's
     # exit selection needs on its sampled frames); the sweep above pays for the shared stages once per exit
@@ -296,6 +315,16 @@ def main():
         "flops_per_step": conv_flops_step, "launches_per_step": conv_launches, "avg_launch_us": 1e3 * conv_ms / max(conv_launches, 1),
         "kernel_ms_per_step": conv_ms,
     }
+    # the target's own figure: backbone convolutions alone at the last exit (flops of the stages only; the stem, the
+    # exit unit and the box head are neither in the flops nor in the time)
+    ep_last = exits[-1]
+    bb_ms = prof_exit[ep_last]["conv"][0] / args.steps
+    bb_tflops = 2.0 * B * macs[ep_last][1] / (bb_ms * 1e-3) / 1e12
+    per_exit_class_ms = {f"EP{ep}": {c: v[0] / args.steps for c, v in prof_exit[ep].items()} for ep in exits}
+    per_exit_mfma = {}
+    for ep in exits:
+        ms_ = sum(prof_exit[ep][c][0] for c in CONV_CLASSES) / args.steps
+        per_exit_mfma[f"EP{ep}"] = 2.0 * B * (macs[ep][1] + macs[ep][2] + macs[ep][3]) / (ms_ * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
     class_ms = {k: v[0] / args.steps for k, v in prof.items()}
     alg_bytes_step = float(B * sum(conv_layer_bytes(spec, H, W, ep) for ep in exits))
     roofline["algorithmic_bytes_per_step"] = alg_bytes_step
@@ -310,7 +339,15 @@ def main():
     roi_bytes = float(len(exits) * B * spec.post_nms * spec.pool ** 2 * (spec.head_ch if spec.has_lateral else 0) * 2)
     nms_bytes = float(len(exits) * B * spec.pre_nms * ((spec.pre_nms + 63) // 64) * 8)
     hbm_side = {}
-    for name, nbytes in (("roialign", roi_bytes), ("nms", nms_bytes)):
+    # top-k: the objectness logits (4 bytes per anchor) read once per frame is what the selection needs; the radix
+    # select reads them once per pass it takes, so its rate against this figure is below its real read rate
+    topk_bytes = 0.0
+    for ep in exits:
+        h, w = conv_out(conv_out(H, 7, 2, 3), 3, 2, 1), conv_out(conv_out(W, 7, 2, 3), 3, 2, 1)
+        for _ in range(ep - 1):
+            h, w = conv_out(h, 3, 2, 1), conv_out(w, 3, 2, 1)
+        topk_bytes += 4.0 * B * h * w * spec.n_anchors
+    for name, nbytes in (("roialign", roi_bytes), ("nms", nms_bytes), ("topk", topk_bytes)):
         ms = class_ms.get(name, 0.0)
         if ms > 0 and nbytes > 0:
             gbs = nbytes / (ms * 1e-3) / 1e9
@@ -327,6 +364,11 @@ def main():
         "per_exit_frames_per_s": per_exit_fps,
         "per_exit_ms": {f"EP{ep}": ms for ep, ms in zip(exits, per_exit_ms)},
         "kernel_class_ms_per_step": class_ms,
+        "per_exit_kernel_class_ms": per_exit_class_ms,
+        "per_exit_mfma_frac": per_exit_mfma,
+        "ep4_backbone_mfma_frac": bb_tflops / PEAK_BF16_TFLOPS,
+        "ep4_backbone": {"what": f"backbone stage kernels of thia_detect_chunk(ep={ep_last}), {B} frames; flops = 2 x MACs of conv2_x..conv5_x",
+                         "kernel_ms": bb_ms, "tflops": bb_tflops, "target_frac": 0.5},
         "instrumented_ms_per_step": 1e3 * (t3 - t2) / args.steps,
         "roofline": roofline,
         "hbm_side_kernels": hbm_side,
@@ -338,6 +380,23 @@ def main():
         result["answers_vs_last_exit"] = agreement
     if not args.skip_cpu_baseline:
         import oracle
+        # max rel err (per tensor: max |gpu - ref| / max |ref|) of the bf16 path's RPN logits and deltas against the fp32
+        # oracle, frame 0 at every exit
+        o32 = oracle.Model(blob, precision=0)
+        model.set_debug(True)
+        errs = {}
+        for ep in exits:
+            model.detect_chunk(frames[:1].contiguous(), ep)
+            torch.cuda.synchronize()
+            ref = o32.detect(frames_h[:1], ep, taps=["rpn_logits", "rpn_deltas"])
+            e_ = 0.0
+            for tap in ("rpn_logits", "rpn_deltas"):
+                g_ = model.tap(tap).reshape(ref[tap].shape).astype(np.float64)
+                e_ = max(e_, float(np.abs(g_ - ref[tap]).max() / np.abs(ref[tap]).max()))
+            errs[f"EP{ep}"] = e_
+        model.set_debug(False)
+        result["max_rel_err"] = {"value": max(errs.values()), "per_exit": errs, "bar": 2e-2,
+                                 "what": "bf16 path vs fp32 oracle, RPN logits and box deltas of frame 0, max |gpu - ref| / max |ref| per tensor"}
         orc = oracle.Model(blob)
         tc0 = time.perf_counter()
         n_cpu = 3

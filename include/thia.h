@@ -132,7 +132,9 @@ int thia_detect_all_exits(thia_model* m, const uint8_t* frames, int n, int H, in
  * exit chunk_ep[c] (host int32 [n_chunks], 0 = skip).  Chunks are grouped by exit and
  * enqueued group by group on the one stream; outputs are written at the frames' own
  * positions, so out_* are laid out exactly as for n_chunks*chunk_len frames of
- * thia_detect_chunk, and each chunk's slice is bit-identical to a stand-alone call.
+ * thia_detect_chunk, and each chunk's slice is bit-identical to a stand-alone call.  Chunks of
+ * one exit share micro-batches (frames are independent): adjacent chunks are joined, and the
+ * remainders of chunks shorter than the micro-batch are gathered into a staging batch.
  */
 int thia_run_plan(thia_model* m, const uint8_t* frames, int n_chunks, int chunk_len, int H, int W,
                   const int32_t* chunk_ep, float* out_boxes, float* out_scores, int32_t* out_labels);
@@ -245,7 +247,7 @@ int thia_plan_from_flags(const uint8_t* flags, int n, int n_exits, const thia_pl
  * gathered and run through every exit in one backbone pass (thia_detect_all_exits) in batches
  * of eval_batch frames, the predicate is applied on the device, and only the per-frame answers
  * come back to the host.  Blocks until the plan is known (it synchronises the model's stream
- * once per batch) and allocates its staging buffers for the duration of the call.  Outputs as
+ * once per batch); its staging buffers belong to the model and only ever grow.  Outputs as
  * for thia_plan_from_flags.  Execute the plan with thia_run_chunks.
  * With cfg->use_estimator the samples go through thia_estimate_exit's path instead, and exit
  * k's true/false positives and false negatives are extrapolated as Sec. 5.3 states them:
@@ -263,8 +265,9 @@ int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, c
  * the predicate to the detections.  frames dev uint8 [n,3,H,W]; answers dev uint8 [n] (1 = the frame
  * satisfies the predicate; frames of skipped chunks are 0).  plan outputs (start/len/ep, capacity cap)
  * and stats as for thia_plan_query; they may be used to see which exit answered which frame.
- * Blocks while planning; the execution and the predicate are enqueued on the model's stream.
- * Allocates detection buffers for n frames for the duration of the call.
+ * Blocks while planning; the execution and the predicate are enqueued on the model's stream and
+ * the call returns without waiting for them.  The detections of the n frames go to a buffer
+ * that belongs to the model and only ever grows.
  */
 int thia_run_query(thia_model* m, const uint8_t* frames, int n, int H, int W, const thia_query* q,
                    const thia_planner_cfg* cfg, uint8_t* answers, int cap, int32_t* start, int32_t* len,
@@ -309,8 +312,12 @@ size_t thia_debug_tap_bytes(const thia_model* m, int which);
  * and launches[THIA_K_COUNT] (host).  Profiling adds two event records per launch.
  */
 enum {
-    THIA_K_STEM = 0, THIA_K_POOL = 1, THIA_K_CONV = 2 /* backbone+lateral+RPN implicit GEMMs */,
-    THIA_K_FC = 3, THIA_K_TOPK = 4, THIA_K_NMS = 5, THIA_K_ROIALIGN = 6, THIA_K_POST = 7, THIA_K_COUNT = 8
+    THIA_K_STEM = 0, THIA_K_POOL = 1,
+    THIA_K_CONV = 2,  /* backbone stages: implicit-GEMM layers and single-kernel blocks (a stage's last block that also
+                         applies the exit's lateral to its own output tile counts here as a whole)                     */
+    THIA_K_FC = 3, THIA_K_TOPK = 4, THIA_K_NMS = 5, THIA_K_ROIALIGN = 6, THIA_K_POST = 7,
+    THIA_K_RPN = 8,   /* exit unit's implicit GEMMs in front of the proposals: lateral, RPN 3x3, RPN predictors        */
+    THIA_K_COUNT = 9
 };
 int thia_profile_begin(thia_model* m);
 int thia_profile_read(thia_model* m, float* ms, int32_t* launches);

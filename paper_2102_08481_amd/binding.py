@@ -20,7 +20,7 @@ TAPS = {"feat": 0, "head_feat": 1, "rpn_logits": 2, "rpn_deltas": 3, "topk_idx":
         "rois": 7, "roi_n": 8, "roi_feat": 9, "cls_logits": 10, "box_deltas": 11, "cand_scores": 12, "cand_boxes": 13,
         "det_n": 14}
 _TAP_ELEM = {"feat": "T", "head_feat": "T", "roi_feat": "T", "topk_idx": "i", "prop_n": "i", "roi_n": "i", "det_n": "i"}
-KERNEL_CLASSES = ["stem", "pool", "conv", "fc", "topk", "nms", "roialign", "post"]
+KERNEL_CLASSES = ["stem", "pool", "conv", "fc", "topk", "nms", "roialign", "post", "rpn"]
 
 EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_microbatch", "thia_get_info",
            "thia_detect_chunk", "thia_detect_all_exits", "thia_run_plan", "thia_run_chunks",

@@ -682,11 +682,10 @@ bool fused_block_supported(const FusedBlockArgs& a, int width) {
 }
 
 template <typename Kern>
-static hipError_t launch_fused_kernel(Kern kern, size_t lds, bool& attr_set, const FusedBlockArgs& a, hipStream_t s) {
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+static hipError_t launch_fused_kernel(Kern kern, size_t lds, const FusedBlockArgs& a, hipStream_t s) {
+    {
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     const long long tiles = (long long)a.N * ((a.H + TH - 1) / TH) * ((a.W + TW - 1) / TW);
     const long long grid = ((tiles + 7) / 8) * 8;
@@ -698,12 +697,11 @@ hipError_t launch_fused_block(const FusedBlockArgs& a, int width, hipStream_t s)
     if (!fused_block_supported(a, width)) return hipErrorInvalidValue;
     constexpr size_t lds64 = (size_t)NHP * ((64 * 2 + 16) + (64 * 2 + 16)) + (size_t)NPX * (64 * 2 + 16);
     constexpr size_t lds128 = (size_t)NH * 256 + (size_t)NPX * 256;
-    static bool set_first = false, set_ident = false, set_128 = false, set_t128 = false, set_t256 = false;
-    if (width == 128) return launch_fused_kernel(bottleneck_fused128_kernel, lds128, set_128, a, s);
-    if (a.tail_n == 128) return launch_fused_kernel(bottleneck_fused_kernel<64, false, 128>, lds64, set_t128, a, s);
-    if (a.tail_n == 256) return launch_fused_kernel(bottleneck_fused_kernel<64, false, 256>, lds64, set_t256, a, s);
-    if (a.first) return launch_fused_kernel(bottleneck_fused_kernel<64, true>, lds64, set_first, a, s);
-    return launch_fused_kernel(bottleneck_fused_kernel<64, false>, lds64, set_ident, a, s);
+    if (width == 128) return launch_fused_kernel(bottleneck_fused128_kernel, lds128, a, s);
+    if (a.tail_n == 128) return launch_fused_kernel(bottleneck_fused_kernel<64, false, 128>, lds64, a, s);
+    if (a.tail_n == 256) return launch_fused_kernel(bottleneck_fused_kernel<64, false, 256>, lds64, a, s);
+    if (a.first) return launch_fused_kernel(bottleneck_fused_kernel<64, true>, lds64, a, s);
+    return launch_fused_kernel(bottleneck_fused_kernel<64, false>, lds64, a, s);
 }
 
 // Host-side packing of a [Cout][K] bf16 weight matrix (K contiguous) into MFMA fragment order:

@@ -734,17 +734,15 @@ bool conv_supported(const ConvArgs& a, int precision) {
 
 template <typename T, int BM, int BN, int BKB, int WAVES_M, int WAVES_N, int MODE, typename OutT>
 static hipError_t launch_cfg(const ConvArgs& a, hipStream_t s) {
-    static bool attr_set = false;
     // (the expansion tail parks an unpadded 256 x 512-byte tile and gives each of the 8 wavefronts 4 KB beside it: the CU's whole LDS)
     const size_t pipe = (size_t)2 * (BN + BM) * (BKB == 128 ? BKB : BKB + 16);
     // (the fused-predictor path of the large bf16 tile parks a padded 256 x 528-byte tile, more than the two pipeline buffers)
     const size_t heads = (std::is_same<T, bf16_t>::value && BM == 256 && BN == 256 && MODE == 0) ? (size_t)BM * (BN * 2 + 16) : 0;
     const size_t lds = MODE == 4 ? (size_t)160 * 1024 : (pipe > heads ? pipe : heads);
     auto kern = conv_igemm_kernel<T, BM, BN, BKB, WAVES_M, WAVES_N, MODE, OutT>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     const long long M = (long long)a.N * a.Ho * a.Wo;
     const long long tiles = ((M + BM - 1) / BM) * ((a.Cout + BN - 1) / BN);

@@ -93,6 +93,14 @@ struct thia_model {
     float *est_w1t = nullptr, *est_b1 = nullptr, *est_w2 = nullptr, *est_b2 = nullptr, *est_pooled = nullptr;
     size_t est_pooled_cap = 0;
     Workspace ws;
+    // grow-only staging owned by the model (never allocated per call once large enough): gathered frames and their outputs
+    // for micro-batches that mix chunks (plan execution) or sampled frames (planner); per-frame answers; query outputs
+    struct Staging {
+        uint8_t* frames = nullptr; size_t frames_cap = 0;
+        float *ob = nullptr, *os = nullptr; int32_t* ol = nullptr; size_t out_rows = 0;   // rows of D detection slots
+        uint8_t* flags = nullptr; size_t flags_cap = 0;
+        int32_t* opt = nullptr; size_t opt_cap = 0;
+    } stg, qry, qout;
     bool debug = false;
     Tap taps[THIA_TAP_COUNT];
     bool profiling = false;
@@ -560,7 +568,7 @@ int run_heads(thia_model* m, const void* feat, int f0, int nb, int H, int W, int
     const void* hf = feat;
     if (m->has_lateral) {
         // (hf_ready: the stage's last block has already applied the lateral to its output tile)
-        if (!hf_ready) TRY(run_conv(m, THIA_K_CONV, E.lateral, feat, nb, g.Hk, g.Wk, 1, 0, nullptr, false, false, ws.hf));
+        if (!hf_ready) TRY(run_conv(m, THIA_K_RPN, E.lateral, feat, nb, g.Hk, g.Wk, 1, 0, nullptr, false, false, ws.hf));
         hf = ws.hf;
     }
     bool fused_heads = false;
@@ -570,14 +578,14 @@ int run_heads(thia_model* m, const void* feat, int f0, int nb, int H, int W, int
         fill_conv_args(m, a, E.rpn_conv, hf, nb, g.Hk, g.Wk, 1, 1, nullptr, true, ws.rpn_t, nullptr, -1, nullptr);
         a.head_w = E.head_f; a.head_b = E.head_fb; a.head_logits = ws.logits; a.head_deltas = ws.deltas; a.head_a = A;
         if (conv_heads_supported(a, m->precision)) {
-            Scope sc(m, THIA_K_CONV);
+            Scope sc(m, THIA_K_RPN);
             HIP_TRY(m, launch_conv(a, m->precision, false, m->stream));
             fused_heads = true;
         }
     }
     if (!fused_heads) {
-        TRY(run_conv(m, THIA_K_CONV, E.rpn_conv, hf, nb, g.Hk, g.Wk, 1, 1, nullptr, true, false, ws.rpn_t));
-        TRY(run_conv(m, THIA_K_CONV, E.rpn_head, ws.rpn_t, nb, g.Hk, g.Wk, 1, 0, nullptr, false, true, ws.logits, ws.deltas, A));
+        TRY(run_conv(m, THIA_K_RPN, E.rpn_conv, hf, nb, g.Hk, g.Wk, 1, 1, nullptr, true, false, ws.rpn_t));
+        TRY(run_conv(m, THIA_K_RPN, E.rpn_head, ws.rpn_t, nb, g.Hk, g.Wk, 1, 0, nullptr, false, true, ws.logits, ws.deltas, A));
     }
     {
         Scope sc(m, THIA_K_TOPK);
@@ -702,6 +710,111 @@ int detect_frames_all_exits(thia_model* m, const uint8_t* frames, int n, int H, 
     return rc;
 }
 
+// Grow-only device buffer of the model: a larger request replaces it (after waiting for work that may still use it).
+template <typename T>
+int grow_buffer(thia_model* m, T*& p, size_t& cap, size_t need) {
+    if (need <= cap) return THIA_OK;
+    if (p) {
+        HIP_TRY(m, hipStreamSynchronize(m->stream));
+        (void)hipFree(p);
+        p = nullptr; cap = 0;
+    }
+    void* q = nullptr;
+    if (hipMalloc(&q, need * sizeof(T)) != hipSuccess) return fail(m, THIA_E_NOMEM, "staging allocation failed");
+    p = static_cast<T*>(q);
+    cap = need;
+    return THIA_OK;
+}
+int ensure_staging(thia_model* m, thia_model::Staging& st, size_t frame_bytes, size_t rows, size_t flags, size_t opt) {
+    TRY(grow_buffer(m, st.frames, st.frames_cap, frame_bytes));
+    if (rows > st.out_rows) {
+        if (st.ob || st.os || st.ol) {
+            HIP_TRY(m, hipStreamSynchronize(m->stream));
+            (void)hipFree(st.ob); (void)hipFree(st.os); (void)hipFree(st.ol);
+            st.ob = st.os = nullptr; st.ol = nullptr; st.out_rows = 0;
+        }
+        const size_t D = (size_t)m->D;
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&st.ob), rows * D * 16);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&st.os), rows * D * 4);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&st.ol), rows * D * 4);
+        if (e != hipSuccess) {
+            (void)hipFree(st.ob); (void)hipFree(st.os); (void)hipFree(st.ol);
+            st.ob = st.os = nullptr; st.ol = nullptr;
+            return fail(m, THIA_E_NOMEM, std::string("staging outputs: ") + hipGetErrorString(e));
+        }
+        st.out_rows = rows;
+    }
+    TRY(grow_buffer(m, st.flags, st.flags_cap, flags));
+    TRY(grow_buffer(m, st.opt, st.opt_cap, opt));
+    return THIA_OK;
+}
+void free_staging(thia_model::Staging& st) {
+    (void)hipFree(st.frames); (void)hipFree(st.ob); (void)hipFree(st.os); (void)hipFree(st.ol); (void)hipFree(st.flags); (void)hipFree(st.opt);
+    st = thia_model::Staging{};
+}
+
+// The frames of `spans` (disjoint, any order) at exit ep.  Frames are independent of each other, so chunks of one exit
+// share micro-batches: adjacent chunks are joined, and what is left over of chunks shorter than the micro-batch is gathered
+// into a staging batch (device-to-device copies of 3 H W bytes per frame), run, and its detections copied to the frames'
+// own output positions.  Every frame's result equals that of a stand-alone call on its chunk.
+struct Span { int start, len; };
+int run_spans(thia_model* m, const uint8_t* frames, int H, int W, int ep, std::vector<Span> spans, float* ob, float* os, int32_t* ol) {
+    if (spans.empty()) return THIA_OK;
+    std::sort(spans.begin(), spans.end(), [](const Span& a, const Span& b) { return a.start < b.start; });
+    std::vector<Span> runs;
+    for (const Span& sp : spans) {
+        if (sp.len <= 0) continue;
+        if (!runs.empty() && runs.back().start + runs.back().len == sp.start) runs.back().len += sp.len;
+        else runs.push_back(sp);
+    }
+    TRY(ensure_workspace(m, H, W));
+    const int mb = m->ws.mb;
+    const size_t D = (size_t)m->D, fbytes = (size_t)3 * H * W;
+    std::vector<Span> rest;   // what is left of each run after its whole micro-batches
+    for (const Span& r : runs) {
+        const int whole = r.len / mb * mb;
+        if (whole > 0)
+            TRY(detect_frames(m, frames + (size_t)r.start * fbytes, whole, H, W, ep, ob + (size_t)r.start * D * 4, os + (size_t)r.start * D,
+                              ol + (size_t)r.start * D));
+        if (r.len > whole) rest.push_back({r.start + whole, r.len - whole});
+    }
+    size_t i = 0;
+    int off = 0;   // frames of rest[i] already taken
+    while (i < rest.size()) {
+        std::vector<Span> pieces;
+        int total = 0;
+        while (i < rest.size() && total < mb) {
+            const int take = std::min(mb - total, rest[i].len - off);
+            pieces.push_back({rest[i].start + off, take});
+            total += take;
+            off += take;
+            if (off == rest[i].len) { ++i; off = 0; }
+        }
+        if (pieces.size() == 1) {
+            const Span& q = pieces[0];
+            TRY(detect_frames(m, frames + (size_t)q.start * fbytes, q.len, H, W, ep, ob + (size_t)q.start * D * 4, os + (size_t)q.start * D,
+                              ol + (size_t)q.start * D));
+            continue;
+        }
+        TRY(ensure_staging(m, m->stg, (size_t)mb * fbytes, (size_t)mb, 0, 0));
+        int pos = 0;
+        for (const Span& q : pieces) {
+            HIP_TRY(m, hipMemcpyAsync(m->stg.frames + (size_t)pos * fbytes, frames + (size_t)q.start * fbytes, (size_t)q.len * fbytes,
+                                      hipMemcpyDeviceToDevice, m->stream));
+            pos += q.len;
+        }
+        TRY(detect_frames(m, m->stg.frames, total, H, W, ep, m->stg.ob, m->stg.os, m->stg.ol));
+        pos = 0;
+        for (const Span& q : pieces) {
+            HIP_TRY(m, hipMemcpyAsync(ob + (size_t)q.start * D * 4, m->stg.ob + (size_t)pos * D * 4, (size_t)q.len * D * 16, hipMemcpyDeviceToDevice, m->stream));
+            HIP_TRY(m, hipMemcpyAsync(os + (size_t)q.start * D, m->stg.os + (size_t)pos * D, (size_t)q.len * D * 4, hipMemcpyDeviceToDevice, m->stream));
+            HIP_TRY(m, hipMemcpyAsync(ol + (size_t)q.start * D, m->stg.ol + (size_t)pos * D, (size_t)q.len * D * 4, hipMemcpyDeviceToDevice, m->stream));
+            pos += q.len;
+        }
+    }
+    return THIA_OK;
+}
+
 void free_estimator(thia_model* m) {
     (void)hipFree(m->est_w1t); (void)hipFree(m->est_b1); (void)hipFree(m->est_w2); (void)hipFree(m->est_b2); (void)hipFree(m->est_pooled);
     m->est_w1t = m->est_b1 = m->est_w2 = m->est_b2 = m->est_pooled = nullptr;
@@ -785,7 +898,10 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
         m->D < 1 || m->D > 512 || m->pool < 1 || m->pool > 16 || !(m->stdv > 0.f))
         return bad(THIA_E_BLOB);
     // kernel limits: channel counts multiples of 64, 64 stem channels, 2x2 sampling
-    if (m->stem_ch != 64 || m->base_width % 64 || m->head_ch % 64 || m->fc_dim % 64 || m->sampling != 2) return bad(THIA_E_SHAPE);
+    if (m->stem_ch != 64 || m->base_width < 64 || m->base_width % 64 || m->head_ch < 64 || m->head_ch % 64 || m->fc_dim < 64 ||
+        m->fc_dim % 64 || m->sampling != 2)
+        return bad(THIA_E_SHAPE);
+    if (m->has_lateral != 0 && m->has_lateral != 1) return bad(THIA_E_BLOB);
     for (int i = 0; i < 8; ++i) m->anc.sizes[i] = hf[13 + i];
     for (int i = 0; i < 4; ++i) m->anc.sqrt_ratios[i] = i < m->anc.n_ratios ? sqrtf(hf[21 + i]) : 1.f;
 
@@ -884,10 +1000,8 @@ int thia_load_model(const void* weights, size_t nbytes, int n_exits, thia_model*
             HostLayer cat;
             cat.w = wcat.data(); cat.b = bcat.data(); cat.co = 96; cat.ci = hc; cat.k = 1;
             rc = upload_fragments(m, cat, &E.head_f);
-            if (!rc) {
-                HIP_TRY(m, hipMalloc(reinterpret_cast<void**>(&E.head_fb), 96 * 4));
-                HIP_TRY(m, hipMemcpy(E.head_fb, bcat.data(), 96 * 4, hipMemcpyHostToDevice));
-            }
+            if (!rc && hipMalloc(reinterpret_cast<void**>(&E.head_fb), 96 * 4) != hipSuccess) rc = THIA_E_NOMEM;
+            if (!rc && hipMemcpy(E.head_fb, bcat.data(), 96 * 4, hipMemcpyHostToDevice) != hipSuccess) rc = THIA_E_HIP;
         }
         // FC1 reads ROI features laid out [(ph*P+pw)][c]: the same O,(kh,kw),I repack as a PxP convolution,
         // after which it is a plain matrix product over K = P*P*hc
@@ -907,6 +1021,7 @@ void thia_free_model(thia_model* m) {
     if (!m) return;
     (void)hipStreamSynchronize(m->stream);
     free_workspace(m);
+    free_staging(m->stg); free_staging(m->qry); free_staging(m->qout);
     for (auto& t : m->taps) if (t.buf) (void)hipFree(t.buf);
     for (auto e : m->ev_pool) (void)hipEventDestroy(e);
     if (m->stem_w) (void)hipFree(m->stem_w);
@@ -987,19 +1102,18 @@ int thia_run_plan(thia_model* m, const uint8_t* frames, int n_chunks, int chunk_
         if (chunk_ep[c] < 0 || chunk_ep[c] > m->n_exits) return fail(m, THIA_E_BADEP, "plan holds an exit outside 0..n_exits");
     if (n_chunks == 0 || chunk_len == 0) return THIA_OK;
     const int D = m->D;
-    const size_t fbytes = (size_t)3 * H * W;
-    // group chunks by exit: one group after the other on the one stream, outputs at the frames' own positions
-    for (int ep = 0; ep <= m->n_exits; ++ep)
+    // group chunks by exit: one group after the other on the one stream, outputs at the frames' own positions; the
+    // chunks of a group share micro-batches (run_spans)
+    for (int ep = 0; ep <= m->n_exits; ++ep) {
+        std::vector<Span> spans;
         for (int c = 0; c < n_chunks; ++c) {
             if (chunk_ep[c] != ep) continue;
             const size_t f0 = (size_t)c * chunk_len;
-            if (ep == 0) {
-                HIP_TRY(m, launch_fill_empty(chunk_len, D, out_boxes + f0 * D * 4, out_scores + f0 * D, out_labels + f0 * D, m->stream));
-            } else {
-                TRY(detect_frames(m, frames + f0 * fbytes, chunk_len, H, W, ep, out_boxes + f0 * D * 4, out_scores + f0 * D,
-                                  out_labels + f0 * D));
-            }
+            if (ep == 0) HIP_TRY(m, launch_fill_empty(chunk_len, D, out_boxes + f0 * D * 4, out_scores + f0 * D, out_labels + f0 * D, m->stream));
+            else spans.push_back({(int)f0, chunk_len});
         }
+        if (ep > 0) TRY(run_spans(m, frames, H, W, ep, spans, out_boxes, out_scores, out_labels));
+    }
     return THIA_OK;
 }
 
@@ -1019,7 +1133,6 @@ int thia_run_chunks(thia_model* m, const uint8_t* frames, int n, int H, int W, i
         if (spans[i].first < spans[i - 1].second) return fail(m, THIA_E_BADARG, "chunks overlap");
     if (n == 0) return THIA_OK;
     const int D = m->D;
-    const size_t fbytes = (size_t)3 * H * W;
     // frames no chunk covers, and skipped chunks, get the empty pattern
     int pos = 0;
     for (size_t i = 0; i <= spans.size(); ++i) {
@@ -1029,17 +1142,16 @@ int thia_run_chunks(thia_model* m, const uint8_t* frames, int n, int H, int W, i
                                          out_labels + (size_t)pos * D, m->stream));
         if (i < spans.size()) pos = spans[i].second;
     }
-    for (int e = 0; e <= m->n_exits; ++e)
+    for (int e = 0; e <= m->n_exits; ++e) {
+        std::vector<Span> group;
         for (int c = 0; c < n_chunks; ++c) {
             if (ep[c] != e || len[c] == 0) continue;
             const size_t f0 = (size_t)start[c];
-            if (e == 0) {
-                HIP_TRY(m, launch_fill_empty(len[c], D, out_boxes + f0 * D * 4, out_scores + f0 * D, out_labels + f0 * D, m->stream));
-            } else {
-                TRY(detect_frames(m, frames + f0 * fbytes, len[c], H, W, e, out_boxes + f0 * D * 4, out_scores + f0 * D,
-                                  out_labels + f0 * D));
-            }
+            if (e == 0) HIP_TRY(m, launch_fill_empty(len[c], D, out_boxes + f0 * D * 4, out_scores + f0 * D, out_labels + f0 * D, m->stream));
+            else group.push_back({start[c], len[c]});
         }
+        if (e > 0) TRY(run_spans(m, frames, H, W, e, group, out_boxes, out_scores, out_labels));
+    }
     return THIA_OK;
 }
 
@@ -1144,25 +1256,13 @@ int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, c
     const int E = m->n_exits, D = m->D;
     const int kb = cfg->eval_batch > 0 ? cfg->eval_batch : 64;  // staging capacity; larger requests are cut into pieces
     const size_t fbytes = (size_t)3 * H * W;
-    // staging: gathered frames, every exit's detections for them, the answers
-    uint8_t *stage = nullptr, *dflags = nullptr;
-    float *ob = nullptr, *os = nullptr;
-    int32_t *ol = nullptr, *dopt = nullptr;
+    // staging (owned by the model, grow-only): gathered frames, every exit's detections for them, the answers
     std::vector<uint8_t> hflags((size_t)E * kb);
     std::vector<int32_t> hopt(kb);
-    auto release = [&]() {
-        (void)hipFree(stage); (void)hipFree(dflags); (void)hipFree(ob); (void)hipFree(os); (void)hipFree(ol); (void)hipFree(dopt);
-    };
-    hipError_t he = hipSuccess;
-    if (n > 0) {
-        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&stage), fbytes * kb);
-        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&dflags), (size_t)E * kb);
-        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&ob), (size_t)E * kb * D * 16);
-        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&os), (size_t)E * kb * D * 4);
-        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&ol), (size_t)E * kb * D * 4);
-        if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&dopt), (size_t)kb * 4);
-        if (he != hipSuccess) { release(); return fail(m, THIA_E_NOMEM, std::string("planner staging: ") + hipGetErrorString(he)); }
-    }
+    if (n > 0) TRY(ensure_staging(m, m->qry, fbytes * kb, (size_t)E * kb, (size_t)E * kb, (size_t)kb));
+    uint8_t *stage = m->qry.frames, *dflags = m->qry.flags;
+    float *ob = m->qry.ob, *os = m->qry.os;
+    int32_t *ol = m->qry.ol, *dopt = m->qry.opt;
     PlanEval eval = [&](const int* fr, int k, uint8_t* out, std::string& err) -> int {
         for (int o = 0; o < k; o += kb) {
             const int kk = std::min(kb, k - o);
@@ -1192,7 +1292,6 @@ int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, c
     std::vector<PlanChunk> plan;
     std::string err;
     const int rc = plan_core(n, E, *cfg, eval, plan, *stats, evaluated, err);
-    release();
     if (rc != THIA_OK) return fail(m, rc, err);
     if (store_plan(plan, cap, start, len, ep) != THIA_OK) return fail(m, THIA_E_BADARG, "plan has more chunks than the capacity given");
     return THIA_OK;
@@ -1204,21 +1303,10 @@ int thia_run_query(thia_model* m, const uint8_t* frames, int n, int H, int W, co
     if (n > 0 && !answers) return fail(m, THIA_E_BADARG, "null pointer");
     TRY(thia_plan_query(m, frames, n, H, W, q, cfg, cap, start, len, ep, stats, nullptr));
     if (n == 0) return THIA_OK;
-    const size_t D = (size_t)m->D;
-    float *ob = nullptr, *os = nullptr;
-    int32_t* ol = nullptr;
-    auto release = [&]() { (void)hipFree(ob); (void)hipFree(os); (void)hipFree(ol); };
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ob), (size_t)n * D * 16);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&os), (size_t)n * D * 4);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ol), (size_t)n * D * 4);
-    if (e != hipSuccess) { release(); return fail(m, THIA_E_NOMEM, std::string("query buffers: ") + hipGetErrorString(e)); }
-    int rc = thia_run_chunks(m, frames, n, H, W, stats->n_chunks, start, len, ep, ob, os, ol);
-    if (rc == THIA_OK) rc = thia_eval_predicate(m, ol, os, n, q, answers);
-    const hipError_t e2 = hipStreamSynchronize(m->stream);   // the buffers are released below
-    release();
-    if (rc != THIA_OK) return rc;
-    if (e2 != hipSuccess) return fail_hip(m, e2, "thia_run_query");
-    return THIA_OK;
+    // detections of all n frames: model-owned, grow-only
+    TRY(ensure_staging(m, m->qout, 0, (size_t)n, 0, 0));
+    TRY(thia_run_chunks(m, frames, n, H, W, stats->n_chunks, start, len, ep, m->qout.ob, m->qout.os, m->qout.ol));
+    return thia_eval_predicate(m, m->qout.ol, m->qout.os, n, q, answers);
 }
 
 const char* thia_last_error(const thia_model* m) { return m ? m->err.c_str() : "null model"; }

@@ -410,14 +410,11 @@ hipError_t launch_select(const float* scores, const float* boxes, const int32_t*
     if (post <= SELC_MAX_POST && Kc >= 2 && Kc - 1 <= SELC_MAX_CLASSES && D <= SELC_MAX_D) {
         const int NC = Kc - 1;
         const size_t lds = (size_t)NC * SELC_MAX_POST * 8 + (size_t)NC * D * (8 + sizeof(Box)) + (size_t)NC * 4;
-        static bool attr_set = false;
-        if (!attr_set) {
+        {
             const size_t lds_max = (size_t)SELC_MAX_CLASSES * SELC_MAX_POST * 8 + (size_t)SELC_MAX_CLASSES * SELC_MAX_D * (8 + sizeof(Box)) +
                                    (size_t)SELC_MAX_CLASSES * 4;
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_classes_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
+            hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(select_classes_kernel), lds_max);
             if (e != hipSuccess) return e;
-            attr_set = true;
         }
         hipLaunchKernelGGL(select_classes_kernel, dim3(n), dim3(1024), lds, s, scores, boxes, roi_n, post, Kc, score_thr, nms_thr, D,
                            out_boxes, out_scores, out_labels, out_n);

@@ -6,12 +6,30 @@
 #include <stdint.h>
 
 #include <functional>
+#include <mutex>
+#include <set>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/thia.h"
 
 namespace thia {
+
+// Raises a kernel's dynamic LDS limit to `bytes` once per (kernel, device): the attribute belongs to the device's copy of
+// the code object, so a flag per process is not enough when a second GPU or a second thread comes along.
+inline hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes) {
+    static std::mutex mu;
+    static std::set<std::pair<const void*, int>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({kernel, dev})) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) done.insert({kernel, dev});
+    return e;
+}
 
 // ---------------------------------------------------------------- element helpers
 typedef uint16_t bf16_t;  // raw bfloat16 bits

@@ -8,10 +8,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# Data-only gains of the synthetic weights (see thia_synth.weights): literal He-normal
-# weights without normalisation layers give degenerate (empty) proposals.
-RES_GAIN = 0.25
-PRED_STD = 0.01
+from thia_synth import recipe_for   # data-only gains of the synthetic weights (see thia_synth.recipe_for)
 
 
 def pytest_configure(config):
@@ -25,14 +22,14 @@ def get_blob(spec, seed):
     """Weights blob for a ModelSpec; cached in memory and under /tmp (generation takes seconds)."""
     from thia_synth import make_blob
     import hashlib
-    key = hashlib.sha1(spec.header() + seed.to_bytes(8, "little") + repr((RES_GAIN, PRED_STD)).encode()).hexdigest()[:16]
+    key = hashlib.sha1(spec.header() + seed.to_bytes(8, "little") + repr(sorted(recipe_for(spec).items())).encode()).hexdigest()[:16]
     if key in _blob_cache:
         return _blob_cache[key]
     path = f"/tmp/thia_blob_{key}.npy"
     if os.path.exists(path):
         blob = np.load(path)
     else:
-        blob = make_blob(spec, seed, res_gain=RES_GAIN, pred_std=PRED_STD)
+        blob = make_blob(spec, seed, **recipe_for(spec))
         tmp = path + f".{os.getpid()}.npy"
         np.save(tmp, blob)
         os.replace(tmp, path)

@@ -13,7 +13,19 @@ from thia_synth import CONFIGS, make_frames
 pytestmark = pytest.mark.gpu
 
 TOL_BF16 = 2e-2          # bf16 path vs the fp32 oracle (stated bar), RPN logits and deltas
-TOL_BF16_SAME = 2e-2     # vs the oracle with the same bf16 storage rounding (bf16 rounding flips accumulate with depth; measured values are printed)
+# vs the oracle with the same bf16 storage rounding: two bf16 pipelines with different summation orders decorrelate with
+# depth, so this is not tighter by construction.  Measured: 3.2e-3 .. 1.14e-2 on the 16-block detector (largest at the
+# last exit), 3.7e-3 .. 1.55e-2 on the 33-block one; the bounds sit ~20 % above the largest value, so that one more
+# rounding in a fused kernel shows up here before it reaches the stated bar.
+TOL_BF16_SAME = {16: 1.4e-2, 33: 1.8e-2}
+# End-to-end agreement of the final detections (same label, IoU >= 0.99, one to one) with the oracle.  The stated bar is
+# 0.99.  fp32 path: the bar itself (measured 1.0000).  bf16 path: no data-only recipe makes the CONTROL - fp32 oracle
+# against bf16-storage oracle, two correct implementations - reach it, because a randomly initialised detector ranks
+# ~10^5 near-equal objectness logits and bf16 rounding reorders neighbours (table of recipes in the design doc).  With the
+# committed recipe the control is 0.78 .. 0.975 per configuration and exit and the GPU path measures 0.855 .. 0.99
+# against the bf16-storage oracle.  Gate: the lowest control minus a margin of 0.03.
+MIN_MATCH_BF16 = 0.75
+MIN_MATCH_FP32 = 0.99
 
 
 def _frames(cfg, n=None):
@@ -35,36 +47,34 @@ def _properties(cfg, boxes, scores, labels, H, W):
     return int(valid.sum())
 
 
-def _compare_with_oracle(cfg, m, blob, frames_h, ep, n_ref, gb, gs, gl, min_frac):
+def _compare_with_oracle(cfg, m, blob, frames_h, ep, ref_frames, gb, gs, gl, min_frac=MIN_MATCH_BF16):
+    """GPU results of the whole batch against the oracle on the frames `ref_frames` (indices into the batch)."""
     names = ["rpn_logits", "rpn_deltas"]
-    r16 = oracle.Model(blob, precision=1).detect(frames_h[:n_ref], ep, taps=names)
-    r32 = oracle.Model(blob, precision=0).detect(frames_h[:n_ref], ep, taps=names)
+    sel = np.ascontiguousarray(frames_h[ref_frames])
+    r16 = oracle.Model(blob, precision=1).detect(sel, ep, taps=names)
+    r32 = oracle.Model(blob, precision=0).detect(sel, ep, taps=names)
     n_all = frames_h.shape[0]
-    lg = m.tap("rpn_logits").reshape(n_all, -1)[:n_ref]
-    dl = m.tap("rpn_deltas").reshape(n_all, -1, 4)[:n_ref]
+    lg = m.tap("rpn_logits").reshape(n_all, -1)[ref_frames]
+    dl = m.tap("rpn_deltas").reshape(n_all, -1, 4)[ref_frames]
     e32 = max(relerr(lg, r32["rpn_logits"]), relerr(dl, r32["rpn_deltas"]))
     e16 = max(relerr(lg, r16["rpn_logits"]), relerr(dl, r16["rpn_deltas"]))
     assert e32 <= TOL_BF16, e32
-    assert e16 <= TOL_BF16_SAME, e16
+    assert e16 <= TOL_BF16_SAME[sum(cfg.model.blocks)], e16
     tot, hit, ctl = 0, 0.0, 0.0
-    for f in range(n_ref):
-        frac, cnt = match_fraction(gb[f].cpu().numpy(), gl[f].cpu().numpy(), r16["boxes"][f], r16["labels"][f])
+    for i, f in enumerate(ref_frames):
+        frac, cnt = match_fraction(gb[f].cpu().numpy(), gl[f].cpu().numpy(), r16["boxes"][i], r16["labels"][i])
         tot += cnt
         hit += frac * cnt
-        # control: the two CPU oracles (fp32 vs bf16 storage) against each other.  With random-init
-        # weights the scores are nearly flat, so rank order - and with it greedy NMS - is decided by
-        # perturbations far below bf16 resolution; the control shows how much two correct
-        # implementations of different precision disagree on the same frame.
-        cf, _ = match_fraction(r32["boxes"][f], r32["labels"][f], r16["boxes"][f], r16["labels"][f])
+        # control: the two CPU oracles (fp32 vs bf16 storage) against each other
+        cf, _ = match_fraction(r32["boxes"][i], r32["labels"][i], r16["boxes"][i], r16["labels"][i])
         ctl += cf * cnt
     frac, ctl = hit / max(tot, 1), ctl / max(tot, 1)
-    print(f"{cfg.name} EP{ep}: max rel err vs fp32 oracle {e32:.2e}, vs bf16 oracle {e16:.2e}; "
+    print(f"{cfg.name} EP{ep} frames {list(ref_frames)}: max rel err vs fp32 oracle {e32:.2e}, vs bf16 oracle {e16:.2e}; "
           f"{frac:.4f} of {tot} detections matched at IoU>=0.99 (control fp32-oracle vs bf16-oracle: {ctl:.4f})")
     assert tot > 0
-    # End-to-end box agreement is REPORTED, not gated, for the bf16 configurations: even the two CPU
-    # oracles disagree (control), so no implementation can meet a fixed bar on these inputs.  What is
-    # gated instead: the tolerances above and the exact stage-by-stage chain below.
-    for f in range(n_ref):
+    assert frac >= min_frac, (frac, ctl)
+    # second line of defence: every stage recomputed by the oracle's step functions from the GPU's own upstream tensors
+    for f in ref_frames:
         info = chain_check(m, blob, cfg.model, frames_h.shape[2], frames_h.shape[3], ep, n_all, f, gb, gs, gl, step_tol=2.0 ** -7)
         print(f"   chain frame {f}: {info}")
     return e32, e16, frac
@@ -79,7 +89,7 @@ def test_config2_r50_ep2_batch16():
     gb, gs, gl = m.detect_chunk(to_dev(fh), 2)
     torch.cuda.synchronize()
     assert _properties(cfg, gb, gs, gl, 540, 960) > 0
-    _compare_with_oracle(cfg, m, blob, fh, 2, 2, gb, gs, gl, min_frac=0.9)
+    _compare_with_oracle(cfg, m, blob, fh, 2, [0, 1, 2, 15], gb, gs, gl)
     m.set_debug(False)
 
 
@@ -93,7 +103,7 @@ def test_config3_r50_sweep_batch32(ep):
     gb, gs, gl = m.detect_chunk(to_dev(fh), ep)
     torch.cuda.synchronize()
     assert _properties(cfg, gb, gs, gl, 540, 960) > 0
-    _compare_with_oracle(cfg, m, blob, fh, ep, 1, gb, gs, gl, min_frac=0.9)
+    _compare_with_oracle(cfg, m, blob, fh, ep, [0, 31], gb, gs, gl)   # first frame and the batch's last (last M tile)
     m.set_debug(False)
     # determinism at full size: the same call again is bit-identical
     gb2, gs2, gl2 = m.detect_chunk(to_dev(fh), ep)
@@ -123,6 +133,24 @@ def test_config4_plan_256_frames_bit_identical_to_chunks():
     torch.cuda.synchronize()
     assert (ql[32:64] == -1).all() and (qs[32:64] == 0).all() and (qb[32:64] == 0).all()
     assert torch.equal(qb[:32], pb[:32]) and torch.equal(qb[64:], pb[64:])
+
+
+def test_plan_of_short_chunks_at_full_frame_size_is_bit_identical_to_chunks():
+    """Config 4's detector and frame size with chunks of 7 frames and mixed exits: same-exit chunks share 32-frame
+    micro-batches (so the kernels run at other batch sizes, tile shapes and fused variants than a stand-alone 7-frame
+    call does), and every chunk's slice is still bit-identical to the stand-alone call."""
+    cfg = CONFIGS[4]
+    m, _ = gpu_model(cfg.model, cfg.weight_seed)
+    plan = [3, 1, 3, 4, 3, 2, 4, 3, 0, 3, 4, 2]
+    L = 7
+    fd = to_dev(_frames(cfg, L * len(plan)))
+    pb, ps, pl = m.run_plan(fd, L, plan)
+    torch.cuda.synchronize()
+    for c, ep in enumerate(plan):
+        b, s, l = m.detect_chunk(fd[L * c:L * (c + 1)].contiguous(), ep)
+        torch.cuda.synchronize()
+        sl = slice(L * c, L * (c + 1))
+        assert torch.equal(pb[sl], b) and torch.equal(ps[sl], s) and torch.equal(pl[sl], l), f"chunk {c} (EP{ep})"
 
 
 def test_config3_all_exits_in_one_pass_bit_identical_to_the_sweep():
@@ -182,12 +210,11 @@ def test_config5_r101_1080p_batch8(ep):
     m, blob = gpu_model(cfg.model, cfg.weight_seed)
     fh = _frames(cfg)
     assert fh.shape == (8, 3, 1080, 1920)
-    m.set_debug(ep in (2, 4))
+    m.set_debug(True)
     gb, gs, gl = m.detect_chunk(to_dev(fh), ep)
     torch.cuda.synchronize()
     assert _properties(cfg, gb, gs, gl, 1080, 1920) > 0
-    if ep in (2, 4):         # oracle sample: frame 0 at exits 2 and 4 (113 and 340 GMAC per frame on the CPU)
-        _compare_with_oracle(cfg, m, blob, fh, ep, 1, gb, gs, gl, min_frac=0.9)
+    _compare_with_oracle(cfg, m, blob, fh, ep, [0], gb, gs, gl)     # oracle sample: frame 0 (134 / 113 / 311 / 340 GMAC on the CPU)
     m.set_debug(False)
 
 
@@ -217,7 +244,5 @@ def test_r50_full_depth_fp32_path_matches_detections(ep):
     assert e <= 1e-4, e
     info = chain_check(m, blob, spec, 540, 960, ep, 2, 0, gb, gs, gl, step_tol=1e-4)
     print(f"   chain: {info}")
-    # With errors of 2e-6 the two sides still order a few near-tied scores differently (the scores of a
-    # random-init detector are nearly flat); measured 0.92-0.99.  Gate at 0.85, report the value.
-    assert hit / tot >= 0.85, hit / tot
+    assert hit / tot >= MIN_MATCH_FP32, hit / tot
     m.set_debug(False)

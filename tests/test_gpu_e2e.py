@@ -29,6 +29,7 @@ def _check_detections(gb, gs, gl, ref, min_frac=0.99):
         tot += cnt
         hit += frac * cnt
     assert tot > 0
+    print(f"{hit / tot:.4f} of {tot} detections matched at IoU >= 0.99 (gate {min_frac})")
     assert hit / tot >= min_frac, f"only {hit / tot:.4f} of {tot} detections match at IoU >= 0.99"
     return hit / tot, tot
 
@@ -94,7 +95,8 @@ def test_mini_bf16_all_exits(ep):
     assert relerr(lg, r32["rpn_logits"]) <= TOL_BF16 and relerr(dl, r32["rpn_deltas"]) <= TOL_BF16
     assert relerr(lg, r16["rpn_logits"]) <= 5e-3 and relerr(dl, r16["rpn_deltas"]) <= 5e-3
     m.set_debug(False)
-    _check_detections(gb.cpu().numpy(), gs.cpu().numpy(), gl.cpu().numpy(), r16, min_frac=0.95)
+    _check_detections(gb.cpu().numpy(), gs.cpu().numpy(), gl.cpu().numpy(), r16, min_frac=0.95)   # measured 0.977 .. 0.997: a handful of near-tied ranks per exit flip under bf16 rounding (the
+    # fp32 path of the same detector, one test up, matches 1.0000)
 
 
 @pytest.mark.parametrize("precision,ep", [(0, 1), (0, 3), (0, 4), (1, 2), (1, 4)])
@@ -270,6 +272,32 @@ def test_plan_is_bit_identical_to_per_chunk_calls_and_skip_is_empty():
         assert torch.equal(pb[c * L:(c + 1) * L], b) and torch.equal(ps[c * L:(c + 1) * L], s) and torch.equal(pl[c * L:(c + 1) * L], l)
     assert (pl[2 * L:3 * L] == -1).all() and (ps[2 * L:3 * L] == 0).all() and (pb[2 * L:3 * L] == 0).all()
     assert (pl[:L, 0] >= 1).all()
+
+
+@pytest.mark.parametrize("L", [1, 4, 7])
+def test_short_chunks_share_micro_batches_and_stay_bit_identical(L):
+    """Chunks shorter than the micro-batch: the chunks of one exit are run together (joined where adjacent, gathered
+    otherwise), and every chunk's slice still equals a stand-alone call on it, with mixed exits and skips, through both
+    thia_run_plan and thia_run_chunks."""
+    m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
+    plan = [2, 2, 1, 0, 2, 4, 1, 1, 3, 2, 0, 4, 4, 2]
+    n = L * len(plan)
+    frames = to_dev(make_frames(SceneSpec(160, 224, n, 4, 10, 10, 90), 43 + L))
+    m.set_microbatch(5)                       # micro-batches then mix whole chunks, chunk remainders and joined neighbours
+    pb, ps, pl = m.run_plan(frames, L, plan)
+    chunks = [(c * L, L, ep) for c, ep in enumerate(plan)]
+    cb, cs, cl = m.run_chunks(frames, chunks[::-1])          # any order of the list
+    torch.cuda.synchronize()
+    m.set_microbatch(0)
+    assert torch.equal(pb, cb) and torch.equal(ps, cs) and torch.equal(pl, cl)
+    for a, ln, ep in chunks:
+        b, s, l = m.detect_chunk(frames[a:a + ln].contiguous(), ep)
+        torch.cuda.synchronize()
+        assert torch.equal(pb[a:a + ln], b) and torch.equal(ps[a:a + ln], s) and torch.equal(pl[a:a + ln], l), (a, ep)
+        if ep == 0:
+            assert (pl[a:a + ln] == -1).all()
+        else:
+            assert (pl[a:a + ln, 0] >= 1).all()
 
 
 def test_all_exits_in_one_pass_matches_each_exit_and_the_oracle():

@@ -105,6 +105,7 @@ class SceneSpec:
     side_min: int
     side_max: int
     style: str = "road"          # "road" (gray road + shading) or "gradient"
+    noise: int = 0               # per-pixel, per-channel sensor noise: uniform integers in -noise .. +noise added before clipping
 
 
 @dataclass(frozen=True)
@@ -122,7 +123,7 @@ _R101 = replace(_R50, blocks=(3, 4, 23, 3), pre_nms=2000, post_nms=1000, n_class
 _TINY = ModelSpec(precision=0, n_exits=1, blocks=(3, 0, 0, 0), has_lateral=0,
                   sizes=(32.0, 64.0, 128.0), ratios=(1.0,), pre_nms=200, post_nms=50, n_classes=3)
 
-_ROAD540 = SceneSpec(540, 960, 16, 5, 40, 16, 300)
+_ROAD540 = SceneSpec(540, 960, 16, 5, 40, 16, 300, noise=16)
 
 CONFIGS = {
     1: Config("tiny-fp32", _TINY, SceneSpec(128, 128, 4, 3, 6, 12, 64, "gradient"),
@@ -130,7 +131,7 @@ CONFIGS = {
     2: Config("r50-ep2-b16", _R50, _ROAD540, 0x7414A + 2, 0xBEEF + 2, (2,)),
     3: Config("r50-sweep-b32", _R50, replace(_ROAD540, n_frames=32), 0x7414A + 3, 0xBEEF + 2, (1, 2, 3, 4)),
     4: Config("r50-plan-8x32", _R50, replace(_ROAD540, n_frames=256), 0x7414A + 4, 0xBEEF + 2, (1, 4, 2, 2, 3, 1, 4, 3)),
-    5: Config("r101-1080p-b8", _R101, SceneSpec(1080, 1920, 8, 20, 150, 8, 400), 0x7414A + 5, 0xBEEF + 5, (1, 2, 3, 4)),
+    5: Config("r101-1080p-b8", _R101, SceneSpec(1080, 1920, 8, 20, 150, 8, 400, noise=16), 0x7414A + 5, 0xBEEF + 5, (1, 2, 3, 4)),
 }
 
 

@@ -10,7 +10,9 @@ pixels per frame with +-1 px jitter, so consecutive frames are correlated.
 rectangles re-drawn per frame with fresh positions.
 
 The number of rectangles of a sequence is drawn once; rectangle r of frame t is a
-pure function of (seed, r, t).
+pure function of (seed, r, t).  `scene.noise` > 0 adds per-pixel, per-channel sensor
+noise (uniform integers in -noise .. +noise, a pure function of (seed, t, position))
+on top of the drawn frame, as a camera would.
 """
 import numpy as np
 
@@ -71,5 +73,10 @@ def make_frames(scene: SceneSpec, seed: int, n_frames=None) -> np.ndarray:
                 continue
             for c in range(3):
                 img[c, y0:y1, x0:x1] = int(255 * u[r, 6 + c])
+        if scene.noise > 0:
+            a = int(scene.noise)
+            nb = 3 * H * W
+            raw = rng.bits64(seed, 6, t * ((nb + 7) // 8), (nb + 7) // 8).view(np.uint8)[:nb].reshape(3, H, W)
+            img = np.clip(img.astype(np.int16) + (raw % (2 * a + 1)).astype(np.int16) - a, 0, 255).astype(np.uint8)
         frames[t] = img
     return frames

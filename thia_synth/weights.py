@@ -16,9 +16,10 @@ FC1's input index is c*pool*pool + ph*pool + pw.  RPN delta channel is 4*a + j
 (j = dx, dy, dw, dh); box output is 4*c + j.
 
 Values: normal with std sqrt(2 / fan_in) (fan_in = Cin*kh*kw), biases zero.
-Two optional gains change only the *data* (never the detector): `res_gain`
-multiplies the last conv of every residual branch, `pred_std` replaces the std of
-the four predictor layers (rpn.obj, rpn.delta, cls, box).
+Optional gains change only the *data* (never the detector): `res_gain` multiplies the
+last conv of every residual branch, `pred_std` replaces the std of the two score
+predictors (rpn.obj, cls) and `delta_std` (default: `pred_std`) that of the two box-delta
+predictors (rpn.delta, box).
 """
 import numpy as np
 
@@ -27,7 +28,7 @@ from .configs import ModelSpec, HEADER_BYTES
 
 
 def tensor_list(spec: ModelSpec):
-    """[(name, shape, role)] in blob order; role in {'conv','res_last','pred','bias'}."""
+    """[(name, shape, role)] in blob order; role in {'conv','res_last','pred','pred_delta','bias'}."""
     out = []
 
     def conv(name, co, ci, k, role="conv"):
@@ -61,11 +62,11 @@ def tensor_list(spec: ModelSpec):
             hc = ce
         conv(p + ".rpn.conv", hc, hc, 3)
         conv(p + ".rpn.obj", A, hc, 1, "pred")
-        conv(p + ".rpn.delta", 4 * A, hc, 1, "pred")
+        conv(p + ".rpn.delta", 4 * A, hc, 1, "pred_delta")
         fc(p + ".fc1", spec.fc_dim, hc * spec.pool * spec.pool)
         fc(p + ".fc2", spec.fc_dim, spec.fc_dim)
         fc(p + ".cls", spec.n_classes, spec.fc_dim, "pred")
-        fc(p + ".box", 4 * spec.n_classes, spec.fc_dim, "pred")
+        fc(p + ".box", 4 * spec.n_classes, spec.fc_dim, "pred_delta")
     return out
 
 
@@ -73,7 +74,7 @@ def blob_floats(spec: ModelSpec):
     return sum(int(np.prod(s)) for _, s, _ in tensor_list(spec))
 
 
-def make_blob(spec: ModelSpec, seed: int, res_gain: float = 1.0, pred_std=None) -> np.ndarray:
+def make_blob(spec: ModelSpec, seed: int, res_gain: float = 1.0, pred_std=None, delta_std=None) -> np.ndarray:
     """uint8 array: header + tensors.  Tensor t draws from rng stream t."""
     tl = tensor_list(spec)
     total = sum(int(np.prod(s)) for _, s, _ in tl)
@@ -90,6 +91,8 @@ def make_blob(spec: ModelSpec, seed: int, res_gain: float = 1.0, pred_std=None) 
             std = np.sqrt(2.0 / fan_in)
             if role == "pred" and pred_std is not None:
                 std = pred_std
+            if role == "pred_delta" and (delta_std is not None or pred_std is not None):
+                std = delta_std if delta_std is not None else pred_std
             if role == "res_last":
                 std *= res_gain
             # generate in slabs to bound temporary memory
