@@ -3,6 +3,7 @@ CPU oracle's tests and the GPU library's tests.  No detector arithmetic lives he
 from .configs import CONFIGS, ModelSpec, SceneSpec, Config, small_variant, HEADER_BYTES
 from .frames import make_frames
 from .weights import make_blob, tensor_list, split_blob, blob_floats
+from .classifier import ClassifierSpec, VGG16_EXITS, make_classifier_blob, split_classifier_blob, classifier_tensor_list
 
 
 def recipe_for(spec):
