@@ -406,6 +406,40 @@ int thia_op_bottleneck_tail(thia_model* m, const void* in, int n, int H, int W, 
  * 3x3/2 max-pool; out T [n,Hp,Wp,stem_ch] NHWC. */
 int thia_op_stem(thia_model* m, const uint8_t* frames, int n, int H, int W, void* out);
 
+/* ---------------------------------------------------------------- image classifier with exits
+ * The paper's generalisation of early inference (Sec. 4.2, "Generalization" and its figure): the same technique on a
+ * VGG-16-style image classifier with eight exits.  The backbone is a stack of 3x3 convolutions (zero padding 1,
+ * stride 1, ReLU) with 2x2 / stride-2 max-pools after some of them; exit k taps the output of one convolution layer
+ * (after its ReLU, before a pool that may follow) and inference stops there: later layers are not run.  The paper does
+ * not define the exit's unit; this library's reading: global average pooling over the tapped map, one fully connected
+ * layer to the class logits, soft-max; the answer is the arg-max class (the lowest class on a tie) and its probability.
+ *
+ * weights: host blob, 256-byte little-endian header (word 0 magic 0x43494854, 1 version 1, 2 precision, 3 n_exits
+ * (1..8), 4 convolution layers (1..16), 5 input channels (3), 6 classes, 7 pixel mean (float), 8 pixel std (float),
+ * 9..24 output channels per layer, 25..40 "a pool follows" per layer, 41..48 tapped layer (1-based) per exit, strictly
+ * increasing) followed by fp32 tensors: per layer weight [Cout,Cin,3,3] and bias [Cout], then per exit the unit's weight
+ * [classes, C_tap] and bias [classes].  Channel counts must be multiples of 64 (32 for fp32 models) and at most 1024.
+ * Calls enqueue on the classifier's stream and return; errors and ownership as for the detector calls above.
+ */
+typedef struct thia_classifier thia_classifier;
+int thia_classifier_load(const void* weights, size_t nbytes, int n_exits, thia_classifier** out);
+void thia_classifier_free(thia_classifier* c);
+int thia_classifier_set_stream(thia_classifier* c, void* hip_stream);
+const char* thia_classifier_last_error(const thia_classifier* c);
+
+/* frames dev uint8 [n,3,H,W]; ep 1..n_exits, or 0 = skip (labels -1, confidence 0).  out_labels dev int32 [n] (class
+ * 0..classes-1), out_conf dev float32 [n] (soft-max probability of that class), out_logits dev float32 [n,classes] or
+ * NULL.  May (re)allocate its activation buffers when a larger chunk or frame comes along; that call then blocks. */
+int thia_classify_chunk(thia_classifier* c, const uint8_t* frames, int n, int H, int W, int ep, int32_t* out_labels,
+                        float* out_conf, float* out_logits);
+
+/* Single steps on caller tensors (NHWC, element type per the model's precision), for checking each against its
+ * definition: the 2x2 / stride-2 max-pool (a trailing odd row / column is dropped), in [n,H,W,C] -> out [n,H/2,W/2,C];
+ * and exit ep's unit on a tapped map feat [n,HW,C_tap]. */
+int thia_classifier_op_pool(thia_classifier* c, const void* in, int n, int H, int W, int C, void* out);
+int thia_classifier_op_unit(thia_classifier* c, const void* feat, int n, int HW, int ep, int32_t* out_labels, float* out_conf,
+                            float* out_logits);
+
 #ifdef __cplusplus
 }
 #endif

@@ -3,7 +3,7 @@
 
 The names below mirror the C entry points; they only marshal arguments.
 """
-from .binding import (Model, ThiaError, ThiaInfo, ThiaQuery, ThiaPlannerCfg, ThiaPlanStats, lib, planner_cfg, plan_from_flags, metrics_from_counts,
+from .binding import (Model, Classifier, ThiaError, ThiaInfo, ThiaQuery, ThiaPlannerCfg, ThiaPlanStats, lib, planner_cfg, plan_from_flags, metrics_from_counts,
                       EXPORTS, TAPS, KERNEL_CLASSES, LIB_PATH)
 
 
@@ -49,3 +49,13 @@ def thia_plan_from_flags(flags, cfg=None):
 
 def thia_free_model(model):
     model.close()
+
+
+def thia_classifier_load(weights, n_exits, device="cuda:0"):
+    """weights: uint8 numpy blob of an image classifier with exits.  Returns the resident classifier."""
+    return Classifier(weights, n_exits, device)
+
+
+def thia_classify_chunk(classifier, frames, ep, want_logits=False):
+    """frames: cuda uint8 [n,3,H,W]; ep in 1..n_exits or 0 (skip).  Returns (labels, confidence[, logits])."""
+    return classifier.classify_chunk(frames, ep, want_logits)

@@ -28,7 +28,9 @@ EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_mi
            "thia_set_estimator", "thia_estimate_exit", "thia_run_query", "thia_answer_counts", "thia_metrics_from_counts", "thia_last_error", "thia_set_debug", "thia_debug_tap",
            "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
            "thia_op_rpn_proposals", "thia_op_nms", "thia_op_nms_noalloc", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
-           "thia_op_stem", "thia_op_bottleneck", "thia_op_bottleneck_tail", "thia_set_fusion"]
+           "thia_op_stem", "thia_op_bottleneck", "thia_op_bottleneck_tail", "thia_set_fusion",
+           "thia_classifier_load", "thia_classifier_free", "thia_classifier_set_stream", "thia_classifier_last_error",
+           "thia_classify_chunk", "thia_classifier_op_pool", "thia_classifier_op_unit"]
 
 
 class ThiaInfo(C.Structure):
@@ -113,6 +115,15 @@ def lib():
     L.thia_op_bottleneck.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.thia_op_bottleneck_tail.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
     L.thia_set_fusion.argtypes = [vp, i32]
+    L.thia_classifier_load.argtypes = [vp, sz, i32, C.POINTER(vp)]
+    L.thia_classifier_free.argtypes = [vp]
+    L.thia_classifier_free.restype = None
+    L.thia_classifier_set_stream.argtypes = [vp, vp]
+    L.thia_classifier_last_error.argtypes = [vp]
+    L.thia_classifier_last_error.restype = C.c_char_p
+    L.thia_classify_chunk.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
+    L.thia_classifier_op_pool.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+    L.thia_classifier_op_unit.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
     for name in EXPORTS:
         getattr(L, name)
     _lib = L
@@ -460,3 +471,64 @@ class Model:
         out = torch.empty((n, Hp, Wp, 64), dtype=self.elem, device=self.device)
         self._check(lib().thia_op_stem(self._h, _ptr(frames), n, H, W, _ptr(out)))
         return out
+
+
+class Classifier:
+    """One resident image classifier with exits (thia_classifier*): argument marshalling only."""
+
+    def __init__(self, blob, n_exits, device="cuda:0"):
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        blob = np.ascontiguousarray(blob, dtype=np.uint8)
+        h = C.c_void_p()
+        rc = lib().thia_classifier_load(blob.ctypes.data, blob.nbytes, n_exits, C.byref(h))
+        if rc:
+            raise ThiaError(rc, "thia_classifier_load")
+        self._h = h
+        hi = blob[:256].view(np.int32)
+        self.precision, self.n_exits, self.n_classes = int(hi[2]), int(hi[3]), int(hi[6])
+        self.elem = torch.bfloat16 if self.precision else torch.float32
+        lib().thia_classifier_set_stream(self._h, C.c_void_p(torch.cuda.current_stream().cuda_stream))
+
+    def _check(self, rc):
+        if rc:
+            raise ThiaError(rc, (lib().thia_classifier_last_error(self._h) or b"").decode())
+
+    def classify_chunk(self, frames, ep, want_logits=False):
+        """frames cuda uint8 [n,3,H,W] -> (labels int32 [n], confidence float32 [n][, logits float32 [n,classes]])."""
+        _dev(frames, torch.uint8)
+        n, c, H, W = frames.shape
+        assert c == 3
+        labels = torch.empty((n,), dtype=torch.int32, device=self.device)
+        conf = torch.empty((n,), dtype=torch.float32, device=self.device)
+        logits = torch.empty((n, self.n_classes), dtype=torch.float32, device=self.device) if want_logits else None
+        self._check(lib().thia_classify_chunk(self._h, _ptr(frames), n, H, W, ep, _ptr(labels), _ptr(conf), _ptr(logits)))
+        return (labels, conf, logits) if want_logits else (labels, conf)
+
+    def op_pool(self, x):
+        _dev(x, self.elem)
+        n, H, W, Cc = x.shape
+        out = torch.empty((n, H // 2, W // 2, Cc), dtype=self.elem, device=self.device)
+        self._check(lib().thia_classifier_op_pool(self._h, _ptr(x), n, H, W, Cc, _ptr(out)))
+        return out
+
+    def op_unit(self, feat, ep):
+        """feat cuda [n,HW,C_tap] -> (labels, confidence, logits)."""
+        _dev(feat, self.elem)
+        n, HW = feat.shape[0], feat.shape[1]
+        labels = torch.empty((n,), dtype=torch.int32, device=self.device)
+        conf = torch.empty((n,), dtype=torch.float32, device=self.device)
+        logits = torch.empty((n, self.n_classes), dtype=torch.float32, device=self.device)
+        self._check(lib().thia_classifier_op_unit(self._h, _ptr(feat), n, HW, ep, _ptr(labels), _ptr(conf), _ptr(logits)))
+        return labels, conf, logits
+
+    def close(self):
+        if self._h:
+            lib().thia_classifier_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libthia.so")
-SOURCES = ["conv_igemm.hip", "bottleneck_fused.hip", "stem.hip", "rpn.hip", "roi.hip", "planner.hip", "model.hip"]
+SOURCES = ["conv_igemm.hip", "bottleneck_fused.hip", "stem.hip", "rpn.hip", "roi.hip", "planner.hip", "classifier.hip", "model.hip"]
 # -ffp-contract=off: box geometry and overlap tests must use singly rounded fp32 operations.
 # packed-fp32-ops is switched off for the test machines of machines.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
