@@ -265,6 +265,8 @@ int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, c
  * the predicate to the detections.  frames dev uint8 [n,3,H,W]; answers dev uint8 [n] (1 = the frame
  * satisfies the predicate; frames of skipped chunks are 0).  plan outputs (start/len/ep, capacity cap)
  * and stats as for thia_plan_query; they may be used to see which exit answered which frame.
+ * Frames the planner has already evaluated keep the answer computed then (the same kernels on the same frame give the
+ * same detections) and are not run again: answers equals thia_run_chunks on the plan followed by thia_eval_predicate.
  * Blocks while planning; the execution and the predicate are enqueued on the model's stream and
  * the call returns without waiting for them.  The detections of the n frames go to a buffer
  * that belongs to the model and only ever grows.

@@ -1244,8 +1244,10 @@ int thia_plan_from_flags(const uint8_t* flags, int n, int n_exits, const thia_pl
     return store_plan(plan, cap, start, len, ep);
 }
 
-int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, const thia_query* q, const thia_planner_cfg* cfg,
-                    int cap, int32_t* start, int32_t* len, int32_t* ep, thia_plan_stats* stats, uint8_t* evaluated) {
+namespace {
+int plan_query_impl(thia_model* m, const uint8_t* frames, int n, int H, int W, const thia_query* q, const thia_planner_cfg* cfg,
+                    int cap, int32_t* start, int32_t* len, int32_t* ep, thia_plan_stats* stats, uint8_t* evaluated,
+                    std::vector<uint8_t>* memo_out) {
     if (!m) return THIA_E_BADARG;
     if (n < 0 || !q || !cfg || cap < 0 || !stats || (n > 0 && !frames) || (cap > 0 && (!start || !len || !ep)))
         return fail(m, THIA_E_BADARG, "bad planner arguments");
@@ -1291,22 +1293,54 @@ int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, c
     };
     std::vector<PlanChunk> plan;
     std::string err;
-    const int rc = plan_core(n, E, *cfg, eval, plan, *stats, evaluated, err);
+    const int rc = plan_core(n, E, *cfg, eval, plan, *stats, evaluated, err, memo_out);
     if (rc != THIA_OK) return fail(m, rc, err);
     if (store_plan(plan, cap, start, len, ep) != THIA_OK) return fail(m, THIA_E_BADARG, "plan has more chunks than the capacity given");
     return THIA_OK;
+}
+}  // namespace
+
+int thia_plan_query(thia_model* m, const uint8_t* frames, int n, int H, int W, const thia_query* q, const thia_planner_cfg* cfg,
+                    int cap, int32_t* start, int32_t* len, int32_t* ep, thia_plan_stats* stats, uint8_t* evaluated) {
+    return plan_query_impl(m, frames, n, H, W, q, cfg, cap, start, len, ep, stats, evaluated, nullptr);
 }
 
 int thia_run_query(thia_model* m, const uint8_t* frames, int n, int H, int W, const thia_query* q, const thia_planner_cfg* cfg,
                    uint8_t* answers, int cap, int32_t* start, int32_t* len, int32_t* ep, thia_plan_stats* stats) {
     if (!m) return THIA_E_BADARG;
     if (n > 0 && !answers) return fail(m, THIA_E_BADARG, "null pointer");
-    TRY(thia_plan_query(m, frames, n, H, W, q, cfg, cap, start, len, ep, stats, nullptr));
+    std::vector<uint8_t> evaluated(n > 0 ? n : 1), memo;
+    TRY(plan_query_impl(m, frames, n, H, W, q, cfg, cap, start, len, ep, stats, evaluated.data(), &memo));
     if (n == 0) return THIA_OK;
-    // detections of all n frames: model-owned, grow-only
-    TRY(ensure_staging(m, m->qout, 0, (size_t)n, 0, 0));
-    TRY(thia_run_chunks(m, frames, n, H, W, stats->n_chunks, start, len, ep, m->qout.ob, m->qout.os, m->qout.ol));
-    return thia_eval_predicate(m, m->qout.ol, m->qout.os, n, q, answers);
+    // Memoisation carried over from the optimisation to the execution (Sec. 5.2): a frame the planner evaluated already has
+    // its answer at every exit (evaluation-based selection), or at the reference exit (estimation-based selection, where the
+    // other exits' entries are estimates and are not reused).  Such frames are cut out of their chunks; the remainders
+    // share micro-batches like any short chunks.
+    const int E = m->n_exits;
+    const bool est = cfg->use_estimator != 0;
+    std::vector<uint8_t> over((size_t)n, (uint8_t)2);
+    std::vector<int32_t> cs, cl, ce;
+    for (int c = 0; c < stats->n_chunks; ++c) {
+        const int e = ep[c];
+        if (e == 0 || (est && e != E)) { cs.push_back(start[c]); cl.push_back(len[c]); ce.push_back(e); continue; }
+        int a = start[c];
+        for (int f = start[c]; f <= start[c] + len[c]; ++f) {
+            const bool cut = f == start[c] + len[c] || evaluated[f];
+            if (!cut) continue;
+            if (f > a) { cs.push_back(a); cl.push_back(f - a); ce.push_back(e); }
+            if (f < start[c] + len[c]) over[f] = memo[(size_t)f * E + (e - 1)] ? 1 : 0;
+            a = f + 1;
+        }
+    }
+    // the known answers go up first (the stream is idle: planning ended with a synchronisation), detections of all n
+    // frames live in a model-owned, grow-only buffer
+    TRY(ensure_staging(m, m->qout, 0, (size_t)n, (size_t)n, 0));
+    HIP_TRY(m, hipMemcpyAsync(m->qout.flags, over.data(), (size_t)n, hipMemcpyHostToDevice, m->stream));
+    HIP_TRY(m, hipStreamSynchronize(m->stream));
+    TRY(thia_run_chunks(m, frames, n, H, W, (int)cs.size(), cs.data(), cl.data(), ce.data(), m->qout.ob, m->qout.os, m->qout.ol));
+    TRY(thia_eval_predicate(m, m->qout.ol, m->qout.os, n, q, answers));
+    HIP_TRY(m, launch_apply_known_answers(m->qout.flags, n, answers, m->stream));
+    return THIA_OK;
 }
 
 const char* thia_last_error(const thia_model* m) { return m ? m->err.c_str() : "null model"; }

@@ -107,6 +107,17 @@ hipError_t launch_count_predicate(const int32_t* labels, const float* scores, lo
     return hipGetLastError();
 }
 
+// answers[i] = over[i] where over[i] < 2 (frames whose answer is already known), else unchanged
+__global__ void apply_known_answers_kernel(const uint8_t* __restrict__ over, long n, uint8_t* __restrict__ answers) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n && over[i] < 2) answers[i] = over[i];
+}
+hipError_t launch_apply_known_answers(const uint8_t* over, long n, uint8_t* answers, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(apply_known_answers_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, over, n, answers);
+    return hipGetLastError();
+}
+
 hipError_t launch_answer_counts(const uint8_t* ans, const uint8_t* ref, long n, int32_t* counts, hipStream_t s) {
     hipLaunchKernelGGL(answer_counts_kernel, dim3(1), dim3(1024), 0, s, ans, ref, n, counts);
     return hipGetLastError();
@@ -132,7 +143,7 @@ const char* planner_cfg_error(const thia_planner_cfg& c) {
 }
 
 int plan_core(int n, int E, const thia_planner_cfg& cfg, const PlanEval& eval, std::vector<PlanChunk>& plan, thia_plan_stats& st,
-              uint8_t* evaluated_mask, std::string& err) {
+              uint8_t* evaluated_mask, std::string& err, std::vector<uint8_t>* memo_out) {
     plan.clear();
     st = thia_plan_stats{};
     if (evaluated_mask) std::fill(evaluated_mask, evaluated_mask + n, (uint8_t)0);
@@ -232,6 +243,7 @@ int plan_core(int n, int E, const thia_planner_cfg& cfg, const PlanEval& eval, s
     }
     std::sort(plan.begin(), plan.end(), [](const PlanChunk& x, const PlanChunk& y) { return x.start < y.start; });
     st.n_chunks = (int)plan.size();
+    if (memo_out) memo_out->swap(memo);   // rows of evaluated frames hold their answers, the rest is zero
     return THIA_OK;
 }
 

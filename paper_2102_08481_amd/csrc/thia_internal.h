@@ -187,7 +187,10 @@ struct PlanChunk { int start, len, ep; };
 // Evaluates every exit on k frames (indices in `frames`) and writes their answers, flags[i * E + e]; blocks until done.
 using PlanEval = std::function<int(const int* frames, int k, uint8_t* flags, std::string& err)>;
 const char* planner_cfg_error(const thia_planner_cfg& c);  // nullptr if the configuration is usable
+// memo_out (optional): receives the per-frame answers the planner memoised, [n][E]; rows of frames it did not evaluate are zero.
 int plan_core(int n, int E, const thia_planner_cfg& cfg, const PlanEval& eval, std::vector<PlanChunk>& plan, thia_plan_stats& st,
-              uint8_t* evaluated_mask, std::string& err);
+              uint8_t* evaluated_mask, std::string& err, std::vector<uint8_t>* memo_out = nullptr);
+// answers[i] = over[i] for the frames with over[i] < 2 (uint8, device)
+hipError_t launch_apply_known_answers(const uint8_t* over, long n, uint8_t* answers, hipStream_t s);
 
 }  // namespace thia

@@ -218,6 +218,12 @@ def test_plan_query_with_estimator_equals_the_oracle_planner_on_the_same_estimat
     kw = dict(min_chunk=9, final_span=2, posi_enough=0.1, posi_skip=0.0, reuse_dist=0)
     plan_o, pl = P.plan_from_estimates(ref, opt, 4, P.PlannerConfig(**kw))
     plan, st, ev = m.plan_query(frames, label, t, 0.0, planner_cfg(eval_batch=16, use_estimator=1, **kw))
+    # the whole query in this mode: only reference-exit answers of sampled frames are carried over to the execution
+    answers, plan_q, _ = m.run_query(frames, label, t, 0.0, planner_cfg(eval_batch=16, use_estimator=1, **kw))
+    cb, cs, cl = m.run_chunks(frames, plan)
+    want = m.eval_predicate(cl, cs, label, t, 0.0)
+    torch.cuda.synchronize()
+    assert plan_q == plan and torch.equal(answers, want)
     m.set_estimator(None, None, None, None)
     assert plan == plan_o
     assert np.flatnonzero(ev).tolist() == sorted(pl.evaluated) and st["samples_reused"] == pl.reused
@@ -237,7 +243,8 @@ def test_run_query_is_plan_then_execution_then_predicate():
     b, s, l = m.run_chunks(frames, plan)
     want = m.eval_predicate(l, s, label, t, 0.0)
     torch.cuda.synchronize()
-    assert torch.equal(answers, want)
+    assert torch.equal(answers, want)       # (sampled frames keep the answer of the planning pass and are not run again)
+    assert st["frames_evaluated"] > 0
     # against the oracle's metrics: frames of skipped chunks answer "no"
     flags = _answers_of_every_frame(m, frames, label, t, 0.0)
     exp = np.zeros(n, bool)
