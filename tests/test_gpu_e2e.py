@@ -328,6 +328,29 @@ def test_all_exits_in_one_pass_matches_each_exit_and_the_oracle():
     assert e[0].shape == (4, 0, m.D, 4)
 
 
+@pytest.mark.parametrize("H,W", [(32, 32), (96, 128)])
+def test_smallest_frames_and_largest_proposal_count(H, W):
+    """The limits of the boundary: the smallest frame it accepts (32 x 32: the last exit's map is a single position, every
+    exit has fewer anchors than the top-k asks for) and the largest pre-NMS count (4096), on the fp32 path, every exit
+    against the oracle."""
+    from dataclasses import replace
+    spec = replace(MINI_FP32, pre_nms=4096, post_nms=512, n_classes=4)
+    m, blob = gpu_model(spec, 0xBEEF + 52)
+    frames = make_frames(SceneSpec(H, W, 3, 1, 3, 6, 24), 77)
+    orc = oracle.Model(blob)
+    for ep in (1, 2, 3, 4):
+        gb, gs, gl = m.detect_chunk(to_dev(frames), ep)
+        torch.cuda.synchronize()
+        ref = orc.detect(frames, ep, taps=["prop_n", "roi_n"])
+        assert ref["prop_n"].max() <= 4096 and ref["roi_n"].max() <= 512
+        if ref["labels"].max() >= 0:
+            _check_detections(gb.cpu().numpy(), gs.cpu().numpy(), gl.cpu().numpy(), ref)
+        else:
+            assert (gl == -1).all()
+    if (H, W) == (96, 128):
+        assert orc.detect(frames, 1, taps=["prop_n"])["prop_n"].min() > 2000      # the 4096-wide sort is really exercised
+
+
 def test_argument_errors_return_codes():
     from paper_2102_08481_amd import lib, ThiaError, thia_load_model
     m, blob = gpu_model(MINI_BF16, 0xBEEF + 51)

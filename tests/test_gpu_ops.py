@@ -235,6 +235,24 @@ def test_nms_op_large_cap():
         assert cnt[f].item() == len(ref) and np.array_equal(keep[f, :len(ref)].cpu().numpy(), ref)
 
 
+def test_nms_op_maximum_cap():
+    """The largest proposal count the step accepts (4096 boxes: 64 words per mask row, 16 staged words per thread)."""
+    m, _ = _model(0)
+    rs = np.random.RandomState(6)
+    cap = 4096
+    counts = np.array([4096, 4095, 3000], np.int32)
+    boxes = np.zeros((3, cap, 4), np.float32)
+    for f, c in enumerate(counts):
+        boxes[f, :c] = _rand_boxes(rs, c, 500.0)
+    for thr, max_keep in [(0.7, 4096), (0.5, 1000)]:
+        keep, cnt = m.op_nms(to_dev(boxes), to_dev(counts), thr, max_keep)
+        torch.cuda.synchronize()
+        for f, c in enumerate(counts):
+            ref = oracle.nms(boxes[f, :c], thr, max_keep)
+            assert cnt[f].item() == len(ref) and np.array_equal(keep[f, :len(ref)].cpu().numpy(), ref), (thr, f)
+            assert (keep[f, len(ref):] == -1).all()
+
+
 @pytest.mark.parametrize("precision", [0, 1])
 def test_rpn_proposals_op_matches_oracle(precision):
     """Top-k indices are bit-exact on identical logits (including ties and signed zeros);
