@@ -3,87 +3,126 @@
 // same-class greedy NMS, top-D).
 #include "device_util.h"
 
+#include <type_traits>
+
 namespace thia {
 
 // ------------------------------------------------------------------ ROIAlign
 // One block per ROI; threads run over channels, so every tap is one contiguous run of Ch
-// elements of the NHWC map.  The P*P*4 sample positions (4 texel offsets + 4 bilinear
-// weights each) are computed once per ROI into LDS.  Convention: texel j has centre
-// j + 0.5; a sample more than one texel outside the map contributes zero; otherwise its
-// coordinates are clamped to the texel-centre range.  Output layout [(ph*P + pw)][c].
+// elements of the NHWC map.  Convention: texel j has centre j + 0.5; a sample more than one
+// texel outside the map contributes zero; otherwise its coordinates are clamped to the
+// texel-centre range.  Output layout [(ph*P + pw)][c].
+//
+// A bin averages 2 x 2 samples of 2 x 2 texels each, and both the sample grid and the bilinear
+// weights are products of a row factor and a column factor.  So a bin is sum_y sum_x Wy[y] Wx[x] F[y][x]
+// over the DISTINCT rows and columns its samples touch (2 to 4 of each), with the weights of coinciding
+// texels added up: a bin narrower than two texels gathers 4, 6 or 9 texels instead of 16.  The per-axis
+// lists are built once per ROI (2 P threads), expanded to one tap table per bin in LDS (texel offset and
+// weight, the 1/4 of the average folded in, entries past the bin's count zero), and every work item runs
+// the smallest unrolled gather that covers its bin's count.
+constexpr int ROI_TAPS = 16;   // most taps per bin (4 rows x 4 columns)
+
+__host__ __device__ inline size_t roialign_lds_bytes(int P) {
+    return (size_t)P * P * (ROI_TAPS * 8 + 4) + (size_t)2 * P * (4 * 8 + 4);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void roialign_kernel(const T* __restrict__ feat, const float* __restrict__ rois, int post,
                                                        int Hk, int Wk, int Ch, float scale, int P, T* __restrict__ out) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    const int ns = P * P * 4;
-    int* s_off = reinterpret_cast<int*>(smem_raw);             // [ns][4] texel offsets (in pixels of the map)
-    float* s_w = reinterpret_cast<float*>(s_off + 4 * ns);     // [ns][4]
+    const int nb = P * P;
+    int* s_off = reinterpret_cast<int*>(smem_raw);             // [nb][16] texel offsets (in pixels of the map)
+    float* s_w = reinterpret_cast<float*>(s_off + ROI_TAPS * nb);   // [nb][16]
+    int* s_nt = reinterpret_cast<int*>(s_w + ROI_TAPS * nb);   // [nb] taps of the bin
+    int* ax_i = s_nt + nb;                                     // [2 P][4] distinct texel rows (first P lists) / columns
+    float* ax_w = reinterpret_cast<float*>(ax_i + 8 * P);      // [2 P][4] their summed weights
+    int* ax_n = reinterpret_cast<int*>(ax_w + 8 * P);          // [2 P] entries per list
     const int roi = blockIdx.x, f = roi / post;
     const float4 r = *reinterpret_cast<const float4*>(rois + 4 * (size_t)roi);
     const float x1 = r.x * scale, y1 = r.y * scale;
     const float bw = (r.z * scale - x1) / (float)P, bh = (r.w * scale - y1) / (float)P;
-    for (int s = threadIdx.x; s < ns; s += blockDim.x) {
-        const int bin = s >> 2, ph = bin / P, pw = bin - ph * P, iy = (s >> 1) & 1, ix = s & 1;
-        const float fy = y1 + (float)ph * bh + ((float)iy + 0.5f) * bh * 0.5f;
-        const float fx = x1 + (float)pw * bw + ((float)ix + 0.5f) * bw * 0.5f;
-        float u = fx - 0.5f, v = fy - 0.5f;
-        int o[4] = {0, 0, 0, 0};
-        float w[4] = {0.f, 0.f, 0.f, 0.f};
-        if (!(u < -1.f || u > (float)Wk || v < -1.f || v > (float)Hk)) {
-            u = fminf(fmaxf(u, 0.f), (float)(Wk - 1));
-            v = fminf(fmaxf(v, 0.f), (float)(Hk - 1));
-            const int x0 = (int)floorf(u), y0 = (int)floorf(v);
-            const int xb = x0 + 1 < Wk ? x0 + 1 : Wk - 1, yb = y0 + 1 < Hk ? y0 + 1 : Hk - 1;
-            const float lx = u - (float)x0, ly = v - (float)y0;
-            o[0] = y0 * Wk + x0; o[1] = y0 * Wk + xb; o[2] = yb * Wk + x0; o[3] = yb * Wk + xb;
-            w[0] = (1.f - ly) * (1.f - lx); w[1] = (1.f - ly) * lx; w[2] = ly * (1.f - lx); w[3] = ly * lx;
+    if ((int)threadIdx.x < 2 * P) {
+        const int lst = threadIdx.x, isx = lst >= P, p = isx ? lst - P : lst;
+        const float start = isx ? x1 : y1, b = isx ? bw : bh;
+        const int L = isx ? Wk : Hk;
+        int n = 0;
+        auto add = [&](int j, float w) {
+            for (int k = 0; k < n; ++k)
+                if (ax_i[4 * lst + k] == j) { ax_w[4 * lst + k] += w; return; }
+            ax_i[4 * lst + n] = j; ax_w[4 * lst + n] = w; ++n;
+        };
+        for (int i = 0; i < 2; ++i) {
+            float tc = start + (float)p * b + ((float)i + 0.5f) * b * 0.5f - 0.5f;
+            if (tc < -1.f || tc > (float)L) continue;
+            tc = fminf(fmaxf(tc, 0.f), (float)(L - 1));
+            const int i0 = (int)floorf(tc), i1 = i0 + 1 < L ? i0 + 1 : L - 1;
+            const float l = tc - (float)i0;
+            add(i0, 1.f - l);
+            add(i1, l);
         }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { s_off[4 * s + q] = o[q]; s_w[4 * s + q] = w[q]; }
+        ax_n[lst] = n;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < ROI_TAPS * nb; e += blockDim.x) {
+        const int bin = e / ROI_TAPS, k = e - bin * ROI_TAPS, ph = bin / P, pw = bin - ph * P;
+        const int ny = ax_n[ph], nx = ax_n[P + pw], nt = ny * nx;
+        int off = 0;
+        float w = 0.f;
+        if (k < nt) {
+            const int ia = k / nx, ib = k - ia * nx;
+            off = ax_i[4 * ph + ia] * Wk + ax_i[4 * (P + pw) + ib];
+            w = ax_w[4 * ph + ia] * ax_w[4 * (P + pw) + ib] * 0.25f;
+        }
+        s_off[e] = off;
+        s_w[e] = w;
+        if (k == 0) s_nt[bin] = nt;
     }
     __syncthreads();
     const T* fm = feat + (size_t)f * Hk * Wk * Ch;
-    T* o = out + (size_t)roi * P * P * Ch;
+    T* o = out + (size_t)roi * nb * Ch;
     // one work item = one bin x one 16-byte run of channels; consecutive threads take consecutive runs
     constexpr int VEC = 16 / (int)sizeof(T);
     const int runs = Ch / VEC;
-    for (int i = threadIdx.x; i < P * P * runs; i += blockDim.x) {
+    for (int i = threadIdx.x; i < nb * runs; i += blockDim.x) {
         const int bin = i / runs, c = (i - bin * runs) * VEC;
+        const int nt = s_nt[bin];
+        const int* toff = s_off + ROI_TAPS * bin;
+        const float* tw = s_w + ROI_TAPS * bin;
         float sum[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) sum[e] = 0.f;
+        auto gather = [&](auto nc) {
+            constexpr int N = decltype(nc)::value;
+            uint4 raw[N];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int q = 4 * (4 * bin + s);
-            float a[VEC];
+            for (int k = 0; k < N; ++k) raw[k] = *reinterpret_cast<const uint4*>(fm + (size_t)toff[k] * Ch + c);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) a[e] = 0.f;
-#pragma unroll
-            for (int tp = 0; tp < 4; ++tp) {
-                const float w = s_w[q + tp];
-                const uint4 raw = *reinterpret_cast<const uint4*>(fm + (size_t)s_off[q + tp] * Ch + c);
+            for (int k = 0; k < N; ++k) {
+                const float w = tw[k];
                 if constexpr (sizeof(T) == 2) {
-                    const uint32_t wd[4] = {raw.x, raw.y, raw.z, raw.w};
+                    const uint32_t wd[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        a[2 * e] += w * __uint_as_float(wd[e] << 16);
-                        a[2 * e + 1] += w * __uint_as_float(wd[e] & 0xffff0000u);
+                        sum[2 * e] += w * __uint_as_float(wd[e] << 16);
+                        sum[2 * e + 1] += w * __uint_as_float(wd[e] & 0xffff0000u);
                     }
                 } else {
-                    a[0] += w * __uint_as_float(raw.x); a[1] += w * __uint_as_float(raw.y);
-                    a[2] += w * __uint_as_float(raw.z); a[3] += w * __uint_as_float(raw.w);
+                    sum[0] += w * __uint_as_float(raw[k].x); sum[1] += w * __uint_as_float(raw[k].y);
+                    sum[2] += w * __uint_as_float(raw[k].z); sum[3] += w * __uint_as_float(raw[k].w);
                 }
             }
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) sum[e] += a[e];
-        }
+        };
+        if (nt <= 4) gather(std::integral_constant<int, 4>{});
+        else if (nt <= 6) gather(std::integral_constant<int, 6>{});
+        else if (nt <= 9) gather(std::integral_constant<int, 9>{});
+        else if (nt <= 12) gather(std::integral_constant<int, 12>{});
+        else gather(std::integral_constant<int, 16>{});
         uint4 pk;
         if constexpr (sizeof(T) == 2) {
-            pk = make_uint4(pack_bf16x2(sum[0] * 0.25f, sum[1] * 0.25f), pack_bf16x2(sum[2] * 0.25f, sum[3] * 0.25f),
-                            pack_bf16x2(sum[4] * 0.25f, sum[5] * 0.25f), pack_bf16x2(sum[6] * 0.25f, sum[7] * 0.25f));
+            pk = make_uint4(pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3]), pack_bf16x2(sum[4], sum[5]),
+                            pack_bf16x2(sum[6], sum[7]));
         } else {
-            pk = make_uint4(__float_as_uint(sum[0] * 0.25f), __float_as_uint(sum[1] * 0.25f), __float_as_uint(sum[2] * 0.25f),
-                            __float_as_uint(sum[3] * 0.25f));
+            pk = make_uint4(__float_as_uint(sum[0]), __float_as_uint(sum[1]), __float_as_uint(sum[2]), __float_as_uint(sum[3]));
         }
         *reinterpret_cast<uint4*>(o + (size_t)bin * Ch + c) = pk;
     }
@@ -92,7 +131,7 @@ __global__ __launch_bounds__(256) void roialign_kernel(const T* __restrict__ fea
 hipError_t launch_roialign(const void* feat, const float* rois, int n, int post, int Hk, int Wk, int Ch, int stride, int P,
                            int precision, void* out, hipStream_t s) {
     if (n <= 0 || post <= 0 || P <= 0 || P > 16 || Ch % 8) return hipErrorInvalidValue;
-    const size_t lds = (size_t)P * P * 4 * 4 * 8;
+    const size_t lds = roialign_lds_bytes(P);
     const float scale = 1.0f / (float)stride;
     const unsigned blocks = (unsigned)n * (unsigned)post;
     if (precision)
