@@ -374,6 +374,31 @@ def main():
         "hbm_side_kernels": hbm_side,
     }
 
+    if not args.skip_all_exits:
+        # beside the metric: a mixed plan through thia_run_plan (256 frames of the same scene in 8 chunks of 32 at exits
+        # 1,4,2,2,3,1,4,3), with the micro-batches alternating between the library's two lanes and on one lane
+        from dataclasses import replace
+        c4 = CONFIGS[4]
+        plan = list(c4.exits)
+        pf = torch.from_numpy(make_frames(replace(c4.scene, n_frames=B * len(plan)), c4.frame_seed)).cuda()
+        pout = model.alloc_outputs(pf.shape[0])
+        plan_ms = {}
+        for lanes in (2, 1):
+            model.set_lanes(lanes)
+            model.run_plan(pf, B, plan, pout)
+            ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            ea.record(stream)
+            for k in range(args.steps):
+                model.run_plan(pf, B, plan, pout)
+            eb.record(stream)
+            torch.cuda.synchronize()
+            plan_ms[lanes] = ea.elapsed_time(eb) / args.steps
+        model.set_lanes(2)
+        result["mixed_plan"] = {"workload": f"{pf.shape[0]} frames, {len(plan)} chunks of {B} at exits {plan}, one thia_run_plan call",
+                                "ms_per_plan": plan_ms[2], "frames_per_s": pf.shape[0] / (plan_ms[2] * 1e-3),
+                                "one_lane_ms_per_plan": plan_ms[1]}
+        del pf, pout
     if all_exits_ms is not None:
         result["all_exits_one_pass"] = {"ms_per_batch": all_exits_ms, "frames_per_s": B / (all_exits_ms * 1e-3),
                                         "vs_sweep": ms_per_step / all_exits_ms}

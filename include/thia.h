@@ -18,7 +18,9 @@
  *    the weights and its workspace inside thia_model.
  *  - Calls enqueue work on the model's stream (thia_set_stream; default: the null
  *    stream) and return without waiting, unless stated otherwise.  The caller
- *    synchronises before reading outputs.
+ *    synchronises before reading outputs.  (Calls that run several micro-batches also
+ *    use a second stream inside, joined into the model's stream before they return:
+ *    thia_set_lanes.)
  *  - Return value: THIA_OK (0) or a negative THIA_E_* code; thia_last_error() gives a
  *    message.  On an argument error nothing is enqueued and outputs are untouched.
  *  - Exits are numbered 1..n_exits (exit k reads the output of backbone stage
@@ -98,6 +100,16 @@ int thia_set_microbatch(thia_model* m, int frames);
  * accumulation order; the switch exists for measurements and tests. */
 int thia_set_fusion(thia_model* m, int on);
 
+/* Micro-batches of one call are independent of each other (Sec. 3: chunks are processed one by one, frames
+ * within them batched).  lanes = 2 (the default): a call that runs more than one micro-batch (thia_run_plan,
+ * thia_run_chunks, thia_run_query, thia_detect_chunk with more frames than a micro-batch) alternates them
+ * between the model's stream and a second stream owned by the model, with a second workspace, so one
+ * micro-batch's proposal and selection kernels overlap the next one's convolutions.  The second stream starts
+ * after everything queued on the model's stream when the call began, and the model's stream waits for it
+ * before the call returns: callers see single-stream ordering, and results do not change.  lanes = 1: one
+ * stream, one workspace.  Profiling and debug taps always run on one lane. */
+int thia_set_lanes(thia_model* m, int lanes);
+
 int thia_get_info(const thia_model* m, thia_info* out);
 
 /*
@@ -130,7 +142,7 @@ int thia_detect_all_exits(thia_model* m, const uint8_t* frames, int n, int H, in
  * Run a fine-grained plan (Sec. 3; Algorithm 1's output): frames dev uint8
  * [n_chunks*chunk_len,3,H,W]; chunk c = frames [c*chunk_len, (c+1)*chunk_len) runs at
  * exit chunk_ep[c] (host int32 [n_chunks], 0 = skip).  Chunks are grouped by exit and
- * enqueued group by group on the one stream; outputs are written at the frames' own
+ * enqueued group by group; outputs are written at the frames' own
  * positions, so out_* are laid out exactly as for n_chunks*chunk_len frames of
  * thia_detect_chunk, and each chunk's slice is bit-identical to a stand-alone call.  Chunks of
  * one exit share micro-batches (frames are independent): adjacent chunks are joined, and the

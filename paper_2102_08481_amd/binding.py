@@ -28,7 +28,7 @@ EXPORTS = ["thia_load_model", "thia_free_model", "thia_set_stream", "thia_set_mi
            "thia_set_estimator", "thia_estimate_exit", "thia_run_query", "thia_answer_counts", "thia_metrics_from_counts", "thia_last_error", "thia_set_debug", "thia_debug_tap",
            "thia_debug_tap_bytes", "thia_profile_begin", "thia_profile_read", "thia_profile_end",
            "thia_op_rpn_proposals", "thia_op_nms", "thia_op_nms_noalloc", "thia_op_roialign", "thia_op_select_detections", "thia_op_conv",
-           "thia_op_stem", "thia_op_bottleneck", "thia_op_bottleneck_tail", "thia_set_fusion",
+           "thia_op_stem", "thia_op_bottleneck", "thia_op_bottleneck_tail", "thia_set_fusion", "thia_set_lanes",
            "thia_classifier_load", "thia_classifier_free", "thia_classifier_set_stream", "thia_classifier_last_error",
            "thia_classify_chunk", "thia_classifier_op_pool", "thia_classifier_op_unit"]
 
@@ -115,6 +115,7 @@ def lib():
     L.thia_op_bottleneck.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.thia_op_bottleneck_tail.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
     L.thia_set_fusion.argtypes = [vp, i32]
+    L.thia_set_lanes.argtypes = [vp, i32]
     L.thia_classifier_load.argtypes = [vp, sz, i32, C.POINTER(vp)]
     L.thia_classifier_free.argtypes = [vp]
     L.thia_classifier_free.restype = None
@@ -439,6 +440,9 @@ class Model:
 
     def set_fusion(self, on):
         self._check(lib().thia_set_fusion(self._h, int(on)))   # 0 off, 1 where it pays (default), 2 wherever it applies
+
+    def set_lanes(self, lanes):
+        self._check(lib().thia_set_lanes(self._h, int(lanes)))   # 2 (default): micro-batches alternate between two streams
 
     def op_bottleneck(self, x, w1, b1, w2, b2, w3, b3, ws=None, bs=None):
         """x: cuda bf16 [n,H,W,Cin]; weights numpy fp32 in [Cout,Cin,k,k] order; ws/bs: projection shortcut."""

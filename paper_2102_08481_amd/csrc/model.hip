@@ -101,6 +101,22 @@ struct thia_model {
         uint8_t* flags = nullptr; size_t flags_cap = 0;
         int32_t* opt = nullptr; size_t opt_cap = 0;
     } stg, qry, qout;
+    // Second lane.  The micro-batches of one call are independent, so they alternate between the caller's stream (workspace
+    // ws, staging stg) and a stream of the model's own (ws_alt, stg_alt): the latency-bound proposal and selection kernels
+    // of one micro-batch then run beside the convolutions of the next, and the last partial round of tiles of a launch
+    // is filled by the other lane's blocks.  The model's stream starts after everything the caller had queued when the
+    // call began (ev_fork) and the caller's stream waits for it before the call returns (ev_join), so callers see the
+    // usual single-stream ordering.  Created on first use.
+    Workspace ws_alt;
+    Staging stg_alt;
+    hipStream_t lane_stream = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    int lanes = 2;              // 1: everything on the caller's stream
+    int lane_depth = 0;         // nesting of LaneScope
+    int lane_next = 0;          // lane of the next micro-batch
+    bool lane_ready = false;    // this call may use the second lane (set by LaneScope::begin)
+    bool lane_forked = false;   // the model's stream holds work of the current call
+    bool lane_active = false;   // the current code runs on the second lane (ws/stg/stream are swapped)
     bool debug = false;
     Tap taps[THIA_TAP_COUNT];
     bool profiling = false;
@@ -275,13 +291,15 @@ int default_microbatch(const thia_model* m, int H, int W) {
     return std::min(32, std::max(1, mb));
 }
 
-void free_workspace(thia_model* m) {
+int microbatch_frames(const thia_model* m, int H, int W) { return m->user_mb > 0 ? m->user_mb : default_microbatch(m, H, W); }
+
+void free_workspace(thia_model* m) {   // the current lane's
     if (m->ws.arena) (void)hipFree(m->ws.arena);
     m->ws = Workspace{};
 }
 
 int ensure_workspace(thia_model* m, int H, int W) {
-    const int mb = m->user_mb > 0 ? m->user_mb : default_microbatch(m, H, W);
+    const int mb = microbatch_frames(m, H, W);
     Workspace& ws = m->ws;
     if (ws.arena && ws.H == H && ws.W == W && ws.mb == mb) return THIA_OK;
     if (ws.arena) {
@@ -344,6 +362,73 @@ int ensure_workspace(thia_model* m, int H, int W) {
     ws.sel_keys = reinterpret_cast<uint64_t*>(a + o_keys); ws.key_cap = key_cap;
     return THIA_OK;
 }
+
+// ---------------------------------------------------------------- lanes
+// Bracket of one call.  The outermost scope notes where the caller's stream stood when the call began (begin); join makes
+// the caller's stream wait for what the call put on the model's stream.  On an error path the destructor waits for that
+// work on the host instead, so no call returns with work of its own still running beside the caller's stream.
+struct LaneScope {
+    thia_model* m;
+    explicit LaneScope(thia_model* m_) : m(m_) {
+        if (m->lane_depth++ == 0) { m->lane_next = 0; m->lane_forked = false; m->lane_ready = false; }
+    }
+    int begin() {
+        if (m->lane_depth != 1 || m->lanes < 2 || m->profiling || m->debug) return THIA_OK;
+        if (!m->lane_stream) {
+            HIP_TRY(m, hipStreamCreateWithFlags(&m->lane_stream, hipStreamNonBlocking));
+            HIP_TRY(m, hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming));
+            HIP_TRY(m, hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming));
+        }
+        if (!m->ev_fork || !m->ev_join) return THIA_OK;   // an earlier creation failed half-way: stay on one lane
+        HIP_TRY(m, hipEventRecord(m->ev_fork, m->stream));
+        m->lane_ready = true;
+        return THIA_OK;
+    }
+    int join() {
+        if (m->lane_depth != 1 || !m->lane_forked) return THIA_OK;
+        HIP_TRY(m, hipEventRecord(m->ev_join, m->lane_stream));
+        HIP_TRY(m, hipStreamWaitEvent(m->stream, m->ev_join, 0));
+        m->lane_forked = false;
+        return THIA_OK;
+    }
+    ~LaneScope() {
+        if (--m->lane_depth > 0) return;
+        if (m->lane_forked) (void)hipStreamSynchronize(m->lane_stream);
+        m->lane_forked = false;
+        m->lane_ready = false;
+    }
+};
+
+// Lane of the next micro-batch (0: the caller's stream).  The model's stream is held back to the call's start the first
+// time a call uses it.  Call outside any LaneGuard.
+int pick_lane(thia_model* m, int* lane) {
+    *lane = 0;
+    if (!m->lane_ready) return THIA_OK;
+    *lane = m->lane_next;
+    m->lane_next ^= 1;
+    if (*lane == 1 && !m->lane_forked) {
+        HIP_TRY(m, hipStreamWaitEvent(m->lane_stream, m->ev_fork, 0));
+        m->lane_forked = true;
+    }
+    return THIA_OK;
+}
+
+// While it lives, the model's stream, workspace and staging are those of `lane`: everything below addresses them as
+// m->stream, m->ws and m->stg.
+struct LaneGuard {
+    thia_model* m;
+    bool on;
+    LaneGuard(thia_model* m_, int lane) : m(m_), on(lane == 1) { if (on) flip(); }
+    ~LaneGuard() { if (on) flip(); }
+    LaneGuard(const LaneGuard&) = delete;
+    LaneGuard& operator=(const LaneGuard&) = delete;
+    void flip() {
+        std::swap(m->ws, m->ws_alt);
+        std::swap(m->stg, m->stg_alt);
+        std::swap(m->stream, m->lane_stream);
+        m->lane_active = !m->lane_active;
+    }
+};
 
 // ---------------------------------------------------------------- launch bookkeeping
 struct Scope {  // brackets one launch (group) with events when profiling is on
@@ -666,18 +751,32 @@ int check_frame_args(thia_model* m, const void* frames, int n, int H, int W, con
 }
 
 // n frames at exit ep (1..n_exits), micro-batched.  Assumes arguments were validated.
-int detect_frames(thia_model* m, const uint8_t* frames, int n, int H, int W, int ep, float* ob, float* os, int32_t* ol) {
+// One micro-batch (nb <= micro-batch frames) on the current lane; f0 = its position in the call (debug taps).
+int detect_batch_here(thia_model* m, const uint8_t* frames, int f0, int nb, int H, int W, int ep, float* ob, float* os, int32_t* ol) {
     TRY(ensure_workspace(m, H, W));
-    if (m->debug) TRY(prepare_taps(m, n, H, W, ep));
-    const int mb = m->ws.mb, D = m->D;
+    const void* feat = nullptr;
+    bool hf_done = false;
+    TRY(run_backbone(m, frames, nb, H, W, ep, &feat, &hf_done));
+    return run_heads(m, feat, f0, nb, H, W, ep, ob, os, ol, hf_done);
+}
+
+int detect_frames(thia_model* m, const uint8_t* frames, int n, int H, int W, int ep, float* ob, float* os, int32_t* ol) {
+    if (m->debug) {
+        TRY(ensure_workspace(m, H, W));
+        TRY(prepare_taps(m, n, H, W, ep));
+    }
+    LaneScope scope(m);
+    TRY(scope.begin());
+    const int mb = microbatch_frames(m, H, W), D = m->D;
     for (int f0 = 0; f0 < n; f0 += mb) {
         const int nb = std::min(mb, n - f0);
-        const void* feat = nullptr;
-        bool hf_done = false;
-        TRY(run_backbone(m, frames + (size_t)f0 * 3 * H * W, nb, H, W, ep, &feat, &hf_done));
-        TRY(run_heads(m, feat, f0, nb, H, W, ep, ob + (size_t)f0 * D * 4, os + (size_t)f0 * D, ol + (size_t)f0 * D, hf_done));
+        int lane = 0;
+        if (n > mb || m->lane_depth > 1) TRY(pick_lane(m, &lane));   // a lone micro-batch stays on the caller's stream
+        LaneGuard guard(m, lane);
+        TRY(detect_batch_here(m, frames + (size_t)f0 * 3 * H * W, f0, nb, H, W, ep, ob + (size_t)f0 * D * 4, os + (size_t)f0 * D,
+                              ol + (size_t)f0 * D));
     }
-    return THIA_OK;
+    return scope.join();
 }
 
 // n frames through the whole backbone once, every exit's heads applied to its own stage tensor on the way.
@@ -767,8 +866,9 @@ int run_spans(thia_model* m, const uint8_t* frames, int H, int W, int ep, std::v
         if (!runs.empty() && runs.back().start + runs.back().len == sp.start) runs.back().len += sp.len;
         else runs.push_back(sp);
     }
-    TRY(ensure_workspace(m, H, W));
-    const int mb = m->ws.mb;
+    LaneScope scope(m);
+    TRY(scope.begin());
+    const int mb = microbatch_frames(m, H, W);
     const size_t D = (size_t)m->D, fbytes = (size_t)3 * H * W;
     std::vector<Span> rest;   // what is left of each run after its whole micro-batches
     for (const Span& r : runs) {
@@ -796,6 +896,10 @@ int run_spans(thia_model* m, const uint8_t* frames, int H, int W, int ep, std::v
                               ol + (size_t)q.start * D));
             continue;
         }
+        // gather, run and scatter on one lane, with that lane's staging buffers
+        int lane = 0;
+        TRY(pick_lane(m, &lane));
+        LaneGuard guard(m, lane);
         TRY(ensure_staging(m, m->stg, (size_t)mb * fbytes, (size_t)mb, 0, 0));
         int pos = 0;
         for (const Span& q : pieces) {
@@ -803,7 +907,7 @@ int run_spans(thia_model* m, const uint8_t* frames, int H, int W, int ep, std::v
                                       hipMemcpyDeviceToDevice, m->stream));
             pos += q.len;
         }
-        TRY(detect_frames(m, m->stg.frames, total, H, W, ep, m->stg.ob, m->stg.os, m->stg.ol));
+        TRY(detect_batch_here(m, m->stg.frames, 0, total, H, W, ep, m->stg.ob, m->stg.os, m->stg.ol));
         pos = 0;
         for (const Span& q : pieces) {
             HIP_TRY(m, hipMemcpyAsync(ob + (size_t)q.start * D * 4, m->stg.ob + (size_t)pos * D * 4, (size_t)q.len * D * 16, hipMemcpyDeviceToDevice, m->stream));
@@ -812,7 +916,7 @@ int run_spans(thia_model* m, const uint8_t* frames, int H, int W, int ep, std::v
             pos += q.len;
         }
     }
-    return THIA_OK;
+    return scope.join();
 }
 
 void free_estimator(thia_model* m) {
@@ -1020,8 +1124,13 @@ void thia_free_model(thia_model* m) {
     if (m) free_estimator(m);
     if (!m) return;
     (void)hipStreamSynchronize(m->stream);
+    if (m->lane_stream) (void)hipStreamSynchronize(m->lane_stream);
     free_workspace(m);
-    free_staging(m->stg); free_staging(m->qry); free_staging(m->qout);
+    if (m->ws_alt.arena) (void)hipFree(m->ws_alt.arena);
+    free_staging(m->stg); free_staging(m->stg_alt); free_staging(m->qry); free_staging(m->qout);
+    if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
+    if (m->ev_join) (void)hipEventDestroy(m->ev_join);
+    if (m->lane_stream) (void)hipStreamDestroy(m->lane_stream);
     for (auto& t : m->taps) if (t.buf) (void)hipFree(t.buf);
     for (auto e : m->ev_pool) (void)hipEventDestroy(e);
     if (m->stem_w) (void)hipFree(m->stem_w);
@@ -1051,7 +1160,15 @@ void thia_free_model(thia_model* m) {
 int thia_set_stream(thia_model* m, void* hip_stream) {
     if (!m) return THIA_E_BADARG;
     HIP_TRY(m, hipStreamSynchronize(m->stream));
+    if (m->lane_stream) HIP_TRY(m, hipStreamSynchronize(m->lane_stream));
     m->stream = static_cast<hipStream_t>(hip_stream);
+    return THIA_OK;
+}
+
+int thia_set_lanes(thia_model* m, int lanes) {
+    if (!m) return THIA_E_BADARG;
+    if (lanes < 1 || lanes > 2) return fail(m, THIA_E_BADARG, "lanes must be 1 or 2");
+    m->lanes = lanes;
     return THIA_OK;
 }
 
@@ -1102,8 +1219,10 @@ int thia_run_plan(thia_model* m, const uint8_t* frames, int n_chunks, int chunk_
         if (chunk_ep[c] < 0 || chunk_ep[c] > m->n_exits) return fail(m, THIA_E_BADEP, "plan holds an exit outside 0..n_exits");
     if (n_chunks == 0 || chunk_len == 0) return THIA_OK;
     const int D = m->D;
-    // group chunks by exit: one group after the other on the one stream, outputs at the frames' own positions; the
-    // chunks of a group share micro-batches (run_spans)
+    LaneScope scope(m);
+    TRY(scope.begin());
+    // group chunks by exit: one group after the other, outputs at the frames' own positions; the chunks of a group share
+    // micro-batches (run_spans), and micro-batches alternate between the two lanes across the groups
     for (int ep = 0; ep <= m->n_exits; ++ep) {
         std::vector<Span> spans;
         for (int c = 0; c < n_chunks; ++c) {
@@ -1114,7 +1233,7 @@ int thia_run_plan(thia_model* m, const uint8_t* frames, int n_chunks, int chunk_
         }
         if (ep > 0) TRY(run_spans(m, frames, H, W, ep, spans, out_boxes, out_scores, out_labels));
     }
-    return THIA_OK;
+    return scope.join();
 }
 
 int thia_run_chunks(thia_model* m, const uint8_t* frames, int n, int H, int W, int n_chunks, const int32_t* start, const int32_t* len,
@@ -1133,6 +1252,8 @@ int thia_run_chunks(thia_model* m, const uint8_t* frames, int n, int H, int W, i
         if (spans[i].first < spans[i - 1].second) return fail(m, THIA_E_BADARG, "chunks overlap");
     if (n == 0) return THIA_OK;
     const int D = m->D;
+    LaneScope scope(m);
+    TRY(scope.begin());
     // frames no chunk covers, and skipped chunks, get the empty pattern
     int pos = 0;
     for (size_t i = 0; i <= spans.size(); ++i) {
@@ -1152,7 +1273,7 @@ int thia_run_chunks(thia_model* m, const uint8_t* frames, int n, int H, int W, i
         }
         if (e > 0) TRY(run_spans(m, frames, H, W, e, group, out_boxes, out_scores, out_labels));
     }
-    return THIA_OK;
+    return scope.join();
 }
 
 void thia_planner_defaults(thia_planner_cfg* cfg) {

@@ -300,6 +300,43 @@ def test_short_chunks_share_micro_batches_and_stay_bit_identical(L):
             assert (pl[a:a + ln, 0] >= 1).all()
 
 
+def test_two_lanes_give_the_results_of_one_lane_in_stream_order():
+    """Micro-batches of one call alternate between the model's stream and its second stream.  The detections equal the
+    one-lane ones bit for bit (plan of mixed exits with whole micro-batches, remainders and gathered pieces; a long
+    single-exit chunk), also for calls queued back to back without a host wait, and work queued on the model's stream
+    right after a call sees the call's finished outputs."""
+    m, _ = gpu_model(MINI_BF16, 0xBEEF + 51)
+    plan = [2, 2, 1, 0, 2, 4, 1, 1, 3, 2, 0, 4, 4, 2, 3, 3, 3]
+    L = 3
+    n = L * len(plan)
+    frames = to_dev(make_frames(SceneSpec(160, 224, n, 4, 10, 10, 90), 77))
+    chunks = [(c * L, L, ep) for c, ep in enumerate(plan)]
+    m.set_microbatch(4)
+    try:
+        m.set_lanes(1)
+        ref_plan = m.run_plan(frames, L, plan)
+        ref_long = m.detect_chunk(frames, 3)
+        torch.cuda.synchronize()
+        m.set_lanes(2)
+        got, copies = [], []
+        for _ in range(3):                                   # no host wait between the calls
+            o = m.run_chunks(frames, chunks)
+            copies.append(tuple(x.clone() for x in o))       # queued on the same stream, right behind the call
+            got.append(o)
+            o = m.detect_chunk(frames, 3)
+            copies.append(tuple(x.clone() for x in o))
+            got.append(o)
+        torch.cuda.synchronize()
+        for i, (o, c) in enumerate(zip(got, copies)):
+            ref = ref_plan if i % 2 == 0 else ref_long
+            for a, b, r in zip(o, c, ref):
+                assert torch.equal(a, r), i
+                assert torch.equal(b, r), i
+    finally:
+        m.set_lanes(2)
+        m.set_microbatch(0)
+
+
 def test_all_exits_in_one_pass_matches_each_exit_and_the_oracle():
     """One backbone pass with every exit's units tapped on the way: each exit's block is bit-identical to a
     call at that exit (also across micro-batch sizes), and it matches the oracle's all-exits result."""
