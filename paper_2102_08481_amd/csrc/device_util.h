@@ -16,8 +16,33 @@ __device__ inline float key_score(uint32_t k) {
     return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
-// In-place descending bitonic sort of n2 (power of two) keys by all threads of the block.
-// keys may live in LDS or in global memory; ends with a barrier.
+// n2 (a power of two) keys in LDS, sorted descending by the whole block (a multiple of 64 threads).  A thread owns
+// compare-exchange pair q of a stage: lower element ((q & ~(j-1)) << 1) | (q & (j-1)), partner = lower | j.  The 64 pairs
+// of one wavefront iteration lie within one aligned block of 128 elements for every distance j <= 64, so between two such
+// stages only the wavefront's own LDS traffic has to be ordered; the block barrier is kept around the stages with j >= 128
+// (10 of the 66 stages at 2048 keys) and after the last one.
+__device__ inline void bitonic_sort_desc_lds(uint64_t* keys, int n2) {
+    const int pairs = n2 >> 1, nt = blockDim.x;
+    for (int k = 2; k <= n2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int q = threadIdx.x; q < pairs; q += nt) {
+                const int i = ((q & ~(j - 1)) << 1) | (q & (j - 1)), p = i | j;
+                const uint64_t a = keys[i], b = keys[p];
+                const bool desc = (i & k) == 0;
+                if (desc ? (a < b) : (a > b)) { keys[i] = b; keys[p] = a; }
+            }
+            const int jn = j > 1 ? (j >> 1) : k;   // distance of the stage that follows (k: first stage of the next merge)
+            if (j >= 128 || jn >= 128 || (j == 1 && k == n2)) {
+                __syncthreads();
+            } else {
+                __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+                __builtin_amdgcn_wave_barrier();
+                asm volatile("" ::: "memory");
+            }
+        }
+}
+
+// The same network with a block barrier after every stage: keys may live in LDS or in global memory.
 __device__ inline void bitonic_sort_desc(uint64_t* keys, int n2) {
     for (int k = 2; k <= n2; k <<= 1)
         for (int j = k >> 1; j > 0; j >>= 1) {

@@ -326,7 +326,7 @@ int ensure_workspace(thia_model* m, int H, int W) {
     for (int ep = 1; ep <= m->n_exits; ++ep) ch_max = std::max(ch_max, head_channels(m, ep));
     const size_t o_hf = ap.add((size_t)mb * hf_max * esz), o_rt = ap.add((size_t)mb * hf_max * esz);
     const size_t o_lg = ap.add((size_t)mb * na_max * 4), o_dl = ap.add((size_t)mb * na_max * 16);
-    const int cap = next_pow2(m->pre);
+    const int cap = topk_cand_cap(m->pre);
     const size_t o_hist = ap.add((size_t)mb * 2048 * 4), o_state = ap.add((size_t)mb * 4 * 8), o_cand = ap.add((size_t)mb * cap * 8);
     const size_t o_idx = ap.add((size_t)mb * m->pre * 4), o_pb = ap.add((size_t)mb * m->pre * 16), o_pn = ap.add((size_t)mb * 4);
     const int words = (m->pre + 63) / 64;

@@ -7,11 +7,13 @@
 // -digit-first radix select (digits of 11,11,10,11,11 bits): each pass histograms, with
 // many blocks per frame and integer atomics only, the digit of the elements that still match
 // the prefix, then one block per frame picks the digit holding the k-th element.  A pass
-// ends the search early when the whole digit bucket is needed (always the case after
-// the three logit digits unless logits tie at the cut).  All elements with key >= the
-// threshold are then gathered (any order) and sorted by key in LDS with a bitonic network,
-// which makes the output order deterministic.  The same block decodes the k anchors and
-// compacts the non-empty boxes in order.
+// ends the search as soon as the keys at or above the digit bucket's lower bound fit the
+// candidate list (twice the next power of two of k, at most 4096): with real-valued logits
+// that is after the second digit, and the last three digits only ever run when logits tie
+// at the cut.  All elements with key >= that bound are then gathered (any order) and
+// sorted by key in LDS with a bitonic network, which makes the output order deterministic;
+// the first k are the result.  The same block decodes the k anchors and compacts the
+// non-empty boxes in order.
 //
 // NMS: a k x k upper-triangular overlap bit matrix (64-bit words) is computed by
 // 64-thread blocks, then one wavefront per frame scans it 64 rows at a time from LDS,
@@ -62,9 +64,17 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(const float* __restrict_
     const long i0 = (long)blockIdx.x * HIST_CHUNK;
     const long i1 = i0 + HIST_CHUNK < nA ? i0 + HIST_CHUNK : nA;
     const float* lg = logits + (size_t)f * nA;
-    for (long i = i0 + threadIdx.x; i < i1; i += 256) {
-        const uint64_t key = rank_key(lg[i], (uint32_t)i);
+    auto count = [&](float v, long i) {
+        const uint64_t key = rank_key(v, (uint32_t)i);
         if (pass == 0 || (key >> hi_shift) == (prefix >> hi_shift)) atomicAdd(&lh[(key >> shift) & ((1u << bits) - 1u)], 1u);
+    };
+    if ((nA & 3) == 0) {   // every frame's logits start on a 16-byte boundary: four per load
+        for (long i = i0 + 4 * threadIdx.x; i < i1; i += 4 * 256) {
+            const float4 v = *reinterpret_cast<const float4*>(lg + i);
+            count(v.x, i); count(v.y, i + 1); count(v.z, i + 2); count(v.w, i + 3);
+        }
+    } else {
+        for (long i = i0 + threadIdx.x; i < i1; i += 256) count(lg[i], i);
     }
     __syncthreads();
     for (int i = threadIdx.x; i < HIST_BINS; i += 256)
@@ -72,7 +82,8 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(const float* __restrict_
 }
 
 // One block per frame: find digit d with  #(digit > d) < k_rem <= #(digit >= d); clears the histogram.
-__global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ hist, uint64_t* __restrict__ state, int pass) {
+__global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ hist, uint64_t* __restrict__ state, int pass, int k_want,
+                                                        int cand_cap) {
     const int f = blockIdx.x;
     if (state[4 * f + 2]) return;  // uniform: written only by this block in earlier launches
     __shared__ uint32_t part[256];
@@ -96,39 +107,74 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ h
             const uint64_t digit = (uint64_t)(8 * t + q);
             state[4 * f + 0] |= digit << pass_shift(pass);
             state[4 * f + 1] = (uint64_t)(k_rem - run);
-            if (h[q] == k_rem - run || pass == N_PASS - 1) state[4 * f + 2] = 1ull;
+            // keys at or above the bucket's lower bound: those above the prefix from earlier passes, above the digit, the bucket
+            if ((uint32_t)k_want - k_rem + run + h[q] <= (uint32_t)cand_cap || pass == N_PASS - 1) state[4 * f + 2] = 1ull;
         }
         run += h[q];
     }
 }
 
+// Keys at or above the threshold, in any order.  A block collects its hits in LDS and reserves their places in the frame's
+// list with one atomic (one per element made ~1500 same-address atomics per frame the whole cost of the kernel); hits
+// beyond the block's LDS list, which only a frame of near-equal logits produces, take their places one by one.
+constexpr int GATHER_LDS_KEYS = 1024;
 __global__ __launch_bounds__(256) void topk_gather_kernel(const float* __restrict__ logits, long nA,
                                                           uint64_t* __restrict__ state, uint64_t* __restrict__ cand, int cap) {
+    __shared__ uint64_t s_keys[GATHER_LDS_KEYS];
+    __shared__ uint32_t s_n;
+    __shared__ unsigned long long s_base;
     const int f = blockIdx.y;
     const uint64_t thr = state[4 * f + 0];
     const long i0 = (long)blockIdx.x * HIST_CHUNK;
     const long i1 = i0 + HIST_CHUNK < nA ? i0 + HIST_CHUNK : nA;
     const float* lg = logits + (size_t)f * nA;
-    for (long i = i0 + threadIdx.x; i < i1; i += 256) {
-        const uint64_t key = rank_key(lg[i], (uint32_t)i);
+    unsigned long long* total = reinterpret_cast<unsigned long long*>(&state[4 * f + 3]);
+    if (threadIdx.x == 0) s_n = 0u;
+    __syncthreads();
+    auto take = [&](float v, long i) {
+        const uint64_t key = rank_key(v, (uint32_t)i);
         if (key >= thr) {
-            const unsigned long long slot = atomicAdd(reinterpret_cast<unsigned long long*>(&state[4 * f + 3]), 1ull);
-            if (slot < (unsigned long long)cap) cand[(size_t)f * cap + slot] = key;
+            const uint32_t slot = atomicAdd(&s_n, 1u);
+            if (slot < (uint32_t)GATHER_LDS_KEYS) {
+                s_keys[slot] = key;
+            } else {
+                const unsigned long long g = atomicAdd(total, 1ull);
+                if (g < (unsigned long long)cap) cand[(size_t)f * cap + g] = key;
+            }
         }
+    };
+    if ((nA & 3) == 0) {
+        for (long i = i0 + 4 * threadIdx.x; i < i1; i += 4 * 256) {
+            const float4 v = *reinterpret_cast<const float4*>(lg + i);
+            take(v.x, i); take(v.y, i + 1); take(v.z, i + 2); take(v.w, i + 3);
+        }
+    } else {
+        for (long i = i0 + threadIdx.x; i < i1; i += 256) take(lg[i], i);
     }
+    __syncthreads();
+    const uint32_t mine = s_n < (uint32_t)GATHER_LDS_KEYS ? s_n : (uint32_t)GATHER_LDS_KEYS;
+    if (mine == 0u) return;   // uniform
+    if (threadIdx.x == 0) s_base = atomicAdd(total, (unsigned long long)mine);
+    __syncthreads();
+    const unsigned long long base = s_base;
+    for (uint32_t j = threadIdx.x; j < mine; j += 256)
+        if (base + j < (unsigned long long)cap) cand[(size_t)f * cap + base + j] = s_keys[j];
 }
 
-// Tail shared by the two top-k paths, run by a 1024-thread block for frame f: `keys` (LDS, cap entries, the first k
-// filled, the rest zero) is sorted, indices are emitted, the anchors decoded and clipped, non-empty boxes compacted in order.
-__device__ inline void sort_decode_emit(uint64_t* keys, int k, int cap, int pre, long nA, const float* __restrict__ deltas, int Wk,
-                                        int stride, float imgW, float imgH, const AnchorSpec& anc, int f, int32_t* __restrict__ out_idx,
-                                        float* __restrict__ out_boxes, int32_t* __restrict__ out_n) {
+// Tail shared by the two top-k paths, run by a 1024-thread block for frame f: `keys` (LDS, cap entries, the gathered
+// candidates first, the rest zero) is sorted, the first k emitted as indices, their anchors decoded and clipped, non-empty
+// boxes compacted in order.
+__device__ inline void sort_decode_emit(uint64_t* keys, int got, int k_want, int cap, int pre, long nA, const float* __restrict__ deltas,
+                                        int Wk, int stride, float imgW, float imgH, const AnchorSpec& anc, int f,
+                                        int32_t* __restrict__ out_idx, float* __restrict__ out_boxes, int32_t* __restrict__ out_n) {
     __shared__ int wave_tot[16];
     __shared__ int base_sh;
     const int t = threadIdx.x;
     if (t == 0) base_sh = 0;
     __syncthreads();
-    bitonic_sort_desc(keys, cap);
+    const int k = got < k_want ? got : k_want;
+    // the usual case gathers k or a few more keys: half the list then holds them all, and the network is a stage shorter
+    bitonic_sort_desc_lds(keys, 2 * got <= cap ? cap / 2 : cap);
 
     const int A = anc.n_sizes * anc.n_ratios;
     const float* dl = deltas + (size_t)f * nA * 4;
@@ -174,44 +220,31 @@ __device__ inline void sort_decode_emit(uint64_t* keys, int k, int cap, int pre,
 
 // One block per frame: sort the gathered keys, emit indices, decode, clip, compact non-empty boxes.
 __global__ __launch_bounds__(1024) void topk_sort_decode_kernel(const uint64_t* __restrict__ cand, const uint64_t* __restrict__ state,
-                                                                int cap, int pre, long nA, const float* __restrict__ deltas,
+                                                                int cap, int k_want, int pre, long nA, const float* __restrict__ deltas,
                                                                 int Wk, int stride, float imgW, float imgH, AnchorSpec anc,
                                                                 int32_t* __restrict__ out_idx, float* __restrict__ out_boxes,
                                                                 int32_t* __restrict__ out_n) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     uint64_t* keys = reinterpret_cast<uint64_t*>(smem_raw);  // [cap]
     const int f = blockIdx.x, t = threadIdx.x;
-    int k = (int)state[4 * f + 3];
-    if (k > pre) k = pre;
-    for (int i = t; i < cap; i += 1024) keys[i] = i < k ? cand[(size_t)f * cap + i] : 0ull;
-    sort_decode_emit(keys, k, cap, pre, nA, deltas, Wk, stride, imgW, imgH, anc, f, out_idx, out_boxes, out_n);
+    int got = (int)state[4 * f + 3];
+    if (got > cap) got = cap;
+    for (int i = t; i < cap; i += 1024) keys[i] = i < got ? cand[(size_t)f * cap + i] : 0ull;
+    sort_decode_emit(keys, got, k_want, cap, pre, nA, deltas, Wk, stride, imgW, imgH, anc, f, out_idx, out_boxes, out_n);
 }
 
-// The whole proposal step of one frame in one 1024-thread block (frames with up to a few hundred thousand anchors): the
-// radix select runs its passes back to back with block-level barriers and an LDS histogram, the elements at or above the
-// threshold key are gathered into LDS (keys are unique, so their order there does not matter), then sorted, decoded and
-// emitted as above.  Same keys, same digits, same result as the multi-kernel path; twelve launches become one.
-__global__ __launch_bounds__(1024) void topk_fused_kernel(const float* __restrict__ logits, long nA, int k_want, int cap, int pre,
-                                                          const float* __restrict__ deltas, int Wk, int stride, float imgW, float imgH,
-                                                          AnchorSpec anc, int32_t* __restrict__ out_idx, float* __restrict__ out_boxes,
-                                                          int32_t* __restrict__ out_n) {
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    uint64_t* keys = reinterpret_cast<uint64_t*>(smem_raw);                  // [cap]
-    uint32_t* hist = reinterpret_cast<uint32_t*>(keys + cap);                // [HIST_BINS]
-    __shared__ uint32_t part[256];
-    __shared__ uint32_t above[256];
-    __shared__ uint64_t s_prefix;
-    __shared__ uint32_t s_krem, s_done, s_count;
-    const int f = blockIdx.x, t = threadIdx.x;
-    const float* lg = logits + (size_t)f * nA;
-    if (t == 0) { s_prefix = 0ull; s_krem = (uint32_t)k_want; s_done = 0u; s_count = 0u; }
-    __syncthreads();
-    for (int pass = 0; pass < N_PASS; ++pass) {
-        if (s_done) break;                                                   // uniform: written before the last barrier
+// Radix-select passes first .. N_PASS - 1 of one frame by one 1024-thread block: LDS histogram of the digit of the elements
+// that match the prefix, then the digit holding the k-th element.  prefix / k_rem / done are the block's shared search
+// state (k_rem and prefix as left by the passes before `first`); hist [HIST_BINS], part and above [256] are LDS scratch.
+__device__ inline void block_select_passes(const float* __restrict__ lg, long nA, int first, int k_want, int cand_cap, uint32_t* hist,
+                                           uint32_t* part, uint32_t* above, uint64_t* s_prefix, uint32_t* s_krem, uint32_t* s_done) {
+    const int t = threadIdx.x;
+    for (int pass = first; pass < N_PASS; ++pass) {
+        if (*s_done) break;                                                  // uniform: written before the last barrier
         for (int i = t; i < HIST_BINS; i += 1024) hist[i] = 0u;
         __syncthreads();
         const int shift = pass_shift(pass), bits = pass_bits(pass), hi_shift = shift + bits;
-        const uint64_t prefix = s_prefix;
+        const uint64_t prefix = *s_prefix;
         // (eight loads in flight per thread: with one the block reads at a few GB/s)
         for (long b = 0; b < nA; b += 8 * 1024) {
             float v[8];
@@ -227,7 +260,7 @@ __global__ __launch_bounds__(1024) void topk_fused_kernel(const float* __restric
         __syncthreads();
         // digit d with  #(digit > d) < k_rem <= #(digit >= d)
         uint32_t h[8], sum = 0;
-        const uint32_t k_rem = s_krem;
+        const uint32_t k_rem = *s_krem;
         if (t < 256) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) { h[q] = hist[8 * t + q]; sum += h[q]; }
@@ -243,15 +276,55 @@ __global__ __launch_bounds__(1024) void topk_fused_kernel(const float* __restric
             uint32_t run = above[t];
             for (int q = 7; q >= 0; --q) {
                 if (run < k_rem && k_rem <= run + h[q]) {                    // exactly one (thread, q) satisfies this
-                    s_prefix = prefix | ((uint64_t)(8 * t + q) << shift);
-                    s_krem = k_rem - run;
-                    if (h[q] == k_rem - run || pass == N_PASS - 1) s_done = 1u;
+                    *s_prefix = prefix | ((uint64_t)(8 * t + q) << shift);
+                    *s_krem = k_rem - run;
+                    if ((uint32_t)k_want - k_rem + run + h[q] <= (uint32_t)cand_cap || pass == N_PASS - 1) *s_done = 1u;
                 }
                 run += h[q];
             }
         }
         __syncthreads();
     }
+}
+
+// Multi-kernel path, after the first two digits: one 1024-thread block per frame runs whatever passes the frame still
+// needs (none unless more keys than the candidate list holds share the cut's first two digits, i.e. logits all but tie
+// there; only the elements matching the prefix touch the histogram, so the block is not bound by LDS atomics).
+__global__ __launch_bounds__(1024) void topk_finish_kernel(const float* __restrict__ logits, long nA, uint64_t* __restrict__ state,
+                                                           int k_want, int cand_cap) {
+    const int f = blockIdx.x, t = threadIdx.x;
+    if (state[4 * f + 2]) return;   // uniform
+    __shared__ uint32_t hist[HIST_BINS];
+    __shared__ uint32_t part[256];
+    __shared__ uint32_t above[256];
+    __shared__ uint64_t s_prefix;
+    __shared__ uint32_t s_krem, s_done;
+    if (t == 0) { s_prefix = state[4 * f + 0]; s_krem = (uint32_t)state[4 * f + 1]; s_done = 0u; }
+    __syncthreads();
+    block_select_passes(logits + (size_t)f * nA, nA, 2, k_want, cand_cap, hist, part, above, &s_prefix, &s_krem, &s_done);
+    if (t == 0) { state[4 * f + 0] = s_prefix; state[4 * f + 1] = (uint64_t)s_krem; state[4 * f + 2] = 1ull; }
+}
+
+// The whole proposal step of one frame in one 1024-thread block (frames with up to a few ten thousand anchors): the
+// radix select runs its passes back to back with block-level barriers and an LDS histogram, the elements at or above the
+// threshold key are gathered into LDS (keys are unique, so their order there does not matter), then sorted, decoded and
+// emitted as above.  Same keys, same digits, same result as the multi-kernel path; its launches become one.
+__global__ __launch_bounds__(1024) void topk_fused_kernel(const float* __restrict__ logits, long nA, int k_want, int cap, int pre,
+                                                          const float* __restrict__ deltas, int Wk, int stride, float imgW, float imgH,
+                                                          AnchorSpec anc, int32_t* __restrict__ out_idx, float* __restrict__ out_boxes,
+                                                          int32_t* __restrict__ out_n) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint64_t* keys = reinterpret_cast<uint64_t*>(smem_raw);                  // [cap]
+    uint32_t* hist = reinterpret_cast<uint32_t*>(keys + cap);                // [HIST_BINS]
+    __shared__ uint32_t part[256];
+    __shared__ uint32_t above[256];
+    __shared__ uint64_t s_prefix;
+    __shared__ uint32_t s_krem, s_done, s_count;
+    const int f = blockIdx.x, t = threadIdx.x;
+    const float* lg = logits + (size_t)f * nA;
+    if (t == 0) { s_prefix = 0ull; s_krem = (uint32_t)k_want; s_done = 0u; s_count = 0u; }
+    __syncthreads();
+    block_select_passes(lg, nA, 0, k_want, cap, hist, part, above, &s_prefix, &s_krem, &s_done);
     const uint64_t thr = s_prefix;
     for (int i = t; i < cap; i += 1024) keys[i] = 0ull;
     __syncthreads();
@@ -270,15 +343,9 @@ __global__ __launch_bounds__(1024) void topk_fused_kernel(const float* __restric
         }
     }
     __syncthreads();
-    int k = (int)s_count;
-    if (k > pre) k = pre;
-    sort_decode_emit(keys, k, cap, pre, nA, deltas, Wk, stride, imgW, imgH, anc, f, out_idx, out_boxes, out_n);
-}
-
-static int next_pow2(int v) {
-    int p = 1;
-    while (p < v) p <<= 1;
-    return p;
+    int got = (int)s_count;
+    if (got > cap) got = cap;
+    sort_decode_emit(keys, got, k_want, cap, pre, nA, deltas, Wk, stride, imgW, imgH, anc, f, out_idx, out_boxes, out_n);
 }
 
 hipError_t launch_rpn_proposals(const float* logits, const float* deltas, int n, long nA, int pre, int Wk, int stride,
@@ -286,7 +353,7 @@ hipError_t launch_rpn_proposals(const float* logits, const float* deltas, int n,
                                 float* out_boxes, int32_t* out_n, hipStream_t s) {
     if (n <= 0 || nA <= 0 || nA > (long)IDX_MASK || pre <= 0 || pre > 4096) return hipErrorInvalidValue;
     const int k = (long)pre < nA ? pre : (int)nA;
-    const int cap = next_pow2(pre);
+    const int cap = topk_cand_cap(pre);
     const unsigned bpf = (unsigned)((nA + HIST_CHUNK - 1) / HIST_CHUNK);
     if (n > 65535) return hipErrorInvalidValue;
     if (nA <= FUSED_MAX_ANCHORS) {
@@ -295,12 +362,13 @@ hipError_t launch_rpn_proposals(const float* logits, const float* deltas, int n,
         return hipGetLastError();
     }
     hipLaunchKernelGGL(topk_init_kernel, dim3(n), dim3(256), 0, s, work.hist, work.state, k);
-    for (int pass = 0; pass < N_PASS; ++pass) {
+    for (int pass = 0; pass < 2; ++pass) {   // the two leading digits with many blocks per frame (every element takes part in the first)
         hipLaunchKernelGGL(topk_hist_kernel, dim3(bpf, n), dim3(256), 0, s, logits, nA, pass, work.hist, work.state);
-        hipLaunchKernelGGL(topk_scan_kernel, dim3(n), dim3(256), 0, s, work.hist, work.state, pass);
+        hipLaunchKernelGGL(topk_scan_kernel, dim3(n), dim3(256), 0, s, work.hist, work.state, pass, k, cap);
     }
+    hipLaunchKernelGGL(topk_finish_kernel, dim3(n), dim3(1024), 0, s, logits, nA, work.state, k, cap);
     hipLaunchKernelGGL(topk_gather_kernel, dim3(bpf, n), dim3(256), 0, s, logits, nA, work.state, work.cand, cap);
-    hipLaunchKernelGGL(topk_sort_decode_kernel, dim3(n), dim3(1024), (size_t)cap * 8, s, work.cand, work.state, cap, pre, nA,
+    hipLaunchKernelGGL(topk_sort_decode_kernel, dim3(n), dim3(1024), (size_t)cap * 8, s, work.cand, work.state, cap, k, pre, nA,
                        deltas, Wk, stride, imgW, imgH, anc, out_idx, out_boxes, out_n);
     return hipGetLastError();
 }

@@ -146,10 +146,17 @@ struct AnchorSpec {
     float sizes[8];
     float sqrt_ratios[4];
 };
+// Entries of a frame's candidate list in the top-k of `pre`: the radix select stops as soon as the keys at or above its
+// current bound fit, the list is sorted and its first `pre` entries are the result.
+inline int topk_cand_cap(int pre) {
+    int p = 1;
+    while (p < pre) p <<= 1;
+    return p >= 4096 ? p : 2 * p;
+}
 struct TopkWork {          // device scratch for n frames
     uint32_t* hist;        // [n][2048]
     uint64_t* state;       // [n][4]: prefix key, k remaining, done flag, collected count
-    uint64_t* cand;        // [n][cap_pow2]
+    uint64_t* cand;        // [n][topk_cand_cap(pre)]
 };
 // logits [n,nA]; deltas [n,nA,4]; out_idx [n,pre] (-1 pad); out_boxes [n,pre,4] (0 pad); out_n [n].
 hipError_t launch_rpn_proposals(const float* logits, const float* deltas, int n, long nA, int pre, int Wk, int stride,
