@@ -321,10 +321,11 @@ __global__ __launch_bounds__(1024) void select_classes_kernel(const float* __res
                                                               int32_t* __restrict__ out_labels, int32_t* __restrict__ out_n) {
     extern __shared__ __align__(16) unsigned char sel_smem[];
     const int NC = Kc - 1;
-    uint64_t* keys = reinterpret_cast<uint64_t*>(sel_smem);              // [NC][SELC_MAX_POST]
+    Box* gbox = reinterpret_cast<Box*>(sel_smem);                        // [NC][64] boxes of the group being resolved
+    Box* kbox = gbox + (size_t)NC * 64;                                  // [NC][D] kept boxes (16-byte aligned: read as float4)
+    uint64_t* keys = reinterpret_cast<uint64_t*>(kbox + (size_t)NC * D); // [NC][SELC_MAX_POST]
     uint64_t* kkey = keys + (size_t)NC * SELC_MAX_POST;                  // [NC][D]
-    Box* kbox = reinterpret_cast<Box*>(kkey + (size_t)NC * D);           // [NC][D]
-    int* kcount = reinterpret_cast<int*>(kbox + (size_t)NC * D);         // [NC]
+    int* kcount = reinterpret_cast<int*>(kkey + (size_t)NC * D);         // [NC]
     const int f = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
     int nr = roi_n[f];
     nr = nr < post ? nr : post;
@@ -370,32 +371,56 @@ __global__ __launch_bounds__(1024) void select_classes_kernel(const float* __res
                 bool hit = false;
                 const Box* kb = kbox + (size_t)c * D;
                 int q = 0;
+                auto ld = [&](int k) { const float4 v = *reinterpret_cast<const float4*>(kb + k); return Box{v.x, v.y, v.z, v.w}; };
                 for (; q + 4 <= nk; q += 4) {
-                    const Box b0 = kb[q], b1 = kb[q + 1], b2 = kb[q + 2], b3 = kb[q + 3];
+                    const Box b0 = ld(q), b1 = ld(q + 1), b2 = ld(q + 2), b3 = ld(q + 3);
                     const int h = (int)iou_over(b0, me, nms_thr) | (int)iou_over(b1, me, nms_thr) | (int)iou_over(b2, me, nms_thr) | (int)iou_over(b3, me, nms_thr);
                     hit = hit || h != 0;
                 }
-                for (; q < nk; ++q) hit = hit || iou_over(kb[q], me, nms_thr);
+                for (; q < nk; ++q) hit = hit || iou_over(ld(q), me, nms_thr);
                 alive = alive && !hit;
             }
-            // column b of the group's overlap matrix (which later candidates candidate b suppresses), held by lane b
+            // column b of the group's overlap matrix (which later candidates candidate b suppresses), held by lane b.
+            // Every lane walks the group's boxes in LDS (all lanes read the same address: a broadcast) and tests its own
+            // box against them; broadcasting box b through scalar registers and collecting a ballot per b instead made
+            // each of the 64 steps a chain of dependent scalar and vector instructions.
             uint64_t col = 0ull;
             const int live = (nc - s0) < 64 ? (nc - s0) : 64;   // candidates in this group
-            for (int b = 0; b < live; ++b) {   // b is wavefront-uniform: the box is broadcast through scalar registers
-                const Box kb = {__uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(me.x1), b)),
-                                __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(me.y1), b)),
-                                __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(me.x2), b)),
-                                __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(me.y2), b))};
-                const uint64_t m = __ballot(lane > b && i < nc && iou_over(kb, me, nms_thr));
-                if (lane == b) col = m;
+            Box* gb = gbox + (size_t)c * 64;
+            gb[lane] = me;
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+            if (i < nc) {
+                // four boxes per step, loaded together and tested independently (slots past `live` hold zero boxes: no overlap)
+                uint32_t word[2] = {0u, 0u};
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    if (32 * h >= live) break;   // uniform
+                    uint32_t w = 0u;
+#pragma unroll 2
+                    for (int j0 = 0; j0 < 32; j0 += 4) {
+                        float4 q[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const float4*>(gb + 32 * h + j0 + u);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int j = 32 * h + j0 + u;
+                            const Box o = {q[u].x, q[u].y, q[u].z, q[u].w};
+                            w |= (j > lane && iou_over(me, o, nms_thr)) ? (1u << (j0 + u)) : 0u;
+                        }
+                    }
+                    word[h] = w;
+                }
+                col = (uint64_t)word[0] | ((uint64_t)word[1] << 32);
             }
             uint64_t dead = ~__ballot(alive);
             uint64_t kept = 0ull;
             const uint32_t clo = (uint32_t)col, chi = (uint32_t)(col >> 32);
-            for (int b = 0; b < 64; ++b) {
-                if ((dead >> b) & 1ull) continue;
+            for (uint64_t avail = ~dead; avail != 0ull;) {   // from one kept candidate to the next: suppressed ones are not visited
+                const int b = __builtin_ctzll(avail);
                 kept |= 1ull << b;
-                dead |= (uint64_t)(uint32_t)__builtin_amdgcn_readlane(clo, b) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(chi, b) << 32);
+                const uint64_t d = (uint64_t)(uint32_t)__builtin_amdgcn_readlane(clo, b) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(chi, b) << 32);
+                avail &= ~d & ~((2ull << b) - 1ull);
             }
             if ((kept >> lane) & 1ull) {
                 const int pos = nk + __popcll(kept & ((1ull << lane) - 1ull));
@@ -448,10 +473,10 @@ hipError_t launch_select(const float* scores, const float* boxes, const int32_t*
     if (n <= 0 || D <= 0 || D > SEL_MAX_D || key_cap < post * Kc) return hipErrorInvalidValue;
     if (post <= SELC_MAX_POST && Kc >= 2 && Kc - 1 <= SELC_MAX_CLASSES && D <= SELC_MAX_D) {
         const int NC = Kc - 1;
-        const size_t lds = (size_t)NC * SELC_MAX_POST * 8 + (size_t)NC * D * (8 + sizeof(Box)) + (size_t)NC * 4;
+        const size_t lds = (size_t)NC * 64 * sizeof(Box) + (size_t)NC * SELC_MAX_POST * 8 + (size_t)NC * D * (8 + sizeof(Box)) + (size_t)NC * 4;
         {
-            const size_t lds_max = (size_t)SELC_MAX_CLASSES * SELC_MAX_POST * 8 + (size_t)SELC_MAX_CLASSES * SELC_MAX_D * (8 + sizeof(Box)) +
-                                   (size_t)SELC_MAX_CLASSES * 4;
+            const size_t lds_max = (size_t)SELC_MAX_CLASSES * 64 * sizeof(Box) + (size_t)SELC_MAX_CLASSES * SELC_MAX_POST * 8 +
+                                   (size_t)SELC_MAX_CLASSES * SELC_MAX_D * (8 + sizeof(Box)) + (size_t)SELC_MAX_CLASSES * 4;
             hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(select_classes_kernel), lds_max);
             if (e != hipSuccess) return e;
         }

@@ -420,8 +420,9 @@ __global__ __launch_bounds__(256) void nms_reduce_kernel(const uint64_t* __restr
     const int wc = (cnt + 63) / 64;
     const uint64_t* mf = mask + (size_t)f * cap * words;
     const int per_thread = (64 * words + 255) / 256;   // <= 16 for words <= 64
-    uint64_t stage[16];
-    auto fetch = [&](int c) {
+    // two tiles ahead: a tile's words are requested while the tile before the previous one is resolved
+    uint64_t stage_a[16], stage_b[16];
+    auto fetch = [&](int c, uint64_t (&stage)[16]) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             if (q >= per_thread) break;
@@ -431,7 +432,7 @@ __global__ __launch_bounds__(256) void nms_reduce_kernel(const uint64_t* __restr
             stage[q] = v;
         }
     };
-    auto stash = [&]() {
+    auto stash = [&](const uint64_t (&stage)[16]) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             if (q >= per_thread) break;
@@ -442,43 +443,49 @@ __global__ __launch_bounds__(256) void nms_reduce_kernel(const uint64_t* __restr
     if (t == 0) s_nk = -1;    // becomes the final count as soon as max_keep boxes are kept (early exit for all wavefronts)
     uint64_t removed = 0ull;  // wavefront 0: lane w holds word w
     int nk = 0;
-    if (wc > 0) fetch(0);
+    if (wc > 0) fetch(0, stage_a);
+    if (wc > 1) fetch(1, stage_b);
     __syncthreads();
-    for (int c = 0; c < wc; ++c) {
-        stash();
+    // one tile: returns true once max_keep boxes are kept
+    auto step = [&](int c, uint64_t (&stage)[16]) {
+        stash(stage);
         __syncthreads();
-        if (c + 1 < wc) fetch(c + 1);
+        if (c + 2 < wc) fetch(c + 2, stage);
         if (wv == 0) {
             const int rows = (cnt - 64 * c) < 64 ? (cnt - 64 * c) : 64;
             const uint64_t diag = lane < rows ? tile[(size_t)lane * words + c] : 0ull;
             const uint32_t dlo = (uint32_t)diag, dhi = (uint32_t)(diag >> 32);
             const uint32_t rlo = (uint32_t)removed, rhi = (uint32_t)(removed >> 32);
             uint64_t cur = (uint64_t)(uint32_t)__builtin_amdgcn_readlane(rlo, c) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(rhi, c) << 32);
-            // serial greedy chain over the tile's rows, registers and scalars only
+            // serial greedy chain over the tile's rows, registers and scalars only.  It steps from one kept row to the next
+            // (lowest row not yet suppressed): with one wavefront on the SIMD every dependent instruction pays its full
+            // latency, ~120 cycles per step, so stepping over suppressed rows one by one was most of the kernel.
             uint64_t kept = 0ull;
             int room = max_keep - nk;
-            for (int b = 0; b < rows && room > 0; ++b) {
-                if ((cur >> b) & 1ull) continue;
+            uint64_t avail = ~cur & (rows < 64 ? (1ull << rows) - 1ull : ~0ull);
+            while (avail != 0ull && room > 0) {
+                const int b = __builtin_ctzll(avail);
                 kept |= 1ull << b;
                 --room;
-                cur |= (uint64_t)(uint32_t)__builtin_amdgcn_readlane(dlo, b) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(dhi, b) << 32);
+                const uint64_t d = (uint64_t)(uint32_t)__builtin_amdgcn_readlane(dlo, b) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(dhi, b) << 32);
+                avail &= ~d & ~((2ull << b) - 1ull);   // rows b suppresses, and rows up to b, are decided
             }
             // kept rows -> keep list (lane b writes its own slot) and OR of their mask rows into the removed set
             if ((kept >> lane) & 1ull) keep[nk + __popcll(kept & ((1ull << lane) - 1ull))] = 64 * c + lane;
             nk += __popcll(kept);
             if (nk < max_keep && lane < words) {
                 uint64_t acc = 0ull;
-#pragma unroll 8
-                for (int b = 0; b < 64; ++b) {
-                    const uint64_t row = tile[(size_t)b * words + lane];
-                    acc |= ((kept >> b) & 1ull) ? row : 0ull;
-                }
+                for (uint64_t k = kept; k != 0ull; k &= k - 1ull) acc |= tile[(size_t)__builtin_ctzll(k) * words + lane];   // kept rows only
                 removed |= acc;
             }
             if (nk == max_keep && lane == 0) s_nk = nk;
         }
         __syncthreads();
-        if (s_nk >= 0) break;   // uniform: written before the barrier
+        return s_nk >= 0;   // uniform: written before the barrier
+    };
+    for (int c = 0; c < wc; c += 2) {
+        if (step(c, stage_a)) break;
+        if (c + 1 < wc && step(c + 1, stage_b)) break;
     }
     if (t == 0 && s_nk < 0) s_nk = nk;
     __syncthreads();
