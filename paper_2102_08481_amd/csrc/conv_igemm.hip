@@ -173,6 +173,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     // staged path: the thread's chunk of the row; direct path: the chunk whose LDS slot is t % CPR (see DIRECT above;
     // row & 7 = lane / 8 and (row >> 3) & 1 = wavefront & 1 for every row lrow + RPP * p of this thread)
     const int lchunk = DIRECT ? ((t % CPR) ^ ((lane >> 3) ^ (wv & 1))) & 7 : t % CPR;
+    // weight rows first: they need no pixel arithmetic, and on the direct path the first K tile's weight requests go out
+    // before the (division-heavy) pixel coordinates are worked out
+    size_t a_base[PA];
+    bool a_ok[PA];
+#pragma unroll
+    for (int p = 0; p < PA; ++p) {
+        const int n = n0 + lrow + RPP * p;
+        a_ok[p] = n < a.Cout;
+        a_base[p] = (size_t)(a_ok[p] ? n : 0) * K + (size_t)lchunk * EPC;
+    }
+    if constexpr (DIRECT) {
+        unsigned char* dA0 = sA + (size_t)((wv * 64) / CPR) * LDS_ROW;
+#pragma unroll
+        for (int p = 0; p < PA; ++p) load_to_lds16(wgt + a_base[p], dA0 + (size_t)(RPP * p) * LDS_ROW);
+    }
     size_t b_base[PB];
     size_t b_base2[DUAL ? PB : 1];
     const T* __restrict__ in2 = static_cast<const T*>(a.in2);
@@ -181,13 +196,36 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
     long long b_off0[ONE ? 1 : PB];
     uint32_t b_taps[ONE ? 1 : PB];
     bool b_ok[PB];
+    // (image, row, column) of the thread's first tile row by division; its other rows are RPP pixels further on each and
+    // are reached by stepping (a few carries) unless the output rows are very short
+    int s_img, s_oy, s_ox;
+    {
+        const int m = m0 + lrow;
+        const int mm = m < M ? m : 0;
+        s_img = mm / HoWo;
+        const int rem = mm - s_img * HoWo;
+        s_oy = rem / a.Wo;
+        s_ox = rem - s_oy * a.Wo;
+    }
+    const bool step_rows = a.Wo >= 16;
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
         const int m = m0 + lrow + RPP * p;
         b_ok[p] = m < M;
-        const int mm = b_ok[p] ? m : 0;
-        const int img = mm / HoWo, rem = mm - img * HoWo;
-        const int oy = rem / a.Wo, ox = rem - oy * a.Wo;
+        int img, oy, ox;
+        if (p == 0 || !b_ok[p]) {   // (rows beyond M are clamped to row 0: they only feed outputs that are never stored)
+            img = b_ok[p] ? s_img : 0; oy = b_ok[p] ? s_oy : 0; ox = b_ok[p] ? s_ox : 0;
+        } else if (step_rows) {
+            s_ox += RPP;
+            while (s_ox >= a.Wo) { s_ox -= a.Wo; ++s_oy; }
+            while (s_oy >= a.Ho) { s_oy -= a.Ho; ++s_img; }
+            img = s_img; oy = s_oy; ox = s_ox;
+        } else {
+            img = m / HoWo;
+            const int rem = m - img * HoWo;
+            oy = rem / a.Wo;
+            ox = rem - oy * a.Wo;
+        }
         const int iy0 = oy * a.stride - a.pad, ix0 = ox * a.stride - a.pad;
         b_base[p] = (size_t)img * a.H * a.W * a.Cin + (size_t)lchunk * EPC;
         // 1x1, unpadded: the row's input pixel is fixed for the whole K loop
@@ -195,22 +233,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
             b_base[p] += ((size_t)iy0 * a.W + ix0) * a.Cin;
         } else {
             b_off0[p] = (long long)b_base[p] + ((long long)iy0 * a.W + ix0) * a.Cin;
+            // tap (ky, kx) lies inside the image iff row iy0 + ky and column ix0 + kx do
+            uint32_t cols = 0;
+            for (int kx = 0; kx < a.kw; ++kx) cols |= ((unsigned)(ix0 + kx) < (unsigned)a.W) ? (1u << kx) : 0u;
             uint32_t bits = 0;
-            for (int ky = 0; ky < a.kh; ++ky)
-                for (int kx = 0; kx < a.kw; ++kx)
-                    if ((unsigned)(iy0 + ky) < (unsigned)a.H && (unsigned)(ix0 + kx) < (unsigned)a.W) bits |= 1u << (ky * a.kw + kx);
+            for (int ky = 0; ky < a.kh; ++ky) bits |= ((unsigned)(iy0 + ky) < (unsigned)a.H) ? (cols << (ky * a.kw)) : 0u;
             b_taps[p] = bits;
         }
         if constexpr (DUAL)
             b_base2[p] = (((size_t)img * a.H2 + (size_t)oy * a.stride2) * a.W2 + (size_t)ox * a.stride2) * a.Cin2 + (size_t)lchunk * EPC;
-    }
-    size_t a_base[PA];
-    bool a_ok[PA];
-#pragma unroll
-    for (int p = 0; p < PA; ++p) {
-        const int n = n0 + lrow + RPP * p;
-        a_ok[p] = n < a.Cout;
-        a_base[p] = (size_t)(a_ok[p] ? n : 0) * K + (size_t)lchunk * EPC;
     }
     const int cin_tiles = a.Cin / BK;
     const int KT = K / BK;
@@ -294,6 +325,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_kernel(cons
                 load_to_lds16(src, dB + (size_t)(RPP * p) * LDS_ROW);
             }
         }
+        if (kt == 0) return;   // the first tile's weight rows were requested at the top of the kernel
 #pragma unroll
         for (int p = 0; p < PA; ++p)
             load_to_lds16(wgt + a_base[p] + (size_t)kt * BK, dA + (size_t)(RPP * p) * LDS_ROW);
